@@ -1,0 +1,320 @@
+"""CPU oracle for the operator-split linear layer (arXiv 2209.13258, Section 3.3).
+
+TEST INFRASTRUCTURE ONLY: imported by tests, the smoke check and the bench's
+cpu_baseline leg.  The GPU package never imports this module and this module
+never imports the GPU package.
+
+The arithmetic lives in ``osdp_oracle.c`` (plain C, fp64, textbook loops);
+this file builds it with gcc and marshals numpy arrays into it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "osdp_oracle.c"
+_LIB = _HERE / "libosdp_oracle.so"
+_lib = None
+
+_i64 = ctypes.c_int64
+_p = ctypes.c_void_p
+
+
+def build(force: bool = False) -> Path:
+    """Compile the C oracle into ``oracle/libosdp_oracle.so`` with gcc."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(f".so.tmp{os.getpid()}")
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-fvisibility=hidden",
+               "-std=c11", "-Wall", "-Wextra", "-o", str(tmp), str(_SRC)]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(str(_LIB))
+        lib.osdp_oracle_bf16_to_f64.restype = ctypes.c_double
+        lib.osdp_oracle_bf16_to_f64.argtypes = [ctypes.c_uint16]
+        lib.osdp_oracle_threads.restype = ctypes.c_int
+        lib.osdp_oracle_weight_bytes.restype = _i64
+        lib.osdp_oracle_weight_bytes.argtypes = [_i64] * 3
+        lib.osdp_oracle_slice_range.restype = None
+        lib.osdp_oracle_slice_range.argtypes = [_i64, _i64, _i64, _p, _p]
+        lib.osdp_oracle_peak_staging_bytes.restype = _i64
+        lib.osdp_oracle_peak_staging_bytes.argtypes = [_i64] * 5
+        lib.osdp_oracle_shard_len.restype = _i64
+        lib.osdp_oracle_shard_len.argtypes = [_i64] * 3
+        lib.osdp_oracle_locate.restype = None
+        lib.osdp_oracle_locate.argtypes = [_i64] * 5 + [_p, _p]
+        lib.osdp_oracle_assemble.restype = None
+        lib.osdp_oracle_assemble.argtypes = [_i64] * 3 + [_p, _p]
+        lib.osdp_oracle_shard.restype = None
+        lib.osdp_oracle_shard.argtypes = [_i64] * 3 + [_p, _p]
+        lib.osdp_oracle_gather_slice.restype = None
+        lib.osdp_oracle_gather_slice.argtypes = [_i64] * 5 + [_p, _p]
+        lib.osdp_oracle_matmul_fwd.restype = None
+        lib.osdp_oracle_matmul_fwd.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _p]
+        lib.osdp_oracle_matmul_dx.restype = None
+        lib.osdp_oracle_matmul_dx.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _p]
+        lib.osdp_oracle_matmul_dw.restype = None
+        lib.osdp_oracle_matmul_dw.argtypes = [_i64, _i64, _i64, _p, _i64, _p, _i64, _p]
+        lib.osdp_oracle_linear.restype = ctypes.c_int
+        lib.osdp_oracle_linear.argtypes = [_i64] * 4 + [_p] * 6
+        lib.osdp_oracle_split_fwd.restype = ctypes.c_int
+        lib.osdp_oracle_split_fwd.argtypes = [_i64] * 5 + [_p] * 4
+        lib.osdp_oracle_split_bwd.restype = ctypes.c_int
+        lib.osdp_oracle_split_bwd.argtypes = [_i64] * 5 + [_p] * 6
+        lib.osdp_oracle_sample_y.restype = None
+        lib.osdp_oracle_sample_y.argtypes = [_i64] * 4 + [_p, _p, _i64, _p, _p, _p]
+        lib.osdp_oracle_sample_dx.restype = None
+        lib.osdp_oracle_sample_dx.argtypes = [_i64] * 4 + [_p, _p, _i64, _p, _p, _p]
+        lib.osdp_oracle_sample_dw.restype = None
+        lib.osdp_oracle_sample_dw.argtypes = [_i64] * 3 + [_p, _p, _i64, _p, _p, _p]
+        _lib = lib
+    return _lib
+
+
+# ---------------------------------------------------------------- marshalling
+def _u16(a, shape=None) -> np.ndarray:
+    a = np.ascontiguousarray(a, dtype=np.uint16)
+    if shape is not None and a.shape != tuple(shape):
+        raise ValueError(f"expected shape {tuple(shape)}, got {a.shape}")
+    return a
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _ptr_array(arrs):
+    return (ctypes.c_void_p * len(arrs))(*[a.ctypes.data for a in arrs])
+
+
+def _check_shards(shards, I, O, N):
+    L = shard_len(I, O, N)
+    if len(shards) != N:
+        raise ValueError(f"expected {N} shards, got {len(shards)}")
+    out = [_u16(s).reshape(-1) for s in shards]
+    for s in out:
+        if s.size != L:
+            raise ValueError(f"each shard must hold {L} elements, got {s.size}")
+    return out
+
+
+# ------------------------------------------------------------------ scalars
+def threads() -> int:
+    """Number of host threads the oracle's loops run on."""
+    return int(_load().osdp_oracle_threads())
+
+
+def bf16_to_f64(bits) -> np.ndarray:
+    """Widen bf16 bit patterns exactly to float64 (scalar loop through the C routine)."""
+    lib = _load()
+    bits = np.asarray(bits, dtype=np.uint16)
+    flat = [lib.osdp_oracle_bf16_to_f64(int(b)) for b in bits.reshape(-1)]
+    return np.array(flat, dtype=np.float64).reshape(bits.shape)
+
+
+def weight_bytes(I: int, O: int, elem_bytes: int) -> int:
+    """Gathered size of one MatMul's weight (Section 3.3)."""
+    return int(_load().osdp_oracle_weight_bytes(I, O, elem_bytes))
+
+
+def slice_range(O: int, k: int, j: int):
+    """Column range [c0, c1) of slice j of k (k = 0 means unsplit)."""
+    c0, c1 = _i64(), _i64()
+    _load().osdp_oracle_slice_range(O, k, j, ctypes.byref(c0), ctypes.byref(c1))
+    return int(c0.value), int(c1.value)
+
+
+def peak_staging_bytes(I: int, O: int, k: int, slots: int = 1, elem_bytes: int = 2) -> int:
+    """Peak gathered-weight bytes with ``slots`` slices live (Section 3.3 law for slots=1)."""
+    return int(_load().osdp_oracle_peak_staging_bytes(I, O, k, slots, elem_bytes))
+
+
+def shard_len(I: int, O: int, N: int) -> int:
+    return int(_load().osdp_oracle_shard_len(I, O, N))
+
+
+def locate(I: int, O: int, N: int, r: int, c: int):
+    """(shard, offset) of W[r, c] in the shard-major layout."""
+    s, off = _i64(), _i64()
+    _load().osdp_oracle_locate(I, O, N, r, c, ctypes.byref(s), ctypes.byref(off))
+    return int(s.value), int(off.value)
+
+
+# ------------------------------------------------------------------- layout
+def shard(W, N: int):
+    """Cut dense W[I x O] (bf16 bits) into N shards of ceil(I*O/N) elements."""
+    W = _u16(W)
+    I, O = W.shape
+    L = shard_len(I, O, N)
+    shards = [np.empty(L, dtype=np.uint16) for _ in range(N)]
+    _load().osdp_oracle_shard(I, O, N, _ptr(W), _ptr_array(shards))
+    return shards
+
+
+def assemble(shards, I: int, O: int):
+    """Dense W[I x O] from its shards."""
+    N = len(shards)
+    sh = _check_shards(shards, I, O, N)
+    W = np.empty((I, O), dtype=np.uint16)
+    _load().osdp_oracle_assemble(I, O, N, _ptr_array(sh), _ptr(W))
+    return W
+
+
+def gather_slice(shards, I: int, O: int, k: int, j: int):
+    """Column slice j of k, dense row-major [I x w_j] bf16 bits."""
+    N = len(shards)
+    sh = _check_shards(shards, I, O, N)
+    c0, c1 = slice_range(O, k, j)
+    Ws = np.empty((I, c1 - c0), dtype=np.uint16)
+    _load().osdp_oracle_gather_slice(I, O, N, k, j, _ptr_array(sh), _ptr(Ws))
+    return Ws
+
+
+# --------------------------------------------------------- definition route
+def matmul_fwd(X, W):
+    X, W = _u16(X), _u16(W)
+    T, I = X.shape
+    I2, O = W.shape
+    assert I == I2
+    Y = np.empty((T, O), dtype=np.float64)
+    _load().osdp_oracle_matmul_fwd(T, I, O, _ptr(X), I, _ptr(W), O, _ptr(Y))
+    return Y
+
+
+def matmul_dx(dY, W):
+    dY, W = _u16(dY), _u16(W)
+    T, O = dY.shape
+    I, O2 = W.shape
+    assert O == O2
+    dX = np.empty((T, I), dtype=np.float64)
+    _load().osdp_oracle_matmul_dx(T, I, O, _ptr(dY), O, _ptr(W), O, _ptr(dX))
+    return dX
+
+
+def matmul_dw(X, dY):
+    X, dY = _u16(X), _u16(dY)
+    T, I = X.shape
+    T2, O = dY.shape
+    assert T == T2
+    dW = np.empty((I, O), dtype=np.float64)
+    _load().osdp_oracle_matmul_dw(T, I, O, _ptr(X), I, _ptr(dY), O, _ptr(dW))
+    return dW
+
+
+def linear(X, shards, O: int, dY=None, want=("Y", "dX", "dW")):
+    """Unsplit operator from shards: dict with fp64 Y [T x O], dX [T x I], dW [I x O]."""
+    X = _u16(X)
+    T, I = X.shape
+    N = len(shards)
+    sh = _check_shards(shards, I, O, N)
+    out = {}
+    Y = np.empty((T, O)) if "Y" in want else None
+    dX = np.empty((T, I)) if "dX" in want else None
+    dW = np.empty((I, O)) if "dW" in want else None
+    if (dX is not None or dW is not None):
+        dY = _u16(dY, (T, O))
+    rc = _load().osdp_oracle_linear(
+        T, I, O, N, _ptr(X), _ptr(dY) if dY is not None else None, _ptr_array(sh),
+        _ptr(Y) if Y is not None else None, _ptr(dX) if dX is not None else None,
+        _ptr(dW) if dW is not None else None)
+    if rc != 0:
+        raise MemoryError("oracle allocation failed")
+    if Y is not None:
+        out["Y"] = Y
+    if dX is not None:
+        out["dX"] = dX
+    if dW is not None:
+        out["dW"] = dW
+    return out
+
+
+# -------------------------------------------------------------- split route
+def split_fwd(X, shards, O: int, k: int):
+    """Split forward: returns (Y fp64 [T x O], peak live staging bytes)."""
+    X = _u16(X)
+    T, I = X.shape
+    N = len(shards)
+    sh = _check_shards(shards, I, O, N)
+    Y = np.empty((T, O), dtype=np.float64)
+    peak = _i64()
+    rc = _load().osdp_oracle_split_fwd(T, I, O, N, k, _ptr(X), _ptr_array(sh), _ptr(Y),
+                                       ctypes.byref(peak))
+    if rc != 0:
+        raise MemoryError("oracle allocation failed")
+    return Y, int(peak.value)
+
+
+def split_bwd(X, dY, shards, O: int, k: int):
+    """Split backward: returns (dX fp64 [T x I], dW shards (list of N fp64 arrays), peak bytes)."""
+    X = _u16(X)
+    T, I = X.shape
+    dY = _u16(dY, (T, O))
+    N = len(shards)
+    sh = _check_shards(shards, I, O, N)
+    L = shard_len(I, O, N)
+    dX = np.empty((T, I), dtype=np.float64)
+    dW = [np.zeros(L, dtype=np.float64) for _ in range(N)]
+    peak = _i64()
+    rc = _load().osdp_oracle_split_bwd(T, I, O, N, k, _ptr(X), _ptr(dY), _ptr_array(sh), _ptr(dX),
+                                       _ptr_array(dW), ctypes.byref(peak))
+    if rc != 0:
+        raise MemoryError("oracle allocation failed")
+    return dX, dW, int(peak.value)
+
+
+def dense_from_f64_shards(dW_shards, I: int, O: int):
+    """Dense [I x O] fp64 view of a shard-major fp64 gradient (drops the padding)."""
+    flat = np.concatenate([np.asarray(s, dtype=np.float64).reshape(-1) for s in dW_shards])
+    return flat[: I * O].reshape(I, O)
+
+
+# ------------------------------------------------------------ sampled entries
+def _idx(a):
+    return np.ascontiguousarray(a, dtype=np.int64)
+
+
+def sample_y(X, shards, O: int, rows, cols):
+    X = _u16(X)
+    T, I = X.shape
+    N = len(shards)
+    sh = _check_shards(shards, I, O, N)
+    rows, cols = _idx(rows), _idx(cols)
+    out = np.empty(rows.size, dtype=np.float64)
+    _load().osdp_oracle_sample_y(T, I, O, N, _ptr(X), _ptr_array(sh), rows.size, _ptr(rows),
+                                 _ptr(cols), _ptr(out))
+    return out
+
+
+def sample_dx(dY, shards, I: int, rows, cols):
+    dY = _u16(dY)
+    T, O = dY.shape
+    N = len(shards)
+    sh = _check_shards(shards, I, O, N)
+    rows, cols = _idx(rows), _idx(cols)
+    out = np.empty(rows.size, dtype=np.float64)
+    _load().osdp_oracle_sample_dx(T, I, O, N, _ptr(dY), _ptr_array(sh), rows.size, _ptr(rows),
+                                  _ptr(cols), _ptr(out))
+    return out
+
+
+def sample_dw(X, dY, rows, cols):
+    X, dY = _u16(X), _u16(dY)
+    T, I = X.shape
+    T2, O = dY.shape
+    assert T == T2
+    rows, cols = _idx(rows), _idx(cols)
+    out = np.empty(rows.size, dtype=np.float64)
+    _load().osdp_oracle_sample_dw(T, I, O, _ptr(X), _ptr(dY), rows.size, _ptr(rows), _ptr(cols),
+                                  _ptr(out))
+    return out
