@@ -1,0 +1,220 @@
+#!/usr/bin/env python3
+"""Benchmark of the operator-split linear layer (libosdp) on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+for every operator of the workload, the split forward (gather slice j, slice
+GEMM) and then, in reverse operator order, the split backward (gather again,
+dW slice GEMM, dX accumulate GEMM).  Inputs are resident in HBM before the
+timed region starts.
+
+Prints one JSON line: whole-job TFLOP/s (6*T*I*O flops per operator), the
+roofline of the dominant kernel measured with HIP events inside this run, and
+the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (vendor figure: 256 CUs x 2.4 GHz x 4096 flop/clk/CU)
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="workload: index into BASELINE.json configs (1-based)")
+    ap.add_argument("--k", type=int, default=None, help="slice granularity (default: the workload's own)")
+    ap.add_argument("--staging", choices=["auto", "single", "double", "half"], default="auto")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the k sweep and the extra workload")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--serial", action="store_true", help="one stream: no gather/GEMM overlap")
+    return ap.parse_args()
+
+
+class Stack:
+    """All operators of a workload resident on the GPU, with one shared workspace."""
+
+    def __init__(self, w, staging, torch, osdp, seed=0):
+        self.w, self.torch, self.osdp = w, torch, osdp
+        g = torch.Generator(device="cuda")
+        g.manual_seed(220913258 + seed)
+        bf = torch.bfloat16
+        self.ops = []
+        for layer in range(w.layers):
+            for n, op in enumerate(w.ops):
+                L = -(-(op.I * op.O) // w.N)
+                d = dict(
+                    n=n, op=op,
+                    X=torch.randn((w.T, op.I), generator=g, device="cuda", dtype=torch.float32).to(bf),
+                    dY=torch.randn((w.T, op.O), generator=g, device="cuda", dtype=torch.float32).to(bf),
+                    W=[(torch.randn((L,), generator=g, device="cuda", dtype=torch.float32) * 0.02).to(bf) for _ in range(w.N)],
+                    Y=torch.empty((w.T, op.O), device="cuda", dtype=bf),
+                    dX=torch.empty((w.T, op.I), device="cuda", dtype=bf),
+                    dW=[torch.empty((L,), device="cuda", dtype=bf) for _ in range(w.N)],
+                )
+                self.ops.append(d)
+        self.plan = osdp.Plan([op.k for op in w.ops], staging=staging)
+        need, self.peak_staging = 0, 0
+        for n, op in enumerate(w.ops):
+            tot, peak = osdp.osdp_split_linear_workspace_bytes(w.T, op.I, op.O, w.N, 0, True, self.plan, n)
+            need, self.peak_staging = max(need, tot), max(self.peak_staging, peak)
+        self.workspace_bytes = need
+        self.ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+        self.sc, self.sp = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def step(self, serial=False):
+        osdp, sp = self.osdp, (None if serial else self.sp)
+        for d in self.ops:
+            osdp.osdp_split_linear_fwd(d["X"], d["W"], d["Y"], 0, self.ws, plan=self.plan, op_index=d["n"],
+                                       stream_compute=self.sc, stream_copy=sp)
+        for d in reversed(self.ops):
+            osdp.osdp_split_linear_bwd(d["X"], d["dY"], d["W"], d["dX"], d["dW"], 0, self.ws, plan=self.plan,
+                                       op_index=d["n"], stream_compute=self.sc, stream_copy=sp)
+
+    def run(self, steps, warmup, serial=False, profile=False):
+        """Returns (ms per step, per-kernel stats or None)."""
+        torch, osdp = self.torch, self.osdp
+        with torch.cuda.stream(self.sc):
+            for _ in range(warmup):
+                self.step(serial)
+            torch.cuda.synchronize()
+            if profile:
+                osdp.osdp_profile_begin(1 << 20)
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                self.step(serial)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            stats = osdp.osdp_profile_end() if profile else None
+        return (t1 - t0) * 1e3 / steps, stats
+
+
+def kernel_table(stats):
+    out = {}
+    for name, s in stats.items():
+        if not s["launches"]:
+            continue
+        avg_ms = s["ms"] / s["launches"]
+        e = dict(launches=s["launches"], avg_us=round(avg_ms * 1e3, 2), total_ms=round(s["ms"], 3))
+        if s["flops"]:
+            e["tflops"] = round(s["flops"] / (s["ms"] * 1e-3) / 1e12, 2)
+            e["frac_mfma_peak"] = round(e["tflops"] / PEAK_BF16_TFLOPS, 4)
+        e["gbs_algorithmic"] = round(s["bytes"] / (s["ms"] * 1e-3) / 1e9, 1)
+        out[name] = e
+    return out
+
+
+def cpu_baseline(w, target_s=15.0):
+    """The oracle's split route on a token sub-sample of the same workload, all host threads."""
+    import numpy as np
+    import oracle
+    import workloads as wl
+
+    def one_pass(Ts):
+        fl, t = 0, 0.0
+        for n, op in enumerate(w.ops):
+            d = wl.operator_inputs(w.cfg, 0, n, Ts, op.I, op.O, w.N)
+            t0 = time.perf_counter()
+            oracle.split_fwd(d["X"], d["W_shards"], op.O, op.k)
+            oracle.split_bwd(d["X"], d["dY"], d["W_shards"], op.O, op.k)
+            t += time.perf_counter() - t0
+            fl += 6 * Ts * op.I * op.O
+        return fl, t
+
+    oracle.build()
+    fl, t = one_pass(16)                      # calibration pass
+    rate = fl / max(t, 1e-9)
+    per_token = sum(6 * op.I * op.O for op in w.ops)
+    Ts = int(min(w.T, max(16, target_s * rate / per_token)))
+    Ts = max(16, Ts // 16 * 16)
+    fl, t = one_pass(Ts)
+    return {"value": round(fl / t / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"first layer of the workload with T'={Ts} of {w.T} tokens (flops are linear in T), "
+                      f"split route fwd+bwd, {t:.1f} s of CPU work"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build covers one GPU's share of the step; --gpus must be 1 "
+              "(no collectives or cross-GPU sharding are part of it)", file=sys.stderr)
+        return 2
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    import paper_2209_13258_amd as osdp
+    import workloads as wl
+
+    staging = {"auto": osdp.OSDP_STAGING_AUTO, "single": osdp.OSDP_STAGING_SINGLE,
+               "double": osdp.OSDP_STAGING_DOUBLE, "half": osdp.OSDP_STAGING_HALF}[a.staging]
+    w = wl.workload(a.config, a.k)
+    st = Stack(w, staging, torch, osdp)
+    flops = wl.flops(w)
+
+    ms, _ = st.run(a.steps, a.warmup, serial=a.serial)
+    ms_prof, stats = st.run(a.steps, 2, serial=a.serial, profile=True)
+    kernels = kernel_table(stats)
+    gemms = {k: v for k, v in kernels.items() if k.startswith("gemm")}
+    dom = max(gemms, key=lambda k: gemms[k]["total_ms"])
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": gemms[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(gemms[dom]["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "avg_launch_us": gemms[dom]["avg_us"], "launches": gemms[dom]["launches"]}
+
+    out = {
+        "metric": "split-linear fwd+bwd TFLOP/s & % bf16 MFMA peak vs k; peak staging MB",
+        "value": round(flops / (ms * 1e-3) / 1e12, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps,
+        "warmup": a.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "baseline_config": a.config, "T": w.T, "N_shards": w.N, "layers": w.layers,
+                   "ops": {op.name: {"I": op.I, "O": op.O, "k": op.k} for op in w.ops},
+                   "staging": a.staging, "overlap": not a.serial},
+        "frac_bf16_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+        "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3),
+        "workspace_mb": round(st.workspace_bytes / 2 ** 20, 3),
+        "ms_per_step_with_kernel_timing": round(ms_prof, 4),
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+
+    if not a.no_sweep:
+        sweep = {}
+        for k in (w.k_sweep or ()):
+            wk = wl.workload(a.config, k)
+            del st
+            torch.cuda.empty_cache()
+            st = Stack(wk, staging, torch, osdp)
+            msk, _ = st.run(max(5, a.steps // 2), max(2, a.warmup // 2), serial=a.serial)
+            mss, _ = st.run(max(5, a.steps // 2), 2, serial=True)
+            _, sk = st.run(max(5, a.steps // 4), 2, serial=a.serial, profile=True)
+            kt = kernel_table(sk)
+            tf = wl.flops(wk) / (msk * 1e-3) / 1e12
+            sweep[str(k)] = {"tflops": round(tf, 2), "frac_bf16_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4),
+                             "ms_per_step": round(msk, 4), "ms_per_step_serial": round(mss, 4),
+                             "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3),
+                             "gather_gbs": kt.get("gather", {}).get("gbs_algorithmic"),
+                             "gather_frac_hbm_peak": round(kt.get("gather", {}).get("gbs_algorithmic", 0) / PEAK_HBM_GBS, 4)}
+        out["k_sweep"] = sweep
+        if a.config == 2:  # the h = 2560 layer under its plan vector, where the 70 % target applies
+            del st
+            torch.cuda.empty_cache()
+            w3 = wl.workload(3)
+            st = Stack(w3, staging, torch, osdp)
+            ms3, _ = st.run(10, 3, serial=a.serial)
+            tf3 = wl.flops(w3) / (ms3 * 1e-3) / 1e12
+            out["also"] = {"workload": w3.name, "plan": {op.name: op.k for op in w3.ops}, "ms_per_step": round(ms3, 4),
+                           "tflops": round(tf3, 2), "frac_bf16_mfma_peak": round(tf3 / PEAK_BF16_TFLOPS, 4),
+                           "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3)}
+    if not a.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,183 @@
+/*
+ * libosdp — operator-split linear layer of OSDP (arXiv 2209.13258) for AMD MI355X (gfx950).
+ *
+ * One GPU's share of a sharded-data-parallel step for one linear operator
+ * Y[T x O] = X[T x I] . W[I x O] (no bias).  W is kept in an N-way shard-major
+ * layout (Section 2.2: ZeRO/FSDP shard the model states over the N workers and
+ * re-gather them for use).  Following Section 3.3 ("Operator Splitting") the
+ * operator is cut into k slices that are gathered and processed one after
+ * another, so that only a slice of gathered weight is live at a time: the
+ * gathered-weight peak drops from size(MatMul) to size(MatMul)/slice_granularity.
+ * The slices are column slices of W (output features):
+ *
+ *     forward  : Y[:, c0_j:c1_j]  = X . Ws_j                     (concatenate)
+ *     backward : dW[:, c0_j:c1_j] = X^T . dY[:, c0_j:c1_j]       (concatenate)
+ *                dX               = sum_j dY[:, c0_j:c1_j] . Ws_j^T   (sum)
+ *
+ * where Ws_j[I x w_j] is slice j gathered from the N shards into a staging
+ * buffer.  All three recombine to exactly the unsplit product.
+ *
+ * Conventions
+ *   - Plain C ABI: no C++ or framework types.  Every "device" pointer is a HIP
+ *     device pointer on the current device; every "host" pointer is ordinary
+ *     host memory that is only read during the call.
+ *   - All matrices hold bf16 (IEEE binary32 upper half), row-major, with an
+ *     explicit leading dimension counted in elements.  Products accumulate in
+ *     fp32 on the matrix cores; outputs are rounded to bf16, nearest even.
+ *   - Shard-major layout of W (and of dW): flat index f = r*O + c, shard
+ *     length L = ceil(I*O/N); the element lives in buffer w_shards[f / L] at
+ *     element offset f % L.  Each shard is its own allocation of L elements;
+ *     the tail of the last shard is padding that is never read or written.
+ *     When N divides I this is N row blocks of I/N rows.
+ *   - Slice bounds: c0_j = floor(j*O/k), c1_j = floor((j+1)*O/k).  k = 0 means
+ *     "no splitting" (the paper's granularity 0, Section 4.3) and equals k = 1.
+ *   - The library never allocates device memory.  The caller owns all buffers,
+ *     including the workspace; the library owns only a few HIP events.
+ *   - Calls enqueue work and return.  When a call returns, synchronising
+ *     stream_compute alone makes every output valid, and stream_copy has been
+ *     ordered after the last use of the workspace.  Inputs must be ready on
+ *     stream_compute when the call is made.
+ *   - Errors: arguments are validated before anything is enqueued, so every
+ *     status except OSDP_ERR_HIP leaves the outputs untouched.
+ *     osdp_last_error() gives a thread-local message for the last failure.
+ *
+ * Shapes the GPU kernels accept (else OSDP_ERR_UNSUPPORTED): I, O, every slice
+ * bound c0_j, the shard length L and every leading dimension are multiples of
+ * 8 elements (16-byte vectors); pointers are 16-byte aligned; N <= 64;
+ * T, I, O < 2^31.
+ */
+#ifndef OSDP_H
+#define OSDP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OSDP_MAX_SHARDS 64
+#define OSDP_API __attribute__((visibility("default")))
+
+typedef enum {
+  OSDP_OK = 0,
+  OSDP_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, k > O, slice out of range, ld too small */
+  OSDP_ERR_UNSUPPORTED = -2, /* legal problem the kernels do not handle (alignment, N > 64, DP slices) */
+  OSDP_ERR_WORKSPACE = -3,   /* workspace_bytes smaller than osdp_split_linear_workspace_bytes says */
+  OSDP_ERR_HIP = -4          /* a HIP runtime call failed; outputs are undefined */
+} osdp_status;
+
+/* One linear operator (the paper's operator i with its parallelism degree N,
+ * Section 3) together with its slice granularity (Section 3.3). */
+typedef struct {
+  int64_t T; /* tokens: rows of X, Y, dY, dX                      */
+  int64_t I; /* in-features: columns of X, rows of W               */
+  int64_t O; /* out-features: columns of W, Y                      */
+  int32_t N; /* shard count                                        */
+  int32_t k; /* slice granularity; 0 == 1 == unsplit               */
+} osdp_shape;
+
+/* How the slice-sized staging area is used. */
+typedef enum {
+  OSDP_STAGING_AUTO = 0,   /* DOUBLE when two distinct streams are given and k > 1, else SINGLE */
+  OSDP_STAGING_SINGLE = 1, /* one slot of one slice (size/k): gather and GEMM alternate, no overlap */
+  OSDP_STAGING_DOUBLE = 2, /* two slots of one slice (2*size/k): gather j+1 overlaps GEMM j        */
+  OSDP_STAGING_HALF = 3    /* two slots of half a slice (size/k in total): every slice is processed
+                              as two half-width sub-slices so that the gather still overlaps      */
+} osdp_staging_mode;
+
+/* The per-operator execution plan (the paper's plan vector p over the n
+ * operators, Section 3.1), extended by the slice granularity of each operator
+ * (Section 3.3).  All arrays are host memory.  A NULL plan means "use
+ * shape->k, every slice gathered (ZDP), OSDP_STAGING_AUTO". */
+typedef struct {
+  int32_t n_ops;            /* number of operators the arrays describe                         */
+  const int32_t *k_per_op;  /* [n_ops] slice granularity; overrides shape->k for op_index      */
+  const uint64_t *zdp_mask; /* [n_ops] or NULL; bit j set: slice j is gathered (ZDP mode).     */
+                            /* Only NULL / all slices set is supported (Section 3.3 describes  */
+                            /* mixing DP and ZDP slices; not built here).                      */
+  int32_t staging;          /* an osdp_staging_mode                                            */
+} osdp_plan;
+
+/* Column range [*c0, *c1) of slice j for shape->O and shape->k. Host only. */
+OSDP_API osdp_status osdp_slice_range(const osdp_shape *shape, int32_t slice_j, int64_t *c0, int64_t *c1);
+
+/* Section 3.3, re-gathering of one slice: Ws_j[r, c] = W[r, c0_j + c].
+ *   w_shards : host array of shape->N device pointers (bf16 shard buffers)
+ *   staging  : device, dense row-major [I x w_j] bf16, >= I*w_j*2 bytes, written in full
+ *   stream   : hipStream_t (NULL = default stream)
+ * Pure copy: the result is bit-exact. */
+OSDP_API osdp_status osdp_split_linear_gather_slice(const osdp_shape *shape, int32_t slice_j,
+                                           const void *const *w_shards, void *staging,
+                                           void *stream);
+
+/* Bytes of workspace a forward (is_bwd = 0) or backward (is_bwd != 0) call
+ * needs, and how many of them hold gathered weights at the peak
+ * (Section 3.3: size(MatMul)/slice_granularity per live slice).
+ * Workspace layout: [staging slots][fp32 dX accumulator T*I, backward with k > 1 only].
+ * Either output pointer may be NULL. Host only. */
+OSDP_API osdp_status osdp_split_linear_workspace_bytes(const osdp_shape *shape, const osdp_plan *plan,
+                                              int32_t op_index, int32_t is_bwd, size_t *total,
+                                              size_t *peak_weight_staging);
+
+/* Section 3.3, forward of the split operator: for j = 0..k-1 gather slice j,
+ * then Y[:, c0_j:c1_j] = X . Ws_j.
+ *   X  : device [T x I], ldx >= I        Y : device [T x O], ldy >= O (every element written)
+ *   w_shards : host array of N device pointers
+ *   workspace: device, 256-byte aligned, >= osdp_split_linear_workspace_bytes(.., 0, ..)
+ *   stream_compute : hipStream_t the GEMMs run on
+ *   stream_copy    : hipStream_t the gathers run on; NULL or == stream_compute = no overlap
+ * Y is bit-identical for every k, staging mode and stream choice. */
+OSDP_API osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index,
+                                  const void *X, int64_t ldx, const void *const *w_shards,
+                                  void *Y, int64_t ldy, void *workspace, size_t workspace_bytes,
+                                  void *stream_compute, void *stream_copy);
+
+/* Section 3.3 applied to the backward pass (the weights are gathered again,
+ * Section 2.2): for j = 0..k-1, dW[:, c0_j:c1_j] = X^T . dY[:, c0_j:c1_j]
+ * (written into dw_shards, same shard-major layout as W, overwritten), and
+ * dX = sum_j dY[:, c0_j:c1_j] . Ws_j^T, accumulated in fp32 across the slices
+ * in ascending j and rounded to bf16 once.
+ *   dY : device [T x O], lddy >= O       dX : device [T x I], lddx >= I
+ *   dw_shards : host array of N device pointers, each L elements
+ * dW is bit-identical for every k; dX is too when every slice width is a
+ * multiple of 16. */
+OSDP_API osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index,
+                                  const void *X, int64_t ldx, const void *dY, int64_t lddy,
+                                  const void *const *w_shards, void *dX, int64_t lddx,
+                                  void *const *dw_shards, void *workspace, size_t workspace_bytes,
+                                  void *stream_compute, void *stream_copy);
+
+/* ---- per-kernel timing (for benchmarks) --------------------------------- */
+
+typedef enum {
+  OSDP_KERNEL_GATHER = 0,
+  OSDP_KERNEL_GEMM_FWD = 1,
+  OSDP_KERNEL_GEMM_DW = 2,
+  OSDP_KERNEL_GEMM_DX = 3,
+  OSDP_KERNEL_KINDS = 4
+} osdp_kernel_kind;
+
+typedef struct {
+  int64_t launches; /* kernel launches seen since osdp_profile_begin          */
+  double ms;        /* sum of their durations, HIP events on the launch stream */
+  double flops;     /* 2*M*N*K summed over GEMM launches                       */
+  double bytes;     /* algorithmic bytes summed over launches (see DESIGN)     */
+} osdp_kernel_stats;
+
+/* Between begin and end every kernel launch of the calling thread is bracketed
+ * by a pair of HIP events on its own stream (at most max_launches launches;
+ * later ones are not timed).  osdp_profile_end synchronises the device and
+ * fills stats[OSDP_KERNEL_KINDS]. Not for use inside hot loops one wants
+ * undisturbed: the event records sit between the kernels. */
+OSDP_API osdp_status osdp_profile_begin(int32_t max_launches);
+OSDP_API osdp_status osdp_profile_end(osdp_kernel_stats *stats);
+
+OSDP_API const char *osdp_strerror(osdp_status status);
+OSDP_API const char *osdp_last_error(void);
+OSDP_API const char *osdp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OSDP_H */

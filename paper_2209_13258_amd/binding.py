@@ -1,0 +1,201 @@
+"""ctypes binding of libosdp: same names as the C ABI, argument marshalling only.
+
+PyTorch supplies device memory (``tensor.data_ptr()``) and streams
+(``torch.cuda.Stream().cuda_stream`` is a ``hipStream_t`` on ROCm builds); every
+step of the path runs inside the library's HIP kernels.  There is no CPU or
+PyTorch fallback: if the library is missing the import of this module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+from . import build as _build
+
+OSDP_OK = 0
+OSDP_ERR_INVALID_ARG = -1
+OSDP_ERR_UNSUPPORTED = -2
+OSDP_ERR_WORKSPACE = -3
+OSDP_ERR_HIP = -4
+
+OSDP_STAGING_AUTO = 0
+OSDP_STAGING_SINGLE = 1
+OSDP_STAGING_DOUBLE = 2
+OSDP_STAGING_HALF = 3
+
+OSDP_KERNEL_GATHER = 0
+OSDP_KERNEL_GEMM_FWD = 1
+OSDP_KERNEL_GEMM_DW = 2
+OSDP_KERNEL_GEMM_DX = 3
+OSDP_KERNEL_KINDS = 4
+KERNEL_NAMES = ("gather", "gemm_fwd", "gemm_dw", "gemm_dx")
+
+EXPORTS = (
+    "osdp_slice_range", "osdp_split_linear_gather_slice", "osdp_split_linear_workspace_bytes",
+    "osdp_split_linear_fwd", "osdp_split_linear_bwd", "osdp_profile_begin", "osdp_profile_end",
+    "osdp_strerror", "osdp_last_error", "osdp_version",
+)
+
+
+class osdp_shape(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int64), ("I", ctypes.c_int64), ("O", ctypes.c_int64),
+                ("N", ctypes.c_int32), ("k", ctypes.c_int32)]
+
+
+class osdp_plan(ctypes.Structure):
+    _fields_ = [("n_ops", ctypes.c_int32), ("k_per_op", ctypes.POINTER(ctypes.c_int32)),
+                ("zdp_mask", ctypes.POINTER(ctypes.c_uint64)), ("staging", ctypes.c_int32)]
+
+
+class osdp_kernel_stats(ctypes.Structure):
+    _fields_ = [("launches", ctypes.c_int64), ("ms", ctypes.c_double), ("flops", ctypes.c_double),
+                ("bytes", ctypes.c_double)]
+
+
+class OsdpError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"libosdp status {status}: {message}")
+        self.status = status
+
+
+def _load() -> ctypes.CDLL:
+    path = _build.LIB
+    if not path.exists():
+        raise ImportError(
+            f"{path} is missing: build it first (python -m paper_2209_13258_amd.build); "
+            "there is no fallback path")
+    lib = ctypes.CDLL(str(path))
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    shp, pln = ctypes.POINTER(osdp_shape), ctypes.POINTER(osdp_plan)
+    lib.osdp_slice_range.argtypes = [shp, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    lib.osdp_split_linear_gather_slice.argtypes = [shp, i32, vp, vp, vp]
+    lib.osdp_split_linear_workspace_bytes.argtypes = [shp, pln, i32, i32, ctypes.POINTER(ctypes.c_size_t),
+                                                      ctypes.POINTER(ctypes.c_size_t)]
+    lib.osdp_split_linear_fwd.argtypes = [shp, pln, i32, vp, i64, vp, vp, i64, vp, ctypes.c_size_t, vp, vp]
+    lib.osdp_split_linear_bwd.argtypes = [shp, pln, i32, vp, i64, vp, i64, vp, vp, i64, vp, vp,
+                                          ctypes.c_size_t, vp, vp]
+    lib.osdp_profile_begin.argtypes = [i32]
+    lib.osdp_profile_end.argtypes = [ctypes.POINTER(osdp_kernel_stats)]
+    for name in ("osdp_slice_range", "osdp_split_linear_gather_slice", "osdp_split_linear_workspace_bytes",
+                 "osdp_split_linear_fwd", "osdp_split_linear_bwd", "osdp_profile_begin", "osdp_profile_end"):
+        getattr(lib, name).restype = ctypes.c_int
+    lib.osdp_strerror.argtypes = [ctypes.c_int]
+    lib.osdp_strerror.restype = ctypes.c_char_p
+    lib.osdp_last_error.restype = ctypes.c_char_p
+    lib.osdp_version.restype = ctypes.c_char_p
+    return lib
+
+
+lib = _load()
+
+
+def _check(status: int) -> None:
+    if status != OSDP_OK:
+        msg = lib.osdp_last_error().decode() or lib.osdp_strerror(status).decode()
+        raise OsdpError(status, msg)
+
+
+@dataclass
+class Plan:
+    """Per-operator slice granularities (and, optionally, ZDP masks) plus the staging mode."""
+    k_per_op: Sequence[int]
+    staging: int = OSDP_STAGING_AUTO
+    zdp_mask: Optional[Sequence[int]] = None
+
+    def to_c(self):
+        n = len(self.k_per_op)
+        ks = (ctypes.c_int32 * n)(*self.k_per_op)
+        mask = (ctypes.c_uint64 * n)(*self.zdp_mask) if self.zdp_mask is not None else None
+        p = osdp_plan(n, ctypes.cast(ks, ctypes.POINTER(ctypes.c_int32)),
+                      ctypes.cast(mask, ctypes.POINTER(ctypes.c_uint64)) if mask is not None else None,
+                      self.staging)
+        return p, (ks, mask)  # keep the arrays alive with the struct
+
+
+def _shape(T, I, O, N, k):
+    return osdp_shape(int(T), int(I), int(O), int(N), int(k))
+
+
+def _plan_ref(plan: Optional[Plan]):
+    if plan is None:
+        return None, None
+    p, keep = plan.to_c()
+    return ctypes.byref(p), (p, keep)
+
+
+def _ptrs(tensors):
+    return (ctypes.c_void_p * len(tensors))(*[int(t.data_ptr()) for t in tensors])
+
+
+def _stream(s) -> Optional[int]:
+    if s is None:
+        return None
+    return int(getattr(s, "cuda_stream", s))
+
+
+def osdp_version() -> str:
+    return lib.osdp_version().decode()
+
+
+def osdp_slice_range(O: int, k: int, j: int, T: int = 1, I: int = 8, N: int = 1):
+    c0, c1 = ctypes.c_int64(), ctypes.c_int64()
+    shape = _shape(T, I, O, N, k)
+    _check(lib.osdp_slice_range(ctypes.byref(shape), j, ctypes.byref(c0), ctypes.byref(c1)))
+    return c0.value, c1.value
+
+
+def osdp_split_linear_workspace_bytes(T, I, O, N, k, is_bwd: bool, plan: Optional[Plan] = None, op_index: int = 0):
+    """Returns (total workspace bytes, peak gathered-weight staging bytes)."""
+    shape = _shape(T, I, O, N, k)
+    total, peak = ctypes.c_size_t(), ctypes.c_size_t()
+    pref, _keep = _plan_ref(plan)
+    _check(lib.osdp_split_linear_workspace_bytes(ctypes.byref(shape), pref, op_index, int(bool(is_bwd)),
+                                                 ctypes.byref(total), ctypes.byref(peak)))
+    return total.value, peak.value
+
+
+def osdp_split_linear_gather_slice(I, O, k, j, w_shards, staging, stream=None, T: int = 1):
+    """Gathers column slice j of k from the shard tensors into ``staging`` (dense [I x w_j])."""
+    shape = _shape(T, I, O, len(w_shards), k)
+    _check(lib.osdp_split_linear_gather_slice(ctypes.byref(shape), j, _ptrs(w_shards),
+                                              int(staging.data_ptr()), _stream(stream)))
+
+
+def osdp_split_linear_fwd(X, w_shards, Y, k, workspace, *, plan: Optional[Plan] = None, op_index: int = 0,
+                          stream_compute=None, stream_copy=None):
+    """Y[T x O] = X[T x I] . W, W given as N shard tensors; X, Y 2-D bf16 tensors (row stride = ld)."""
+    T, I = X.shape
+    O = Y.shape[1]
+    shape = _shape(T, I, O, len(w_shards), k)
+    pref, _keep = _plan_ref(plan)
+    _check(lib.osdp_split_linear_fwd(ctypes.byref(shape), pref, op_index, int(X.data_ptr()), X.stride(0),
+                                     _ptrs(w_shards), int(Y.data_ptr()), Y.stride(0),
+                                     int(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                                     _stream(stream_compute), _stream(stream_copy)))
+
+
+def osdp_split_linear_bwd(X, dY, w_shards, dX, dw_shards, k, workspace, *, plan: Optional[Plan] = None,
+                          op_index: int = 0, stream_compute=None, stream_copy=None):
+    """dX[T x I] and the shard-major dW from X[T x I], dY[T x O] and the weight shards."""
+    T, I = X.shape
+    O = dY.shape[1]
+    shape = _shape(T, I, O, len(w_shards), k)
+    pref, _keep = _plan_ref(plan)
+    _check(lib.osdp_split_linear_bwd(ctypes.byref(shape), pref, op_index, int(X.data_ptr()), X.stride(0),
+                                     int(dY.data_ptr()), dY.stride(0), _ptrs(w_shards),
+                                     int(dX.data_ptr()), dX.stride(0), _ptrs(dw_shards),
+                                     int(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                                     _stream(stream_compute), _stream(stream_copy)))
+
+
+def osdp_profile_begin(max_launches: int = 1 << 16) -> None:
+    _check(lib.osdp_profile_begin(max_launches))
+
+
+def osdp_profile_end():
+    """Returns {kernel name: dict(launches, ms, flops, bytes)}."""
+    stats = (osdp_kernel_stats * OSDP_KERNEL_KINDS)()
+    _check(lib.osdp_profile_end(stats))
+    return {KERNEL_NAMES[i]: dict(launches=stats[i].launches, ms=stats[i].ms, flops=stats[i].flops,
+                                  bytes=stats[i].bytes) for i in range(OSDP_KERNEL_KINDS)}

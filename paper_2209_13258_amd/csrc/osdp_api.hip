@@ -1,0 +1,487 @@
+// Host side of libosdp: argument validation, slice planning, the two-stream
+// gather/GEMM pipeline and the optional per-kernel timing.
+//
+// Pipeline (arXiv 2209.13258, Section 3.3: slices are processed one after
+// another so that their memory is released serially, and the re-gathering is
+// overlapped with computation): the gather of slice j+1 runs on the copy
+// stream into the staging slot that the GEMM of slice j-1 has released, while
+// the GEMM of slice j runs on the compute stream.
+#include <algorithm>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "osdp_internal.h"
+
+namespace {
+
+using namespace osdp;
+
+thread_local std::string t_last_error;
+
+osdp_status fail(osdp_status st, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  t_last_error = buf;
+  return st;
+}
+
+osdp_status fail_hip(hipError_t e, const char *what) {
+  return fail(OSDP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define OSDP_HIP(call)                                     \
+  do {                                                     \
+    hipError_t e_ = (call);                                \
+    if (e_ != hipSuccess) return fail_hip(e_, #call);      \
+  } while (0)
+
+constexpr size_t kSlotAlign = 256;
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// ---- slice planning ---------------------------------------------------------
+struct Slice {
+  int64_t c0, c1;
+};
+
+struct Resolved {
+  int64_t T, I, O;
+  int32_t N, k;
+  int32_t mode;              // resolved osdp_staging_mode (never AUTO)
+  int32_t slots;             // staging slots in the workspace
+  std::vector<Slice> sub;    // the column ranges processed one after another
+  ShardLayout layout;
+  size_t slot_bytes;         // one staging slot, rounded up to kSlotAlign
+  size_t peak_staging;       // gathered-weight bytes live at the peak (unrounded)
+  size_t acc_bytes;          // fp32 dX accumulator (backward with more than one sub-slice)
+};
+
+void slice_bounds(int64_t O, int64_t k, int64_t j, int64_t *c0, int64_t *c1) {
+  *c0 = (j * O) / k;
+  *c1 = ((j + 1) * O) / k;
+}
+
+osdp_status check_shape(const osdp_shape *s) {
+  if (!s) return fail(OSDP_ERR_INVALID_ARG, "shape is NULL");
+  if (s->T <= 0 || s->I <= 0 || s->O <= 0)
+    return fail(OSDP_ERR_INVALID_ARG, "T, I, O must be positive (got %lld, %lld, %lld)", (long long)s->T,
+                (long long)s->I, (long long)s->O);
+  if (s->N < 1) return fail(OSDP_ERR_INVALID_ARG, "N must be >= 1 (got %d)", s->N);
+  if (s->k < 0) return fail(OSDP_ERR_INVALID_ARG, "k must be >= 0 (got %d)", s->k);
+  return OSDP_OK;
+}
+
+// Resolves k and the staging mode, checks what the kernels need and lists the sub-slices.
+// `overlap_possible`: two distinct streams were given (or, for the size query, assumed).
+osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, bool overlap_possible,
+                    bool is_bwd, Resolved *r) {
+  osdp_status st = check_shape(shape);
+  if (st != OSDP_OK) return st;
+  int64_t k = shape->k;
+  int32_t mode = OSDP_STAGING_AUTO;
+  const uint64_t *mask = nullptr;
+  if (plan) {
+    if (plan->n_ops <= 0) return fail(OSDP_ERR_INVALID_ARG, "plan->n_ops must be positive");
+    if (op_index < 0 || op_index >= plan->n_ops)
+      return fail(OSDP_ERR_INVALID_ARG, "op_index %d outside the plan's %d operators", op_index, plan->n_ops);
+    if (plan->k_per_op) k = plan->k_per_op[op_index];
+    if (k < 0) return fail(OSDP_ERR_INVALID_ARG, "plan k must be >= 0 (got %lld)", (long long)k);
+    mode = plan->staging;
+    if (mode < OSDP_STAGING_AUTO || mode > OSDP_STAGING_HALF)
+      return fail(OSDP_ERR_INVALID_ARG, "unknown staging mode %d", mode);
+    if (plan->zdp_mask) mask = plan->zdp_mask + op_index;
+  }
+  if (k == 0) k = 1;
+  if (k > shape->O) return fail(OSDP_ERR_INVALID_ARG, "k = %lld exceeds O = %lld", (long long)k, (long long)shape->O);
+  if (mask) {
+    const uint64_t want = k >= 64 ? ~0ull : ((1ull << k) - 1ull);
+    if (k > 64 || (*mask & want) != want)
+      return fail(OSDP_ERR_UNSUPPORTED, "slices in DP mode (zdp_mask with cleared bits) are not supported");
+  }
+  const int64_t T = shape->T, I = shape->I, O = shape->O;
+  const int32_t N = shape->N;
+  if (T >= (1ll << 31) || I >= (1ll << 31) || O >= (1ll << 31))
+    return fail(OSDP_ERR_UNSUPPORTED, "T, I, O must be below 2^31");
+  if (N > OSDP_MAX_SHARDS) return fail(OSDP_ERR_UNSUPPORTED, "N = %d exceeds %d shards", N, OSDP_MAX_SHARDS);
+  if (I % 8 || O % 8) return fail(OSDP_ERR_UNSUPPORTED, "I and O must be multiples of 8 (got %lld, %lld)", (long long)I, (long long)O);
+  const int64_t L = (I * O + N - 1) / N;
+  if (L % 8) return fail(OSDP_ERR_UNSUPPORTED, "shard length %lld is not a multiple of 8", (long long)L);
+
+  if (mode == OSDP_STAGING_AUTO) mode = (overlap_possible && k > 1) ? OSDP_STAGING_DOUBLE : OSDP_STAGING_SINGLE;
+  if (k == 1 && mode == OSDP_STAGING_DOUBLE) mode = OSDP_STAGING_SINGLE;
+
+  r->T = T; r->I = I; r->O = O; r->N = N; r->k = static_cast<int32_t>(k); r->mode = mode;
+  r->layout.O = O; r->layout.L = L; r->layout.N = N;
+  r->layout.rows_per_shard = (I % N == 0) ? static_cast<int32_t>(I / N) : 0;
+  r->sub.clear();
+  int64_t wmax = 0;
+  for (int64_t j = 0; j < k; ++j) {
+    int64_t c0, c1;
+    slice_bounds(O, k, j, &c0, &c1);
+    if (c0 % 8 || c1 % 8)
+      return fail(OSDP_ERR_UNSUPPORTED, "slice %lld = [%lld, %lld) is not aligned to 8 columns", (long long)j, (long long)c0, (long long)c1);
+    if (mode == OSDP_STAGING_HALF) {
+      if ((c1 - c0) % 16)
+        return fail(OSDP_ERR_UNSUPPORTED, "half-slice staging needs slice widths that are multiples of 16 (slice %lld has %lld)", (long long)j, (long long)(c1 - c0));
+      const int64_t mid = c0 + (c1 - c0) / 2;
+      r->sub.push_back({c0, mid});
+      r->sub.push_back({mid, c1});
+      wmax = std::max(wmax, (c1 - c0) / 2);
+    } else {
+      r->sub.push_back({c0, c1});
+      wmax = std::max(wmax, c1 - c0);
+    }
+  }
+  r->slots = (mode == OSDP_STAGING_SINGLE) ? 1 : 2;
+  if (static_cast<uint64_t>(I) * static_cast<uint64_t>(wmax) / 8 >= (1ull << 32))
+    return fail(OSDP_ERR_UNSUPPORTED, "slice of %lld x %lld elements is too large for the gather kernel", (long long)I, (long long)wmax);
+  const size_t slice_bytes = static_cast<size_t>(I) * static_cast<size_t>(wmax) * 2;
+  r->slot_bytes = round_up(slice_bytes, kSlotAlign);
+  r->peak_staging = slice_bytes * r->slots;
+  r->acc_bytes = (is_bwd && r->sub.size() > 1) ? static_cast<size_t>(T) * static_cast<size_t>(I) * 4 : 0;
+  return OSDP_OK;
+}
+
+size_t workspace_total(const Resolved &r) { return r.slot_bytes * r.slots + r.acc_bytes; }
+
+osdp_status fill_table(const void *const *ptrs, int32_t N, const char *name, ShardTable *t) {
+  if (!ptrs) return fail(OSDP_ERR_INVALID_ARG, "%s is NULL", name);
+  std::memset(t, 0, sizeof *t);
+  for (int32_t s = 0; s < N; ++s) {
+    if (!ptrs[s]) return fail(OSDP_ERR_INVALID_ARG, "%s[%d] is NULL", name, s);
+    if (!aligned16(ptrs[s])) return fail(OSDP_ERR_UNSUPPORTED, "%s[%d] is not 16-byte aligned", name, s);
+    t->p[s] = const_cast<void *>(ptrs[s]);
+  }
+  return OSDP_OK;
+}
+
+osdp_status check_matrix(const void *p, int64_t ld, int64_t cols, const char *name) {
+  if (!p) return fail(OSDP_ERR_INVALID_ARG, "%s is NULL", name);
+  if (ld < cols) return fail(OSDP_ERR_INVALID_ARG, "leading dimension of %s (%lld) is below its row length %lld", name, (long long)ld, (long long)cols);
+  if (ld % 8) return fail(OSDP_ERR_UNSUPPORTED, "leading dimension of %s (%lld) is not a multiple of 8", name, (long long)ld);
+  if (!aligned16(p)) return fail(OSDP_ERR_UNSUPPORTED, "%s is not 16-byte aligned", name);
+  return OSDP_OK;
+}
+
+osdp_status check_workspace(const Resolved &r, const void *ws, size_t bytes) {
+  if (!ws) return fail(OSDP_ERR_INVALID_ARG, "workspace is NULL");
+  if (reinterpret_cast<uintptr_t>(ws) % kSlotAlign) return fail(OSDP_ERR_UNSUPPORTED, "workspace is not 256-byte aligned");
+  const size_t need = workspace_total(r);
+  if (bytes < need) return fail(OSDP_ERR_WORKSPACE, "workspace holds %zu bytes, %zu needed", bytes, need);
+  return OSDP_OK;
+}
+
+// ---- events -----------------------------------------------------------------
+// A cyclic pool of untimed events for the cross-stream edges.  An event may be
+// re-recorded once the waits on its earlier record have been enqueued, which
+// always holds here: every wait is issued within a few pool steps of its record.
+class EventPool {
+ public:
+  hipError_t get(hipEvent_t *out) {
+    std::lock_guard<std::mutex> g(mu_);
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    PerDevice &d = dev_[dev];
+    if (d.ev.size() < kPool) {
+      hipEvent_t ev;
+      e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+      if (e != hipSuccess) return e;
+      d.ev.push_back(ev);
+      *out = ev;
+      return hipSuccess;
+    }
+    *out = d.ev[d.next];
+    d.next = (d.next + 1) % kPool;
+    return hipSuccess;
+  }
+
+ private:
+  static constexpr size_t kPool = 512;
+  static constexpr int kMaxDevices = 16;
+  struct PerDevice {
+    std::vector<hipEvent_t> ev;
+    size_t next = 0;
+  };
+  std::mutex mu_;
+  PerDevice dev_[kMaxDevices];
+};
+
+EventPool g_events;
+
+// after: everything enqueued on `from` so far; makes `to` wait for it
+hipError_t edge(hipStream_t from, hipStream_t to) {
+  hipEvent_t ev;
+  hipError_t e = g_events.get(&ev);
+  if (e != hipSuccess) return e;
+  e = hipEventRecord(ev, from);
+  if (e != hipSuccess) return e;
+  return hipStreamWaitEvent(to, ev, 0);
+}
+
+// ---- per-kernel timing --------------------------------------------------------
+struct TimedLaunch {
+  int kind;
+  hipEvent_t start, stop;
+  double flops, bytes;
+};
+
+struct Profile {
+  bool active = false;
+  size_t max_launches = 0;
+  std::vector<TimedLaunch> launches;
+  std::vector<hipEvent_t> spare;  // timed events kept for reuse
+};
+
+thread_local Profile t_profile;
+
+hipError_t timed_event(hipEvent_t *ev) {
+  if (!t_profile.spare.empty()) {
+    *ev = t_profile.spare.back();
+    t_profile.spare.pop_back();
+    return hipSuccess;
+  }
+  return hipEventCreate(ev);
+}
+
+template <class F>
+hipError_t timed(int kind, double flops, double bytes, hipStream_t stream, F &&launch) {
+  Profile &pf = t_profile;
+  if (!pf.active || pf.launches.size() >= pf.max_launches) return launch();
+  TimedLaunch t{kind, nullptr, nullptr, flops, bytes};
+  hipError_t e = timed_event(&t.start);
+  if (e != hipSuccess) return e;
+  e = timed_event(&t.stop);
+  if (e != hipSuccess) return e;
+  e = hipEventRecord(t.start, stream);
+  if (e != hipSuccess) return e;
+  e = launch();
+  if (e != hipSuccess) return e;
+  e = hipEventRecord(t.stop, stream);
+  if (e != hipSuccess) return e;
+  pf.launches.push_back(t);
+  return hipSuccess;
+}
+
+hipError_t do_gather(const Resolved &r, const ShardTable &tab, const Slice &s, void *slot, hipStream_t stream) {
+  const int64_t w = s.c1 - s.c0;
+  const double bytes = 2.0 * static_cast<double>(r.I) * static_cast<double>(w) * 2.0;
+  return timed(OSDP_KERNEL_GATHER, 0.0, bytes, stream,
+               [&] { return launch_gather(tab, r.layout, r.I, s.c0, w, slot, stream); });
+}
+
+hipError_t do_gemm(int kind, const GemmProblem &g, hipStream_t stream) {
+  const double M = g.M, N = g.N, K = g.K;
+  const double out_bytes = g.epilogue == Epilogue::kF32Workspace ? 4.0 : 2.0;
+  const double bytes = 2.0 * M * K + 2.0 * K * N + out_bytes * M * N + (g.acc_in ? 4.0 * M * N : 0.0);
+  return timed(kind, 2.0 * M * N * K, bytes, stream, [&] { return launch_gemm(g, stream); });
+}
+
+}  // namespace
+
+// =============================================================================
+extern "C" {
+
+const char *osdp_version(void) { return "libosdp 0.1 (gfx950)"; }
+
+const char *osdp_last_error(void) { return t_last_error.c_str(); }
+
+const char *osdp_strerror(osdp_status status) {
+  switch (status) {
+    case OSDP_OK: return "ok";
+    case OSDP_ERR_INVALID_ARG: return "invalid argument";
+    case OSDP_ERR_UNSUPPORTED: return "unsupported shape, alignment or plan";
+    case OSDP_ERR_WORKSPACE: return "workspace too small";
+    case OSDP_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+osdp_status osdp_slice_range(const osdp_shape *shape, int32_t slice_j, int64_t *c0, int64_t *c1) {
+  osdp_status st = check_shape(shape);
+  if (st != OSDP_OK) return st;
+  if (!c0 || !c1) return fail(OSDP_ERR_INVALID_ARG, "c0 / c1 is NULL");
+  const int64_t k = shape->k == 0 ? 1 : shape->k;
+  if (k > shape->O) return fail(OSDP_ERR_INVALID_ARG, "k = %lld exceeds O = %lld", (long long)k, (long long)shape->O);
+  if (slice_j < 0 || slice_j >= k) return fail(OSDP_ERR_INVALID_ARG, "slice %d outside [0, %lld)", slice_j, (long long)k);
+  slice_bounds(shape->O, k, slice_j, c0, c1);
+  return OSDP_OK;
+}
+
+osdp_status osdp_split_linear_workspace_bytes(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index,
+                                              int32_t is_bwd, size_t *total, size_t *peak_weight_staging) {
+  Resolved r;
+  osdp_status st = resolve(shape, plan, op_index, /*overlap_possible=*/true, is_bwd != 0, &r);
+  if (st != OSDP_OK) return st;
+  if (total) *total = workspace_total(r);
+  if (peak_weight_staging) *peak_weight_staging = r.peak_staging;
+  return OSDP_OK;
+}
+
+osdp_status osdp_split_linear_gather_slice(const osdp_shape *shape, int32_t slice_j, const void *const *w_shards,
+                                           void *staging, void *stream) {
+  Resolved r;
+  osdp_plan plan = {1, nullptr, nullptr, OSDP_STAGING_SINGLE};
+  osdp_status st = resolve(shape, &plan, 0, false, false, &r);
+  if (st != OSDP_OK) return st;
+  if (slice_j < 0 || slice_j >= r.k) return fail(OSDP_ERR_INVALID_ARG, "slice %d outside [0, %d)", slice_j, r.k);
+  ShardTable tab;
+  st = fill_table(w_shards, r.N, "w_shards", &tab);
+  if (st != OSDP_OK) return st;
+  if (!staging) return fail(OSDP_ERR_INVALID_ARG, "staging is NULL");
+  if (!aligned16(staging)) return fail(OSDP_ERR_UNSUPPORTED, "staging is not 16-byte aligned");
+  OSDP_HIP(do_gather(r, tab, r.sub[slice_j], staging, static_cast<hipStream_t>(stream)));
+  return OSDP_OK;
+}
+
+osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, const void *X,
+                                  int64_t ldx, const void *const *w_shards, void *Y, int64_t ldy, void *workspace,
+                                  size_t workspace_bytes, void *stream_compute, void *stream_copy) {
+  hipStream_t sc = static_cast<hipStream_t>(stream_compute), sp = static_cast<hipStream_t>(stream_copy);
+  const bool two_streams = sp != nullptr && sp != sc;
+  Resolved r;
+  osdp_status st = resolve(shape, plan, op_index, two_streams, false, &r);
+  if (st != OSDP_OK) return st;
+  if ((st = check_matrix(X, ldx, r.I, "X")) != OSDP_OK) return st;
+  if ((st = check_matrix(Y, ldy, r.O, "Y")) != OSDP_OK) return st;
+  ShardTable tab;
+  if ((st = fill_table(w_shards, r.N, "w_shards", &tab)) != OSDP_OK) return st;
+  if ((st = check_workspace(r, workspace, workspace_bytes)) != OSDP_OK) return st;
+
+  char *ws = static_cast<char *>(workspace);
+  const int n = static_cast<int>(r.sub.size());
+  const bool overlap = two_streams && r.slots == 2 && n > 1;
+  std::vector<hipEvent_t> done(n, nullptr);
+  if (overlap) OSDP_HIP(edge(sc, sp));  // the staging area may still be in use by earlier compute-stream work
+  for (int j = 0; j < n; ++j) {
+    const Slice &s = r.sub[j];
+    void *slot = ws + static_cast<size_t>(j % r.slots) * r.slot_bytes;
+    hipStream_t sg = overlap ? sp : sc;
+    if (overlap && j >= 2) OSDP_HIP(hipStreamWaitEvent(sp, done[j - 2], 0));  // slot released by GEMM j-2
+    OSDP_HIP(do_gather(r, tab, s, slot, sg));
+    if (overlap) OSDP_HIP(edge(sp, sc));
+    GemmProblem g{};
+    g.M = static_cast<int32_t>(r.T); g.N = static_cast<int32_t>(s.c1 - s.c0); g.K = static_cast<int32_t>(r.I);
+    g.A = X; g.lda = ldx; g.a_kcontig = true;
+    g.B = slot; g.ldb = s.c1 - s.c0; g.b_kcontig = false;
+    g.C = static_cast<uint16_t *>(Y) + s.c0; g.ldc = ldy;
+    g.epilogue = Epilogue::kBf16RowMajor;
+    OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_FWD, g, sc));
+    if (overlap && j + 2 < n) {
+      OSDP_HIP(g_events.get(&done[j]));
+      OSDP_HIP(hipEventRecord(done[j], sc));
+    }
+  }
+  if (overlap) OSDP_HIP(edge(sc, sp));  // later copy-stream work may reuse the workspace
+  return OSDP_OK;
+}
+
+osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, const void *X,
+                                  int64_t ldx, const void *dY, int64_t lddy, const void *const *w_shards, void *dX,
+                                  int64_t lddx, void *const *dw_shards, void *workspace, size_t workspace_bytes,
+                                  void *stream_compute, void *stream_copy) {
+  hipStream_t sc = static_cast<hipStream_t>(stream_compute), sp = static_cast<hipStream_t>(stream_copy);
+  const bool two_streams = sp != nullptr && sp != sc;
+  Resolved r;
+  osdp_status st = resolve(shape, plan, op_index, two_streams, true, &r);
+  if (st != OSDP_OK) return st;
+  if ((st = check_matrix(X, ldx, r.I, "X")) != OSDP_OK) return st;
+  if ((st = check_matrix(dY, lddy, r.O, "dY")) != OSDP_OK) return st;
+  if ((st = check_matrix(dX, lddx, r.I, "dX")) != OSDP_OK) return st;
+  ShardTable tab, gtab;
+  if ((st = fill_table(w_shards, r.N, "w_shards", &tab)) != OSDP_OK) return st;
+  if ((st = fill_table(reinterpret_cast<const void *const *>(dw_shards), r.N, "dw_shards", &gtab)) != OSDP_OK) return st;
+  if ((st = check_workspace(r, workspace, workspace_bytes)) != OSDP_OK) return st;
+
+  char *ws = static_cast<char *>(workspace);
+  float *acc = reinterpret_cast<float *>(ws + r.slot_bytes * r.slots);
+  const int n = static_cast<int>(r.sub.size());
+  const bool overlap = two_streams && r.slots == 2 && n > 1;
+  std::vector<hipEvent_t> done(n, nullptr);
+  if (overlap) OSDP_HIP(edge(sc, sp));
+  for (int j = 0; j < n; ++j) {
+    const Slice &s = r.sub[j];
+    const int64_t w = s.c1 - s.c0;
+    void *slot = ws + static_cast<size_t>(j % r.slots) * r.slot_bytes;
+    hipStream_t sg = overlap ? sp : sc;
+    if (overlap && j >= 2) OSDP_HIP(hipStreamWaitEvent(sp, done[j - 2], 0));
+    OSDP_HIP(do_gather(r, tab, s, slot, sg));
+    hipEvent_t gathered = nullptr;
+    if (overlap) {
+      OSDP_HIP(g_events.get(&gathered));
+      OSDP_HIP(hipEventRecord(gathered, sp));
+    }
+    // dW_j = X^T . dY_j needs no weights: it runs while the gather is still in flight
+    GemmProblem gw{};
+    gw.M = static_cast<int32_t>(r.I); gw.N = static_cast<int32_t>(w); gw.K = static_cast<int32_t>(r.T);
+    gw.A = X; gw.lda = ldx; gw.a_kcontig = false;
+    gw.B = static_cast<const uint16_t *>(dY) + s.c0; gw.ldb = lddy; gw.b_kcontig = false;
+    gw.epilogue = Epilogue::kBf16ShardMajor;
+    gw.layout = r.layout; gw.shards = gtab; gw.c0 = s.c0;
+    OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DW, gw, sc));
+    if (overlap) OSDP_HIP(hipStreamWaitEvent(sc, gathered, 0));
+    // dX (+)= dY_j . Ws_j^T ; the fp32 partial sum is carried in the workspace between slices
+    GemmProblem gx{};
+    gx.M = static_cast<int32_t>(r.T); gx.N = static_cast<int32_t>(r.I); gx.K = static_cast<int32_t>(w);
+    gx.A = static_cast<const uint16_t *>(dY) + s.c0; gx.lda = lddy; gx.a_kcontig = true;
+    gx.B = slot; gx.ldb = w; gx.b_kcontig = true;
+    if (j > 0) { gx.acc_in = acc; gx.ld_acc = r.I; }
+    if (j == n - 1) {
+      gx.C = dX; gx.ldc = lddx; gx.epilogue = Epilogue::kBf16RowMajor;
+    } else {
+      gx.C = acc; gx.ldc = r.I; gx.epilogue = Epilogue::kF32Workspace;
+    }
+    OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DX, gx, sc));
+    if (overlap && j + 2 < n) {
+      OSDP_HIP(g_events.get(&done[j]));
+      OSDP_HIP(hipEventRecord(done[j], sc));
+    }
+  }
+  if (overlap) OSDP_HIP(edge(sc, sp));
+  return OSDP_OK;
+}
+
+osdp_status osdp_profile_begin(int32_t max_launches) {
+  if (max_launches <= 0) return fail(OSDP_ERR_INVALID_ARG, "max_launches must be positive");
+  Profile &pf = t_profile;
+  for (TimedLaunch &t : pf.launches) {
+    pf.spare.push_back(t.start);
+    pf.spare.push_back(t.stop);
+  }
+  pf.launches.clear();
+  pf.max_launches = static_cast<size_t>(max_launches);
+  pf.active = true;
+  return OSDP_OK;
+}
+
+osdp_status osdp_profile_end(osdp_kernel_stats *stats) {
+  Profile &pf = t_profile;
+  if (!stats) return fail(OSDP_ERR_INVALID_ARG, "stats is NULL");
+  if (!pf.active) return fail(OSDP_ERR_INVALID_ARG, "osdp_profile_begin was not called");
+  pf.active = false;
+  std::memset(stats, 0, sizeof(osdp_kernel_stats) * OSDP_KERNEL_KINDS);
+  OSDP_HIP(hipDeviceSynchronize());
+  for (TimedLaunch &t : pf.launches) {
+    float ms = 0.f;
+    OSDP_HIP(hipEventElapsedTime(&ms, t.start, t.stop));
+    osdp_kernel_stats &s = stats[t.kind];
+    s.launches += 1;
+    s.ms += ms;
+    s.flops += t.flops;
+    s.bytes += t.bytes;
+    pf.spare.push_back(t.start);
+    pf.spare.push_back(t.stop);
+  }
+  pf.launches.clear();
+  return OSDP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,85 @@
+// Shard -> slice gather (arXiv 2209.13258, Section 3.3: each slice of the
+// sharded weight is re-gathered on its own before it is used).
+//
+// On one GPU the N shards are N device buffers, so the all-gather of a slice
+// becomes a strided copy: row r of the slice is w contiguous elements that
+// start at flat index r*O + c0 of the shard-major matrix.  The kernel is a
+// pure 16-byte-vector copy and is bound by HBM bandwidth: it reads I*w*2
+// bytes and writes I*w*2 bytes.
+#include "osdp_internal.h"
+
+namespace osdp {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kUnroll = 4;
+
+// One thread moves kUnroll vectors of 8 bf16 per grid-stride step.  Vector v of
+// the dense destination [I x w] is row v / vecs_per_row, column chunk
+// v % vecs_per_row.
+template <bool kRowBlock>
+__global__ __launch_bounds__(kThreads) void gather_slice_kernel(
+    ShardTable shards, ShardLayout lay, uint64_t c0, uint32_t vecs_per_row, uint64_t total_vecs,
+    uint4 *__restrict__ dst) {
+  __shared__ const uint16_t *s_tab[OSDP_MAX_SHARDS];
+  if (threadIdx.x < OSDP_MAX_SHARDS)
+    s_tab[threadIdx.x] = static_cast<const uint16_t *>(shards.p[threadIdx.x]);
+  __syncthreads();
+
+  const uint64_t step = static_cast<uint64_t>(gridDim.x) * (kThreads * kUnroll);
+  for (uint64_t base = static_cast<uint64_t>(blockIdx.x) * (kThreads * kUnroll); base < total_vecs;
+       base += step) {
+    uint4 val[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint64_t v = base + u * kThreads + threadIdx.x;
+      if (v < total_vecs) {
+        // total_vecs < 2^32 is checked by the host, so 32-bit division is enough here
+        const uint32_t v32 = static_cast<uint32_t>(v);
+        const uint32_t r = v32 / vecs_per_row;
+        const uint32_t cv = v32 - r * vecs_per_row;
+        uint32_t s;
+        uint64_t off;
+        if (kRowBlock) {
+          s = r / static_cast<uint32_t>(lay.rows_per_shard);
+          off = static_cast<uint64_t>(r - s * lay.rows_per_shard) * lay.O + c0 + cv * 8u;
+        } else {
+          const uint64_t f = static_cast<uint64_t>(r) * lay.O + c0 + cv * 8u;
+          s = static_cast<uint32_t>(f / static_cast<uint64_t>(lay.L));
+          off = f - static_cast<uint64_t>(s) * lay.L;
+        }
+        val[u] = *reinterpret_cast<const uint4 *>(s_tab[s] + off);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint64_t v = base + u * kThreads + threadIdx.x;
+      if (v < total_vecs) dst[v] = val[u];
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_gather(const ShardTable &shards, const ShardLayout &layout, int64_t I, int64_t c0,
+                         int64_t w, void *staging, hipStream_t stream) {
+  const uint64_t vecs_per_row = static_cast<uint64_t>(w) / 8;
+  const uint64_t total = static_cast<uint64_t>(I) * vecs_per_row;
+  if (total == 0) return hipSuccess;
+  uint64_t blocks = (total + kThreads * kUnroll - 1) / (kThreads * kUnroll);
+  if (blocks > 2048) blocks = 2048;
+  dim3 grid(static_cast<unsigned>(blocks)), block(kThreads);
+  if (layout.rows_per_shard > 0) {
+    hipLaunchKernelGGL(gather_slice_kernel<true>, grid, block, 0, stream, shards, layout,
+                       static_cast<uint64_t>(c0), static_cast<uint32_t>(vecs_per_row), total,
+                       static_cast<uint4 *>(staging));
+  } else {
+    hipLaunchKernelGGL(gather_slice_kernel<false>, grid, block, 0, stream, shards, layout,
+                       static_cast<uint64_t>(c0), static_cast<uint32_t>(vecs_per_row), total,
+                       static_cast<uint4 *>(staging));
+  }
+  return hipGetLastError();
+}
+
+}  // namespace osdp

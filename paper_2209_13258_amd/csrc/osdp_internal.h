@@ -1,0 +1,57 @@
+// Internal declarations shared by the host API and the kernel launchers of libosdp.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "osdp.h"
+
+namespace osdp {
+
+// Device pointers of the N shard buffers, passed to kernels by value.
+struct ShardTable {
+  void *p[OSDP_MAX_SHARDS];
+};
+
+// Where the shard-major matrix W / dW [I x O] lives: element (r, c) has flat
+// index f = r*O + c and sits in shard f / L at offset f % L.  When N divides I
+// (rows_per_shard > 0) shard s holds rows [s*rows_per_shard, (s+1)*rows_per_shard).
+struct ShardLayout {
+  int64_t O;               // row length of the full matrix
+  int64_t L;               // elements per shard
+  int32_t N;
+  int32_t rows_per_shard;  // I / N when N divides I, else 0 (general flat map)
+};
+
+enum class Epilogue : int32_t {
+  kBf16RowMajor = 0,   // C -> bf16, row-major with ldc
+  kBf16ShardMajor = 1, // C -> bf16, scattered into the shard-major layout at column offset c0
+  kF32Workspace = 2    // C -> fp32, row-major with ldc (the dX accumulator between slices)
+};
+
+// One GEMM launch: C[M x N] (+)= A[M x K] . B[K x N], bf16 inputs, fp32 accumulate.
+struct GemmProblem {
+  int32_t M, N, K;
+  const void *A;     // a_kcontig: A[m*lda + k], else A[k*lda + m]
+  int64_t lda;
+  bool a_kcontig;
+  const void *B;     // b_kcontig: B[n*ldb + k], else B[k*ldb + n]
+  int64_t ldb;
+  bool b_kcontig;
+  void *C;           // row-major outputs; unused for kBf16ShardMajor
+  int64_t ldc;
+  const float *acc_in;  // fp32 [M x N] with ld_acc added to the product first, or nullptr
+  int64_t ld_acc;
+  Epilogue epilogue;
+  ShardLayout layout;   // kBf16ShardMajor only
+  ShardTable shards;    // kBf16ShardMajor only
+  int64_t c0;           // kBf16ShardMajor only: column offset of C inside the full matrix
+};
+
+// Enqueue on `stream`.  Returns hipSuccess or the launch error.
+hipError_t launch_gemm(const GemmProblem &p, hipStream_t stream);
+
+// Ws[r, c] = W[r, c0 + c] for r < I, c < w; Ws dense row-major [I x w].
+hipError_t launch_gather(const ShardTable &shards, const ShardLayout &layout, int64_t I, int64_t c0,
+                         int64_t w, void *staging, hipStream_t stream);
+
+}  // namespace osdp

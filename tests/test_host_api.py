@@ -1,0 +1,146 @@
+"""Host-side logic of libosdp that needs no GPU: symbols, slice planning, sizes, argument checks."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+import paper_2209_13258_amd as osdp
+
+ROOT = Path(__file__).resolve().parent.parent
+
+
+def test_library_exports_every_declared_symbol():
+    header = (ROOT / "include" / "osdp.h").read_text()
+    declared = re.findall(r"OSDP_API\s+[\w\s\*]+?\b(osdp_\w+)\s*\(", header)
+    assert len(declared) >= 10 and {"osdp_split_linear_fwd", "osdp_split_linear_bwd",
+                                    "osdp_split_linear_gather_slice"} <= set(declared)
+    for name in declared:
+        assert hasattr(osdp.lib, name), f"{name} is declared in osdp.h but not exported"
+    assert set(declared) == set(osdp.EXPORTS)
+
+
+def test_struct_layouts_match_the_header():
+    assert ctypes.sizeof(osdp.binding.osdp_shape) == 32
+    assert ctypes.sizeof(osdp.binding.osdp_plan) == 32
+    assert ctypes.sizeof(osdp.binding.osdp_kernel_stats) == 32
+
+
+@pytest.mark.parametrize("O", [8, 24, 1024, 7680, 32768])
+@pytest.mark.parametrize("k", [0, 1, 2, 3, 4, 6, 8, 16])
+def test_slice_ranges_agree_with_oracle(oracle, O, k):
+    if max(k, 1) > O:
+        return
+    for j in range(max(k, 1)):
+        assert osdp.osdp_slice_range(O, k, j) == oracle.slice_range(O, k, j)
+
+
+@pytest.mark.parametrize("T,I,O,N,k", [(128, 256, 1024, 2, 4), (8192, 1024, 4096, 8, 8), (16384, 10240, 2560, 8, 4),
+                                       (4096, 8192, 32768, 8, 16), (4096, 32768, 8192, 8, 4), (64, 64, 64, 1, 0)])
+def test_workspace_and_peak_staging_follow_the_law(oracle, T, I, O, N, k):
+    """Section 3.3: one live slice is size / granularity; two slots double it; halves restore it."""
+    single = osdp.Plan([k], staging=osdp.OSDP_STAGING_SINGLE)
+    double = osdp.Plan([k], staging=osdp.OSDP_STAGING_DOUBLE)
+    half = osdp.Plan([k], staging=osdp.OSDP_STAGING_HALF)
+    keff = max(k, 1)
+    for is_bwd in (False, True):
+        tot1, peak1 = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, is_bwd, single)
+        tot2, peak2 = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, is_bwd, double)
+        toth, peakh = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, is_bwd, half)
+        assert peak1 == oracle.peak_staging_bytes(I, O, k, 1, 2) == oracle.weight_bytes(I, O, 2) // keff
+        assert peak2 == oracle.peak_staging_bytes(I, O, k, 2, 2)
+        assert peakh == peak1
+        acc1 = T * I * 4 if (is_bwd and keff > 1) else 0
+        assert tot1 == peak1 + acc1 and tot2 == peak2 + acc1
+        assert toth == peakh + (T * I * 4 if is_bwd else 0)  # always at least two sub-slices
+    # AUTO assumes two streams will be given
+    assert osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, False)[1] == (peak2 if keff > 1 else peak1)
+
+
+def test_plan_vector_selects_k():
+    plan = osdp.Plan([2, 1, 4, 4])
+    peaks = [osdp.osdp_split_linear_workspace_bytes(16384, 2560, 10240, 8, 7, False, plan, n)[1] for n in range(4)]
+    full = 2560 * 10240 * 2
+    assert peaks == [full, full, full // 2, full // 2]  # 2 slots of 1/k, one slot when k = 1
+    with pytest.raises(osdp.OsdpError) as e:
+        osdp.osdp_split_linear_workspace_bytes(16384, 2560, 10240, 8, 1, False, plan, 4)
+    assert e.value.status == osdp.binding.OSDP_ERR_INVALID_ARG
+
+
+def test_dp_slices_are_rejected_as_unsupported():
+    plan = osdp.Plan([4], zdp_mask=[0b0111])
+    with pytest.raises(osdp.OsdpError) as e:
+        osdp.osdp_split_linear_workspace_bytes(128, 256, 1024, 2, 4, False, plan)
+    assert e.value.status == osdp.binding.OSDP_ERR_UNSUPPORTED
+    osdp.osdp_split_linear_workspace_bytes(128, 256, 1024, 2, 4, False, osdp.Plan([4], zdp_mask=[0b1111]))
+
+
+@pytest.mark.parametrize("args,status", [
+    ((0, 256, 1024, 2, 4), -1), ((128, 256, 1024, 0, 4), -1), ((128, 256, 1024, 2, -1), -1),
+    ((128, 256, 8, 2, 16), -1),        # k > O
+    ((128, 252, 1024, 2, 4), -2),      # I not a multiple of 8
+    ((128, 256, 1024, 2, 3), -2),      # slice bounds not aligned to 8 columns
+    ((128, 256, 1024, 65, 1), -2),     # more shards than the kernels take
+])
+def test_bad_shapes(args, status):
+    with pytest.raises(osdp.OsdpError) as e:
+        osdp.osdp_split_linear_workspace_bytes(*args, True)
+    assert e.value.status == status
+    assert str(e.value)
+
+
+class _FakeTensor:
+    """Stands in for a device tensor in argument-validation tests: nothing is ever launched."""
+
+    def __init__(self, ptr, shape, stride0=None, elem=2):
+        self._ptr, self.shape, self._s, self._e = ptr, shape, stride0 if stride0 is not None else shape[-1], elem
+
+    def data_ptr(self):
+        return self._ptr
+
+    def stride(self, d):
+        return self._s
+
+    def numel(self):
+        n = 1
+        for s in self.shape:
+            n *= s
+        return n
+
+    def element_size(self):
+        return self._e
+
+
+def test_argument_errors_are_raised_before_anything_is_enqueued():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("uses made-up device addresses: only run where nothing can be launched")
+    T, I, O, N, k = 128, 256, 1024, 2, 4
+    X = _FakeTensor(0x10000, (T, I))
+    Y = _FakeTensor(0x20000, (T, O))
+    shards = [_FakeTensor(0x30000, (I * O // N,)), _FakeTensor(0x40000, (I * O // N,))]
+    plan = osdp.Plan([k], staging=osdp.OSDP_STAGING_SINGLE)
+    need, _ = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, False, plan)
+    cases = [
+        (dict(X=_FakeTensor(0, (T, I))), -1),                       # NULL X
+        (dict(X=_FakeTensor(0x10008, (T, I))), -2),                 # misaligned X
+        (dict(X=_FakeTensor(0x10000, (T, I), stride0=I - 8)), -1),  # ld below the row length
+        (dict(Y=_FakeTensor(0x20000, (T, O), stride0=O + 4)), -2),  # ld not a multiple of 8
+        (dict(shards=[shards[0], _FakeTensor(0, (1,))]), -1),       # NULL shard
+        (dict(ws=_FakeTensor(0x50000, (need - 1,), elem=1)), -3),   # workspace one byte short
+        (dict(ws=_FakeTensor(0x50010, (need,), elem=1)), -2),       # workspace not 256-byte aligned
+    ]
+    for over, status in cases:
+        a = dict(X=X, Y=Y, shards=shards, ws=_FakeTensor(0x50000, (need,), elem=1))
+        a.update(over)
+        with pytest.raises(osdp.OsdpError) as e:
+            osdp.osdp_split_linear_fwd(a["X"], a["shards"], a["Y"], k, a["ws"], plan=plan)
+        assert e.value.status == status, (over, str(e.value))
+    with pytest.raises(osdp.OsdpError) as e:
+        osdp.osdp_split_linear_gather_slice(I, O, k, 4, shards, _FakeTensor(0x50000, (1,)))
+    assert e.value.status == -1  # slice index out of range
+
+
+def test_profile_end_without_begin_is_an_error():
+    with pytest.raises(osdp.OsdpError):
+        osdp.osdp_profile_end()
