@@ -114,7 +114,8 @@ OSDP_API osdp_status osdp_split_linear_gather_slice(const osdp_shape *shape, int
 /* Bytes of workspace a forward (is_bwd = 0) or backward (is_bwd != 0) call
  * needs, and how many of them hold gathered weights at the peak
  * (Section 3.3: size(MatMul)/slice_granularity per live slice).
- * Workspace layout: [staging slots][fp32 dX accumulator T*I, backward with k > 1 only].
+ * Workspace layout: [staging slots][fp32 dX accumulator T*I, backward with more than one dX pass].
+ * With OSDP_STAGING_AUTO the total covers both the one-stream and the two-stream call.
  * Either output pointer may be NULL. Host only. */
 OSDP_API osdp_status osdp_split_linear_workspace_bytes(const osdp_shape *shape, const osdp_plan *plan,
                                               int32_t op_index, int32_t is_bwd, size_t *total,
@@ -137,7 +138,10 @@ OSDP_API osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_p
  * Section 2.2): for j = 0..k-1, dW[:, c0_j:c1_j] = X^T . dY[:, c0_j:c1_j]
  * (written into dw_shards, same shard-major layout as W, overwritten), and
  * dX = sum_j dY[:, c0_j:c1_j] . Ws_j^T, accumulated in fp32 across the slices
- * in ascending j and rounded to bf16 once.
+ * in ascending j and rounded to bf16 once.  Slices that are staged together
+ * (two slots) share one dW launch, and one dX pass when their widths are
+ * multiples of 64; the fp32 partial sum goes through the workspace only
+ * between passes.
  *   dY : device [T x O], lddy >= O       dX : device [T x I], lddx >= I
  *   dw_shards : host array of N device pointers, each L elements
  * dW is bit-identical for every k; dX is too when every slice width is a

@@ -1,0 +1,126 @@
+// Device-side pieces shared by the GEMM kernels of libosdp: parameter block, bf16 rounding,
+// the workgroup -> tile map, accumulator load and the three epilogues.
+#pragma once
+#include "osdp_internal.h"
+
+namespace osdp {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+struct GemmParams {
+  int32_t M, N, K;
+  const uint16_t *A;
+  int64_t lda;
+  const uint16_t *B;
+  int64_t ldb;
+  const uint16_t *B2;  // second B segment (K-contiguous B only): used for k >= k_split; k_split = 0: none
+  int64_t ldb2;
+  int32_t k_split;
+  void *C;
+  int64_t ldc;
+  const float *acc_in;
+  int64_t ld_acc;
+  ShardLayout lay;
+  int64_t c0;
+  ShardTable shards;
+};
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  const uint32_t u = __builtin_bit_cast(uint32_t, f);
+  const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;  // nearest even; carries into the exponent correctly
+  const uint32_t quiet = (u >> 16) | 0x0040u;                        // NaN stays NaN
+  return static_cast<uint16_t>((u & 0x7fffffffu) > 0x7f800000u ? quiet : rounded);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return static_cast<uint32_t>(f32_to_bf16_rne(lo)) | (static_cast<uint32_t>(f32_to_bf16_rne(hi)) << 16);
+}
+
+
+// Tile index of this workgroup.  Workgroups are dealt round-robin to the 8 XCDs, each with its
+// own L2, so consecutive logical tile ids are first mapped onto one XCD; logical ids then walk
+// the tile grid in column-major groups of kGroupM tile rows, which keeps the tiles that run
+// together on an XCD inside a small patch of A row panels and B column panels.
+constexpr int kXcds = 8;
+constexpr int kGroupM = 8;
+
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int *tm, int *tn) {
+  const int nb = gridDim.x, bid = blockIdx.x;
+  const int xcd = bid % kXcds, idx = bid / kXcds;
+  const int base = nb / kXcds, rem = nb % kXcds;
+  const int pid = xcd * base + (xcd < rem ? xcd : rem) + idx;
+  const int per_group = kGroupM * tiles_n;
+  const int group = pid / per_group, in_group = pid - group * per_group;
+  const int first_m = group * kGroupM;
+  const int gm = (tiles_m - first_m) < kGroupM ? (tiles_m - first_m) : kGroupM;
+  *tm = first_m + in_group % gm;
+  *tn = in_group / gm;
+}
+
+// Accumulator layout of one wave: acc[bm][bn][i] is C[m][n] with
+//   m = m_base + 32*bm + l32,  n = n_base + 32*bn + 8*(i/4) + 4*g + i%4
+// (l32 = lane % 32, g = lane / 32): the MFMA is fed B as its first operand, so a lane holds
+// runs of 4 consecutive output columns.  No bounds checks: the caller's tile is full.
+template <int MB, int NB>
+__device__ __forceinline__ void load_acc_tile(const GemmParams &p, f32x16 (&acc)[MB][NB], int m_base, int n_base,
+                                              int l32, int g) {
+#pragma unroll
+  for (int bm = 0; bm < MB; ++bm)
+#pragma unroll
+    for (int bn = 0; bn < NB; ++bn) {
+      const float *src = p.acc_in + static_cast<int64_t>(m_base + bm * 32 + l32) * p.ld_acc + n_base + bn * 32 + 4 * g;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const float4 c = *reinterpret_cast<const float4 *>(src + 8 * q);
+        acc[bm][bn][4 * q + 0] = c.x;
+        acc[bm][bn][4 * q + 1] = c.y;
+        acc[bm][bn][4 * q + 2] = c.z;
+        acc[bm][bn][4 * q + 3] = c.w;
+      }
+    }
+}
+
+template <int MB, int NB, int kEpi>
+__device__ __forceinline__ void store_acc_tile(const GemmParams &p, const f32x16 (&acc)[MB][NB], int m_base, int n_base,
+                                               int l32, int g, uint16_t *const *s_tab) {
+#pragma unroll
+  for (int bm = 0; bm < MB; ++bm)
+#pragma unroll
+    for (int bn = 0; bn < NB; ++bn) {
+      const int m = m_base + bm * 32 + l32;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n_base + bn * 32 + 8 * q + 4 * g;
+        const float c0 = acc[bm][bn][4 * q], c1 = acc[bm][bn][4 * q + 1], c2 = acc[bm][bn][4 * q + 2],
+                    c3 = acc[bm][bn][4 * q + 3];
+        if (kEpi == static_cast<int>(Epilogue::kF32Workspace)) {
+          float4 o = {c0, c1, c2, c3};
+          *reinterpret_cast<float4 *>(static_cast<float *>(p.C) + static_cast<int64_t>(m) * p.ldc + n) = o;
+        } else {
+          uint2 o = {pack_bf16x2(c0, c1), pack_bf16x2(c2, c3)};
+          uint16_t *dst;
+          if (kEpi == static_cast<int>(Epilogue::kBf16RowMajor)) {
+            dst = static_cast<uint16_t *>(p.C) + static_cast<int64_t>(m) * p.ldc + n;
+          } else {
+            int s;
+            int64_t off;
+            if (p.lay.rows_per_shard > 0) {
+              s = m / p.lay.rows_per_shard;
+              off = static_cast<int64_t>(m - s * p.lay.rows_per_shard) * p.lay.O + p.c0 + n;
+            } else {
+              const int64_t f = static_cast<int64_t>(m) * p.lay.O + p.c0 + n;
+              s = static_cast<int>(f / p.lay.L);
+              off = f - static_cast<int64_t>(s) * p.lay.L;
+            }
+            dst = s_tab[s] + off;
+          }
+          *reinterpret_cast<uint2 *>(dst) = o;
+        }
+      }
+    }
+}
+
+}  // namespace
+}  // namespace osdp

@@ -1,0 +1,218 @@
+// Main GEMM kernel of libosdp: tiles stream from global memory straight into LDS
+// (global_load_lds_dwordx4, no staging registers), a ring of LDS stages keeps one or more K
+// blocks in flight behind the MFMAs, and operand fragments are double-buffered in registers.
+//
+// Needs M % BM == 0, N % BN == 0, K % BK == 0; there are no bounds checks.
+//
+// LDS layouts.  A direct-to-LDS load of one wave deposits lane i's 16 bytes at base + 16*i, so a
+// stage is a sequence of 1 KB chunks that cannot be padded; bank conflicts are avoided by
+// permuting which 16 bytes of global memory each lane fetches (an XOR swizzle on the source side):
+//   K-contiguous operand  [rows][BK]   : 16-byte chunk c of row r is stored at chunk c ^ f(r),
+//       f(r) = (r >> 1) & 7 for BK = 64, (r >> 2) & 3 for BK = 32, so that the 16 rows a
+//       ds_read_b128 serves per cycle fall into 16 different 16-byte bank groups.
+//   MN-contiguous operand [BK][rows]   : 64-byte granule w of k-row k is stored at granule
+//       w ^ (k & 3), so that the 4 k-rows one ds_read_b64_tr_b16 group touches are 64 bytes apart.
+#pragma once
+#include "gemm_common.h"
+
+namespace osdp {
+namespace {
+
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+typedef const __attribute__((address_space(1))) void *global_void_ptr;
+typedef __attribute__((ext_vector_type(4))) short dma_s16x4;
+typedef __attribute__((ext_vector_type(8))) short dma_s16x8;
+
+// One wave-level direct-to-LDS load: lane i's 16 bytes at src land at LDS byte address dst + 16*i
+// (dst is wave-uniform and travels in M0).  Written as inline assembly on purpose: the compiler
+// then does not know that LDS is written asynchronously and inserts no waits of its own in front
+// of the fragment reads; the kernel orders these loads itself with wait_vmcnt + barrier.
+__device__ __forceinline__ void dma16(const uint16_t *src, uint32_t dst) {
+  const uint32_t m0 = __builtin_amdgcn_readfirstlane(dst);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(m0), "v"(src) : "memory");
+}
+
+__device__ __forceinline__ uint32_t lds_address(const void *p) {
+  return static_cast<uint32_t>(reinterpret_cast<size_t>((lds_void_ptr)p));
+}
+
+// s_waitcnt vmcnt(n) alone (expcnt and lgkmcnt left at their maxima), gfx9 encoding.
+template <int n>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(n >= 0 && n < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14));
+}
+
+template <bool kKC, int kRows, int kBK, int kWaves>
+struct DmaOperand {
+  static constexpr int kElems = kRows * kBK;             // one stage
+  static constexpr int kLoads = kElems / 512 / kWaves;   // wave-level loads (1 KB each) per wave per stage
+  static_assert(kLoads >= 1 && kLoads * kWaves * 512 == kElems, "stage must divide into 1 KB chunks over the waves");
+  static constexpr int CPR = kBK / 8, RPL = 64 / CPR;    // K-contiguous: 16-byte chunks per row, rows per load
+  static constexpr int VPR = kRows / 8, KPL = 64 / VPR;  // MN-contiguous: 16-byte vectors per k-row, k-rows per load
+  static_assert(kBK == 64 || kBK == 32, "BK is 32 or 64");
+  static_assert(kKC || (kRows >= 128 && kRows <= 512), "MN-contiguous tiles are 128..512 wide");
+
+  static __device__ __forceinline__ int swz_k(int row) { return CPR == 8 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+
+  // Element offset, from the tile origin (mn = 0 of the tile, k = k0), of the 16 bytes this lane fetches in
+  // its wave's load 0.  Load p of the wave adds p * load_stride(); the swizzle terms do not change with p
+  // because a wave's loads are a multiple of 16 rows (4 k-rows) apart.
+  static __device__ __forceinline__ int64_t lane_src(int wave, int lane, int64_t ld) {
+    if (kKC) {
+      const int row = wave * RPL + lane / CPR;
+      const int c = (lane % CPR) ^ swz_k(row);
+      return static_cast<int64_t>(row) * ld + c * 8;
+    } else {
+      const int krow = wave * KPL + lane / VPR;
+      const int pv = lane % VPR;
+      const int lv = (((pv >> 2) ^ (krow & 3)) << 2) | (pv & 3);
+      return static_cast<int64_t>(krow) * ld + lv * 8;
+    }
+  }
+  static __device__ __forceinline__ int64_t load_stride(int64_t ld) {
+    return static_cast<int64_t>(kWaves) * (kKC ? RPL : KPL) * ld;
+  }
+  static __device__ __forceinline__ int64_t block_stride(int64_t ld) { return kKC ? kBK : static_cast<int64_t>(kBK) * ld; }
+
+  // Issues this wave's loads of one K block into the stage at LDS byte address `stage` (the operand's area).
+  static __device__ __forceinline__ void issue(const uint16_t *src, int64_t lstride, uint32_t stage, int wave) {
+#pragma unroll
+    for (int p = 0; p < kLoads; ++p) dma16(src + p * lstride, stage + (wave + kWaves * p) * 1024);
+  }
+
+  // Fragment of the 32-row block at mn0 for K step kk: lane (l32, g) gets k = 16*kk + 8*g + 0..7 of row mn0 + l32.
+  static __device__ __forceinline__ bf16x8 frag(const uint16_t *s, int mn0, int kk, int lane) {
+    if (kKC) {
+      const int r = mn0 + (lane & 31);
+      const int c = (kk * 2 + (lane >> 5)) ^ swz_k(r);
+      return *reinterpret_cast<const bf16x8 *>(s + r * kBK + c * 8);
+    } else {
+      const int i = lane & 15;
+      const int krow = kk * 16 + (lane >> 5) * 8 + (i >> 2);
+      const int mn = mn0 + ((lane >> 4) & 1) * 16 + (i & 3) * 4;
+      const uint16_t *q = s + krow * kRows + (((mn >> 5) ^ (krow & 3)) << 5) + (mn & 31);
+      typedef dma_s16x4 __attribute__((address_space(3))) * lds_s16x4;
+      const dma_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(q));
+      const dma_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(q + 4 * kRows));
+      const dma_s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      return __builtin_bit_cast(bf16x8, both);
+    }
+  }
+};
+
+template <int BM, int BN, int WM, int WN, int BK, int kStages, bool kAK, bool kBK, int kEpi, bool kAccIn>
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(GemmParams p, int tiles_m, int tiles_n) {
+  constexpr int kWaves = (BM / WM) * (BN / WN);
+  constexpr int MB = WM / 32, NB = WN / 32, KS = BK / 16;
+  using OpA = DmaOperand<kAK, BM, BK, kWaves>;
+  using OpB = DmaOperand<kBK, BN, BK, kWaves>;
+  constexpr int kStageElems = OpA::kElems + OpB::kElems;
+  constexpr int kLoadsPerStage = OpA::kLoads + OpB::kLoads;
+  static_assert(kStages >= 2 && kStages <= 4, "2 to 4 LDS stages");
+  static_assert((kStages - 2) * kLoadsPerStage < 64, "in-flight loads must fit the vmcnt counter");
+  extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];
+  __shared__ uint16_t *s_tab[OSDP_MAX_SHARDS];
+
+  const int tid = threadIdx.x;
+  if (kEpi == static_cast<int>(Epilogue::kBf16ShardMajor)) {
+    if (tid < OSDP_MAX_SHARDS) s_tab[tid] = static_cast<uint16_t *>(p.shards.p[tid]);
+  }
+  int tm, tn;
+  tile_of_block(tiles_m, tiles_n, &tm, &tn);
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = (wave / (BN / WN)) * WM, wn = (wave % (BN / WN)) * WN;
+  const int l32 = lane & 31, g = lane >> 5;
+
+  const uint16_t *gA = (kAK ? p.A + static_cast<int64_t>(m0) * p.lda : p.A + m0) + OpA::lane_src(wave, lane, p.lda);
+  const uint16_t *gB = (kBK ? p.B + static_cast<int64_t>(n0) * p.ldb : p.B + n0) + OpB::lane_src(wave, lane, p.ldb);
+  const int64_t lsA = OpA::load_stride(p.lda), lsB = OpB::load_stride(p.ldb);
+  const int64_t bsA = OpA::block_stride(p.lda), bsB = OpB::block_stride(p.ldb);
+  const int nk = p.K / BK;
+
+  f32x16 acc[MB][NB];
+  if (kAccIn) {
+    load_acc_tile<MB, NB>(p, acc, m0 + wm, n0 + wn, l32, g);
+  } else {
+#pragma unroll
+    for (int bm = 0; bm < MB; ++bm)
+#pragma unroll
+      for (int bn = 0; bn < NB; ++bn)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[bm][bn][i] = 0.f;
+  }
+
+  const uint32_t lds_base = lds_address(smem);
+  // K blocks still to be issued from the first B segment; afterwards B continues in the second one
+  int first_seg = (kBK && p.k_split) ? p.k_split / BK : nk;
+  int64_t lsB_cur = lsB;
+  auto issue = [&](int stage) {
+    const uint32_t s = lds_base + stage * (kStageElems * 2);
+    OpA::issue(gA, lsA, s, wave);
+    OpB::issue(gB, lsB_cur, s + OpA::kElems * 2, wave);
+    gA += bsA;
+    gB += bsB;
+    if (kBK && p.k_split && --first_seg == 0) {
+      gB = p.B2 + static_cast<int64_t>(n0) * p.ldb2 + OpB::lane_src(wave, lane, p.ldb2);
+      lsB_cur = OpB::load_stride(p.ldb2);
+    }
+  };
+
+  // Prologue: K blocks 0 .. kStages-2 are put in flight, block 0 is awaited.
+#pragma unroll
+  for (int s = 0; s < kStages - 1; ++s)
+    if (s < nk) issue(s);
+  if (nk >= kStages - 1) wait_vmcnt<(kStages - 2) * kLoadsPerStage>();
+  else wait_vmcnt<0>();
+  __syncthreads();
+
+  bf16x8 fa0[MB], fb0[NB], fa1[MB], fb1[NB];
+#define OSDP_FRAGS(FA, FB, KK)                                                                          \
+  {                                                                                                     \
+    _Pragma("unroll") for (int bm = 0; bm < MB; ++bm) FA[bm] = OpA::frag(cA, wm + bm * 32, KK, lane);   \
+    _Pragma("unroll") for (int bn = 0; bn < NB; ++bn) FB[bn] = OpB::frag(cB, wn + bn * 32, KK, lane);   \
+  }
+#define OSDP_MFMAS(FA, FB)                                                                              \
+  {                                                                                                     \
+    _Pragma("unroll") for (int bm = 0; bm < MB; ++bm)                                                   \
+    _Pragma("unroll") for (int bn = 0; bn < NB; ++bn)                                                   \
+      acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FB[bn], FA[bm], acc[bm][bn], 0, 0, 0);      \
+  }
+  int cur = 0, nxt = kStages - 1;  // stage holding block it; stage that receives block it + kStages - 1
+  for (int it = 0; it < nk; ++it) {
+    const uint16_t *cA = smem + cur * kStageElems;
+    const uint16_t *cB = cA + OpA::kElems;
+    const bool more = it + kStages - 1 < nk;
+    // the stage being refilled was read during block it-1; the barrier that ended it freed the stage
+    if (more) issue(nxt);
+    OSDP_FRAGS(fa0, fb0, 0);
+    OSDP_FRAGS(fa1, fb1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    OSDP_MFMAS(fa0, fb0);
+    if (KS == 4) {
+      __builtin_amdgcn_sched_barrier(0);
+      OSDP_FRAGS(fa0, fb0, 2);
+      __builtin_amdgcn_sched_barrier(0);
+      OSDP_MFMAS(fa1, fb1);
+      __builtin_amdgcn_sched_barrier(0);
+      OSDP_FRAGS(fa1, fb1, 3);
+      __builtin_amdgcn_sched_barrier(0);
+      OSDP_MFMAS(fa0, fb0);
+    }
+    OSDP_MFMAS(fa1, fb1);
+    // block it+1 must have landed before anyone reads it: everything but the younger blocks is awaited
+    if (more) wait_vmcnt<(kStages - 2) * kLoadsPerStage>();
+    else wait_vmcnt<0>();
+    __syncthreads();
+    cur = (cur + 1 == kStages) ? 0 : cur + 1;
+    nxt = (nxt + 1 == kStages) ? 0 : nxt + 1;
+  }
+#undef OSDP_FRAGS
+#undef OSDP_MFMAS
+
+  store_acc_tile<MB, NB, kEpi>(p, acc, m0 + wm, n0 + wn, l32, g, s_tab);
+}
+
+}  // namespace
+}  // namespace osdp

@@ -60,8 +60,11 @@ struct Resolved {
   ShardLayout layout;
   size_t slot_bytes;         // one staging slot, rounded up to kSlotAlign
   size_t peak_staging;       // gathered-weight bytes live at the peak (unrounded)
-  size_t acc_bytes;          // fp32 dX accumulator (backward with more than one sub-slice)
+  size_t acc_bytes;          // fp32 dX accumulator (backward with more than one dX pass)
+  std::vector<Slice> group;  // backward: [first, last) sub-slice indices staged together (c0 = first, c1 = last)
+  std::vector<Slice> pass;   // backward: [first, last) sub-slice indices of each dX pass
 };
+
 
 void slice_bounds(int64_t O, int64_t k, int64_t j, int64_t *c0, int64_t *c1) {
   *c0 = (j * O) / k;
@@ -145,7 +148,21 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
   const size_t slice_bytes = static_cast<size_t>(I) * static_cast<size_t>(wmax) * 2;
   r->slot_bytes = round_up(slice_bytes, kSlotAlign);
   r->peak_staging = slice_bytes * r->slots;
-  r->acc_bytes = (is_bwd && r->sub.size() > 1) ? static_cast<size_t>(T) * static_cast<size_t>(I) * 4 : 0;
+  // Backward processes the sub-slices in groups of `slots` (all staged at once): one dW GEMM per group
+  // and one dX pass per group when the widths allow it, else one dX pass per sub-slice.
+  r->group.clear();
+  r->pass.clear();
+  const int64_t n = static_cast<int64_t>(r->sub.size());
+  for (int64_t g0 = 0; g0 < n; g0 += r->slots) {
+    const int64_t g1 = std::min<int64_t>(n, g0 + r->slots);
+    r->group.push_back({g0, g1});
+    const bool fuse = (g1 - g0 == 2) && gemm_takes_two_segments(T, I, r->sub[g0].c1 - r->sub[g0].c0,
+                                                                    r->sub[g0 + 1].c1 - r->sub[g0 + 1].c0);
+    if (fuse) r->pass.push_back({g0, g1});
+    else
+      for (int64_t j = g0; j < g1; ++j) r->pass.push_back({j, j + 1});
+  }
+  r->acc_bytes = (is_bwd && r->pass.size() > 1) ? static_cast<size_t>(T) * static_cast<size_t>(I) * 4 : 0;
   return OSDP_OK;
 }
 
@@ -318,11 +335,15 @@ osdp_status osdp_slice_range(const osdp_shape *shape, int32_t slice_j, int64_t *
 
 osdp_status osdp_split_linear_workspace_bytes(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index,
                                               int32_t is_bwd, size_t *total, size_t *peak_weight_staging) {
-  Resolved r;
-  osdp_status st = resolve(shape, plan, op_index, /*overlap_possible=*/true, is_bwd != 0, &r);
+  // With OSDP_STAGING_AUTO the call decides between one and two slots by the streams it is given:
+  // the answer covers both (peak staging is that of the two-slot case).
+  Resolved two, one;
+  osdp_status st = resolve(shape, plan, op_index, /*overlap_possible=*/true, is_bwd != 0, &two);
   if (st != OSDP_OK) return st;
-  if (total) *total = workspace_total(r);
-  if (peak_weight_staging) *peak_weight_staging = r.peak_staging;
+  st = resolve(shape, plan, op_index, /*overlap_possible=*/false, is_bwd != 0, &one);
+  if (st != OSDP_OK) return st;
+  if (total) *total = std::max(workspace_total(two), workspace_total(one));
+  if (peak_weight_staging) *peak_weight_staging = two.peak_staging;
   return OSDP_OK;
 }
 
@@ -405,44 +426,57 @@ osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan
   float *acc = reinterpret_cast<float *>(ws + r.slot_bytes * r.slots);
   const int n = static_cast<int>(r.sub.size());
   const bool overlap = two_streams && r.slots == 2 && n > 1;
-  std::vector<hipEvent_t> done(n, nullptr);
+  hipStream_t sg = overlap ? sp : sc;
+  hipEvent_t released = nullptr;  // recorded on the compute stream when a group's last GEMM has been enqueued
   if (overlap) OSDP_HIP(edge(sc, sp));
-  for (int j = 0; j < n; ++j) {
-    const Slice &s = r.sub[j];
-    const int64_t w = s.c1 - s.c0;
-    void *slot = ws + static_cast<size_t>(j % r.slots) * r.slot_bytes;
-    hipStream_t sg = overlap ? sp : sc;
-    if (overlap && j >= 2) OSDP_HIP(hipStreamWaitEvent(sp, done[j - 2], 0));
-    OSDP_HIP(do_gather(r, tab, s, slot, sg));
+  size_t next_pass = 0;
+  for (const Slice &grp : r.group) {
+    const int g0 = static_cast<int>(grp.c0), g1 = static_cast<int>(grp.c1);
+    // gather every slice of the group into its slot once the previous group has released the slots
+    if (overlap && released) OSDP_HIP(hipStreamWaitEvent(sp, released, 0));
+    for (int j = g0; j < g1; ++j)
+      OSDP_HIP(do_gather(r, tab, r.sub[j], ws + static_cast<size_t>(j - g0) * r.slot_bytes, sg));
     hipEvent_t gathered = nullptr;
     if (overlap) {
       OSDP_HIP(g_events.get(&gathered));
       OSDP_HIP(hipEventRecord(gathered, sp));
     }
-    // dW_j = X^T . dY_j needs no weights: it runs while the gather is still in flight
+    // dW of the group's columns = X^T . dY[:, columns] needs no weights: it runs while the gathers are in flight
+    const int64_t gc0 = r.sub[g0].c0, gc1 = r.sub[g1 - 1].c1;
     GemmProblem gw{};
-    gw.M = static_cast<int32_t>(r.I); gw.N = static_cast<int32_t>(w); gw.K = static_cast<int32_t>(r.T);
+    gw.M = static_cast<int32_t>(r.I); gw.N = static_cast<int32_t>(gc1 - gc0); gw.K = static_cast<int32_t>(r.T);
     gw.A = X; gw.lda = ldx; gw.a_kcontig = false;
-    gw.B = static_cast<const uint16_t *>(dY) + s.c0; gw.ldb = lddy; gw.b_kcontig = false;
+    gw.B = static_cast<const uint16_t *>(dY) + gc0; gw.ldb = lddy; gw.b_kcontig = false;
     gw.epilogue = Epilogue::kBf16ShardMajor;
-    gw.layout = r.layout; gw.shards = gtab; gw.c0 = s.c0;
+    gw.layout = r.layout; gw.shards = gtab; gw.c0 = gc0;
     OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DW, gw, sc));
     if (overlap) OSDP_HIP(hipStreamWaitEvent(sc, gathered, 0));
-    // dX (+)= dY_j . Ws_j^T ; the fp32 partial sum is carried in the workspace between slices
-    GemmProblem gx{};
-    gx.M = static_cast<int32_t>(r.T); gx.N = static_cast<int32_t>(r.I); gx.K = static_cast<int32_t>(w);
-    gx.A = static_cast<const uint16_t *>(dY) + s.c0; gx.lda = lddy; gx.a_kcontig = true;
-    gx.B = slot; gx.ldb = w; gx.b_kcontig = true;
-    if (j > 0) { gx.acc_in = acc; gx.ld_acc = r.I; }
-    if (j == n - 1) {
-      gx.C = dX; gx.ldc = lddx; gx.epilogue = Epilogue::kBf16RowMajor;
-    } else {
-      gx.C = acc; gx.ldc = r.I; gx.epilogue = Epilogue::kF32Workspace;
+    // dX (+)= dY[:, columns] . Ws^T ; the fp32 partial sum is carried in the workspace between passes
+    for (; next_pass < r.pass.size() && r.pass[next_pass].c1 <= g1; ++next_pass) {
+      const int j0 = static_cast<int>(r.pass[next_pass].c0), j1 = static_cast<int>(r.pass[next_pass].c1);
+      const Slice &s0 = r.sub[j0];
+      const int64_t w0 = s0.c1 - s0.c0;
+      GemmProblem gx{};
+      gx.M = static_cast<int32_t>(r.T); gx.N = static_cast<int32_t>(r.I);
+      gx.K = static_cast<int32_t>(r.sub[j1 - 1].c1 - s0.c0);
+      gx.A = static_cast<const uint16_t *>(dY) + s0.c0; gx.lda = lddy; gx.a_kcontig = true;
+      gx.B = ws + static_cast<size_t>(j0 - g0) * r.slot_bytes; gx.ldb = w0; gx.b_kcontig = true;
+      if (j1 - j0 == 2) {  // both staged slices in one pass
+        gx.B2 = ws + static_cast<size_t>(j0 + 1 - g0) * r.slot_bytes;
+        gx.ldb2 = r.sub[j0 + 1].c1 - r.sub[j0 + 1].c0;
+        gx.k_split = static_cast<int32_t>(w0);
+      }
+      if (next_pass > 0) { gx.acc_in = acc; gx.ld_acc = r.I; }
+      if (next_pass + 1 == r.pass.size()) {
+        gx.C = dX; gx.ldc = lddx; gx.epilogue = Epilogue::kBf16RowMajor;
+      } else {
+        gx.C = acc; gx.ldc = r.I; gx.epilogue = Epilogue::kF32Workspace;
+      }
+      OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DX, gx, sc));
     }
-    OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DX, gx, sc));
-    if (overlap && j + 2 < n) {
-      OSDP_HIP(g_events.get(&done[j]));
-      OSDP_HIP(hipEventRecord(done[j], sc));
+    if (overlap && g1 < n) {
+      OSDP_HIP(g_events.get(&released));
+      OSDP_HIP(hipEventRecord(released, sc));
     }
   }
   if (overlap) OSDP_HIP(edge(sc, sp));

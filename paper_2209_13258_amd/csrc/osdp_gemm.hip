@@ -10,40 +10,14 @@
 // logical k = 8*g + e sits in lane group g, element e of both operands.  Tile
 // shape therefore never changes a result bit, which is what makes Y and dW of
 // a split operator bit-identical to the unsplit ones.
-#include "osdp_internal.h"
+#include <cstdlib>
+
+#include "gemm_common.h"
+#include "gemm_dma.h"
 
 namespace osdp {
 
 namespace {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-
-struct GemmParams {
-  int32_t M, N, K;
-  const uint16_t *A;
-  int64_t lda;
-  const uint16_t *B;
-  int64_t ldb;
-  void *C;
-  int64_t ldc;
-  const float *acc_in;
-  int64_t ld_acc;
-  ShardLayout lay;
-  int64_t c0;
-  ShardTable shards;
-};
-
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-  uint32_t u = __builtin_bit_cast(uint32_t, f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return static_cast<uint16_t>((u >> 16) | 0x0040u);  // NaN
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return static_cast<uint16_t>(u >> 16);
-}
-
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  return static_cast<uint32_t>(f32_to_bf16_rne(lo)) | (static_cast<uint32_t>(f32_to_bf16_rne(hi)) << 16);
-}
 
 // ---------------------------------------------------------------------------
 // Generic kernel: 128 x 128 x 32 tile, 4 waves of 64 x 64, single LDS buffer,
@@ -202,30 +176,82 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
     }
 }
 
-template <bool kAK, bool kBK>
-hipError_t dispatch_generic(const GemmProblem &q, const GemmParams &p, hipStream_t stream) {
+template <bool kAK, bool kBK, int kEpi, bool kAccIn>
+hipError_t launch_generic(const GemmParams &p, hipStream_t stream) {
   const int tiles = ((p.M + GBM - 1) / GBM) * ((p.N + GBN - 1) / GBN);
-  dim3 grid(tiles), block(256);
-  const bool acc = q.acc_in != nullptr;
-#define OSDP_LAUNCH(EPI, ACC)                                                                          \
-  hipLaunchKernelGGL((gemm_generic_kernel<kAK, kBK, static_cast<int>(EPI), ACC>), grid, block, 0, stream, p)
-  switch (q.epilogue) {
-    case Epilogue::kBf16RowMajor:
-      if (acc) OSDP_LAUNCH(Epilogue::kBf16RowMajor, true); else OSDP_LAUNCH(Epilogue::kBf16RowMajor, false);
-      break;
-    case Epilogue::kBf16ShardMajor:
-      if (acc) return hipErrorInvalidValue;
-      OSDP_LAUNCH(Epilogue::kBf16ShardMajor, false);
-      break;
-    case Epilogue::kF32Workspace:
-      if (acc) OSDP_LAUNCH(Epilogue::kF32Workspace, true); else OSDP_LAUNCH(Epilogue::kF32Workspace, false);
-      break;
-  }
-#undef OSDP_LAUNCH
+  hipLaunchKernelGGL((gemm_generic_kernel<kAK, kBK, kEpi, kAccIn>), dim3(tiles), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 
+template <class Kernel>
+hipError_t allow_lds(Kernel kernel, size_t lds, bool *configured) {
+  if (!*configured) {  // a benign race sets the same attribute twice
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       static_cast<int>(lds));
+    if (e != hipSuccess) return e;
+    *configured = true;
+  }
+  return hipSuccess;
+}
+
+template <int BM, int BN, int WM, int WN, int BK, int kStages, bool kAK, bool kBK, int kEpi, bool kAccIn>
+hipError_t launch_dma(const GemmParams &p, hipStream_t stream) {
+  constexpr int kWaves = (BM / WM) * (BN / WN);
+  constexpr size_t lds = static_cast<size_t>(kStages) * (BM + BN) * BK * sizeof(uint16_t);
+  static_assert(lds + OSDP_MAX_SHARDS * 8 <= 160 * 1024, "tile does not fit the 160 KB of LDS");
+  auto kernel = gemm_dma_kernel<BM, BN, WM, WN, BK, kStages, kAK, kBK, kEpi, kAccIn>;
+  static bool configured = false;
+  hipError_t e = allow_lds(kernel, lds, &configured);
+  if (e != hipSuccess) return e;
+  const int tiles_m = p.M / BM, tiles_n = p.N / BN;
+  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n), dim3(kWaves * 64), lds, stream, p, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
+constexpr int kCUs = 256;
+
+// Estimated cost of covering M x N with BM x BN tiles on 256 CUs: rounds of tiles times the tile's area,
+// with a penalty for the lower MFMA efficiency of smaller tiles.  0 when the tile does not divide the problem.
+double tile_cost(int M, int N, int BM, int BN, double penalty) {
+  if (M % BM || N % BN) return 0.0;
+  const long tiles = static_cast<long>(M / BM) * (N / BN);
+  const long rounds = (tiles + kCUs - 1) / kCUs;
+  return static_cast<double>(rounds) * BM * BN * penalty;
+}
+
+bool fast_path(int M, int N, int K, int k_split) {
+  const char *force = getenv("OSDP_GEMM");  // testing: "generic" forces the bounds-checked kernel
+  return !(force && force[0] == 'g') && M % 128 == 0 && N % 128 == 0 && K % 64 == 0 && k_split % 64 == 0;
+}
+
+template <bool kAK, bool kBK, int kEpi, bool kAccIn>
+hipError_t launch_best(const GemmParams &p, hipStream_t stream) {
+  if (fast_path(p.M, p.N, p.K, p.k_split)) {
+    // penalties: measured throughput of each tile shape relative to 256 x 256 on large problems
+    const double c[4] = {tile_cost(p.M, p.N, 256, 256, 1.0), tile_cost(p.M, p.N, 256, 128, 1.4),
+                         tile_cost(p.M, p.N, 128, 256, 1.4), tile_cost(p.M, p.N, 128, 128, 1.9)};
+    int best = -1;
+    for (int i = 0; i < 4; ++i)
+      if (c[i] > 0.0 && (best < 0 || c[i] < c[best])) best = i;
+    const char *t = getenv("OSDP_TILE");  // testing: force tile 0..3 when it divides the problem
+    if (t && t[0] >= '0' && t[0] <= '3' && c[t[0] - '0'] > 0.0) best = t[0] - '0';
+    switch (best) {
+      case 0: return launch_dma<256, 256, 64, 128, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
+      case 1: return launch_dma<256, 128, 64, 64, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
+      case 2: return launch_dma<128, 256, 64, 64, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
+      case 3: return launch_dma<128, 128, 64, 64, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
+    }
+  }
+  if (p.k_split) return hipErrorInvalidValue;  // the bounds-checked kernel takes one B segment only
+  return launch_generic<kAK, kBK, kEpi, kAccIn>(p, stream);
+}
+
 }  // namespace
+
+bool gemm_takes_two_segments(int64_t M, int64_t N, int64_t k_first, int64_t k_second) {
+  return fast_path(static_cast<int>(M), static_cast<int>(N), static_cast<int>(k_first + k_second), static_cast<int>(k_first)) &&
+         k_first > 0 && k_second > 0;
+}
 
 hipError_t launch_gemm(const GemmProblem &q, hipStream_t stream) {
   if (q.M <= 0 || q.N <= 0 || q.K <= 0) return hipSuccess;
@@ -236,10 +262,21 @@ hipError_t launch_gemm(const GemmProblem &q, hipStream_t stream) {
   p.C = q.C; p.ldc = q.ldc;
   p.acc_in = q.acc_in; p.ld_acc = q.ld_acc;
   p.lay = q.layout; p.c0 = q.c0; p.shards = q.shards;
-  if (q.a_kcontig && !q.b_kcontig) return dispatch_generic<true, false>(q, p, stream);
-  if (!q.a_kcontig && !q.b_kcontig) return dispatch_generic<false, false>(q, p, stream);
-  if (q.a_kcontig && q.b_kcontig) return dispatch_generic<true, true>(q, p, stream);
-  return dispatch_generic<false, true>(q, p, stream);
+  p.B2 = static_cast<const uint16_t *>(q.B2); p.ldb2 = q.ldb2; p.k_split = q.B2 ? q.k_split : 0;
+  if (p.k_split && !(q.a_kcontig && q.b_kcontig)) return hipErrorInvalidValue;
+  constexpr int kRow = static_cast<int>(Epilogue::kBf16RowMajor), kShard = static_cast<int>(Epilogue::kBf16ShardMajor),
+                kF32 = static_cast<int>(Epilogue::kF32Workspace);
+  const bool acc = q.acc_in != nullptr;
+  // The three GEMMs of the split linear layer and the four accumulate forms of dX are the only combinations built.
+  if (q.a_kcontig && !q.b_kcontig && q.epilogue == Epilogue::kBf16RowMajor && !acc)
+    return launch_best<true, false, kRow, false>(p, stream);                       // forward
+  if (!q.a_kcontig && !q.b_kcontig && q.epilogue == Epilogue::kBf16ShardMajor && !acc)
+    return launch_best<false, false, kShard, false>(p, stream);                    // dW
+  if (q.a_kcontig && q.b_kcontig) {                                                // dX
+    if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_best<true, true, kRow, true>(p, stream) : launch_best<true, true, kRow, false>(p, stream);
+    if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_best<true, true, kF32, true>(p, stream) : launch_best<true, true, kF32, false>(p, stream);
+  }
+  return hipErrorInvalidValue;
 }
 
 }  // namespace osdp

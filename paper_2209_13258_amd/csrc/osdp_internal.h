@@ -37,6 +37,11 @@ struct GemmProblem {
   const void *B;     // b_kcontig: B[n*ldb + k], else B[k*ldb + n]
   int64_t ldb;
   bool b_kcontig;
+  // Optional second segment of a K-contiguous B: rows k >= k_split of the product come from
+  // B2[n*ldb2 + (k - k_split)].  Lets dX run over two staged slices in one pass.
+  const void *B2;
+  int64_t ldb2;
+  int32_t k_split;
   void *C;           // row-major outputs; unused for kBf16ShardMajor
   int64_t ldc;
   const float *acc_in;  // fp32 [M x N] with ld_acc added to the product first, or nullptr
@@ -49,6 +54,10 @@ struct GemmProblem {
 
 // Enqueue on `stream`.  Returns hipSuccess or the launch error.
 hipError_t launch_gemm(const GemmProblem &p, hipStream_t stream);
+
+// Whether launch_gemm accepts a two-segment B (B2 / k_split) for an M x N product whose K range is
+// k_first columns from B followed by k_second columns from B2.
+bool gemm_takes_two_segments(int64_t M, int64_t N, int64_t k_first, int64_t k_second);
 
 // Ws[r, c] = W[r, c0 + c] for r < I, c < w; Ws dense row-major [I x w].
 hipError_t launch_gather(const ShardTable &shards, const ShardLayout &layout, int64_t I, int64_t c0,
