@@ -15,9 +15,10 @@ struct GemmParams {
   int64_t lda;
   const uint16_t *B;
   int64_t ldb;
-  const uint16_t *B2;  // second B segment (K-contiguous B only): used for k >= k_split; k_split = 0: none
+  const uint16_t *B2;  // second B segment: K-contiguous B, rows k >= k_split; N-contiguous B, columns n >= n_split
   int64_t ldb2;
-  int32_t k_split;
+  int32_t k_split;     // 0: none
+  int32_t n_split;     // 0: none
   void *C;
   int64_t ldc;
   const float *acc_in;

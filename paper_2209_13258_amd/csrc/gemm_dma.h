@@ -126,9 +126,13 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
   const int l32 = lane & 31, g = lane >> 5;
 
   const uint16_t *gA = (kAK ? p.A + static_cast<int64_t>(m0) * p.lda : p.A + m0) + OpA::lane_src(wave, lane, p.lda);
-  const uint16_t *gB = (kBK ? p.B + static_cast<int64_t>(n0) * p.ldb : p.B + n0) + OpB::lane_src(wave, lane, p.ldb);
-  const int64_t lsA = OpA::load_stride(p.lda), lsB = OpB::load_stride(p.ldb);
-  const int64_t bsA = OpA::block_stride(p.lda), bsB = OpB::block_stride(p.ldb);
+  // an N-contiguous B may come in two column segments (two staged slices): the tile lies in one of them
+  const bool second = !kBK && p.n_split && n0 >= p.n_split;
+  const uint16_t *tileB = kBK ? p.B + static_cast<int64_t>(n0) * p.ldb : (second ? p.B2 + (n0 - p.n_split) : p.B + n0);
+  const int64_t ldb = second ? p.ldb2 : p.ldb;
+  const uint16_t *gB = tileB + OpB::lane_src(wave, lane, ldb);
+  const int64_t lsA = OpA::load_stride(p.lda), lsB = OpB::load_stride(ldb);
+  const int64_t bsA = OpA::block_stride(p.lda), bsB = OpB::block_stride(ldb);
   const int nk = p.K / BK;
 
   f32x16 acc[MB][NB];
@@ -179,11 +183,27 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
     _Pragma("unroll") for (int bn = 0; bn < NB; ++bn)                                                   \
       acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FB[bn], FA[bm], acc[bm][bn], 0, 0, 0);      \
   }
+#ifndef OSDP_ABLATE
+#define OSDP_ABLATE 0  // timing experiments only: 1 no loads in the loop, 4 no fragment reads, 8 no MFMAs, 16 no wait/barrier
+#endif
+#if OSDP_ABLATE & 4
+  {
+    const uint16_t *cA = smem, *cB = smem + OpA::kElems;
+    OSDP_FRAGS(fa0, fb0, 0);
+    OSDP_FRAGS(fa1, fb1, 1);
+  }
+#undef OSDP_FRAGS
+#define OSDP_FRAGS(FA, FB, KK) {}
+#endif
+#if OSDP_ABLATE & 8
+#undef OSDP_MFMAS
+#define OSDP_MFMAS(FA, FB) { _Pragma("unroll") for (int bm = 0; bm < MB; ++bm) _Pragma("unroll") for (int bn = 0; bn < NB; ++bn) { acc[bm][bn][0] += (float)FA[bm][0] + (float)FB[bn][1]; } }
+#endif
   int cur = 0, nxt = kStages - 1;  // stage holding block it; stage that receives block it + kStages - 1
   for (int it = 0; it < nk; ++it) {
     const uint16_t *cA = smem + cur * kStageElems;
     const uint16_t *cB = cA + OpA::kElems;
-    const bool more = it + kStages - 1 < nk;
+    const bool more = (it + kStages - 1 < nk) && !(OSDP_ABLATE & 1);
     // the stage being refilled was read during block it-1; the barrier that ended it freed the stage
     if (more) issue(nxt);
     OSDP_FRAGS(fa0, fb0, 0);
@@ -202,9 +222,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
     }
     OSDP_MFMAS(fa1, fb1);
     // block it+1 must have landed before anyone reads it: everything but the younger blocks is awaited
-    if (more) wait_vmcnt<(kStages - 2) * kLoadsPerStage>();
-    else wait_vmcnt<0>();
-    __syncthreads();
+    if (!(OSDP_ABLATE & 16)) {
+      if (more) wait_vmcnt<(kStages - 2) * kLoadsPerStage>();
+      else wait_vmcnt<0>();
+      __syncthreads();
+    }
     cur = (cur + 1 == kStages) ? 0 : cur + 1;
     nxt = (nxt + 1 == kStages) ? 0 : nxt + 1;
   }

@@ -9,6 +9,7 @@
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <string>
@@ -61,9 +62,15 @@ struct Resolved {
   size_t slot_bytes;         // one staging slot, rounded up to kSlotAlign
   size_t peak_staging;       // gathered-weight bytes live at the peak (unrounded)
   size_t acc_bytes;          // fp32 dX accumulator (backward with more than one dX pass)
-  std::vector<Slice> group;  // backward: [first, last) sub-slice indices staged together (c0 = first, c1 = last)
-  std::vector<Slice> pass;   // backward: [first, last) sub-slice indices of each dX pass
+  // launch plan; every entry is a range [c0, c1) of sub-slice indices
+  std::vector<Slice> fwd;    // forward GEMM launches: one sub-slice, or two staged ones in one launch
+  std::vector<Slice> group;  // backward: sub-slices staged together
+  std::vector<Slice> pass;   // backward: dX passes
+  std::vector<Slice> dw;     // backward: dW launches (dW needs no staged weights, so these may span groups)
 };
+
+// Rough duration of one gather launch in microseconds (read + write of the slice at about 3 TB/s).
+double gather_estimate_us(int64_t I, int64_t w) { return 4.0 * static_cast<double>(I) * static_cast<double>(w) / 3.0e6 + 6.0; }
 
 
 void slice_bounds(int64_t O, int64_t k, int64_t j, int64_t *c0, int64_t *c1) {
@@ -148,20 +155,64 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
   const size_t slice_bytes = static_cast<size_t>(I) * static_cast<size_t>(wmax) * 2;
   r->slot_bytes = round_up(slice_bytes, kSlotAlign);
   r->peak_staging = slice_bytes * r->slots;
-  // Backward processes the sub-slices in groups of `slots` (all staged at once): one dW GEMM per group
-  // and one dX pass per group when the widths allow it, else one dX pass per sub-slice.
+  const int64_t n = static_cast<int64_t>(r->sub.size());
+  auto width = [&](int64_t j) { return r->sub[j].c1 - r->sub[j].c0; };
+  auto span = [&](int64_t a, int64_t b) { return r->sub[b - 1].c1 - r->sub[a].c0; };
+
+  // Forward: with two slots, two staged slices may share one GEMM launch (twice the columns, so fewer
+  // half-empty rounds of tiles) at the price of exposing their gathers; taken when the estimate says it pays.
+  r->fwd.clear();
+  bool pair_fwd = r->slots == 2 && n >= 2;
+  if (pair_fwd) {
+    double t_single = 0.0, t_pair = 0.0;
+    for (int64_t j = 0; j + 1 < n; j += 2) {
+      pair_fwd = pair_fwd && gemm_takes_two_column_segments(T, width(j), width(j + 1), I);
+      if (!pair_fwd) break;
+      t_single += gemm_estimate_us(T, width(j), I) + gemm_estimate_us(T, width(j + 1), I);
+      t_pair += gemm_estimate_us(T, span(j, j + 2), I) + gather_estimate_us(I, width(j)) + gather_estimate_us(I, width(j + 1));
+    }
+    pair_fwd = pair_fwd && t_pair < 0.97 * t_single;
+    if (const char *f = getenv("OSDP_FWD_PAIR")) {  // testing: "0" never pairs, "1" pairs whenever the kernel can
+      if (f[0] == '0') pair_fwd = false;
+      if (f[0] == '1') {
+        pair_fwd = true;
+        for (int64_t j = 0; j + 1 < n; j += 2) pair_fwd = pair_fwd && gemm_takes_two_column_segments(T, width(j), width(j + 1), I);
+      }
+    }
+  }
+  for (int64_t j = 0; j < n;) {
+    const int64_t step = (pair_fwd && j + 1 < n) ? 2 : 1;
+    r->fwd.push_back({j, j + step});
+    j += step;
+  }
+
+  // Backward processes the sub-slices in groups of `slots` (all staged at once): one dX pass per group
+  // when the widths allow it, else one dX pass per sub-slice.
   r->group.clear();
   r->pass.clear();
-  const int64_t n = static_cast<int64_t>(r->sub.size());
   for (int64_t g0 = 0; g0 < n; g0 += r->slots) {
     const int64_t g1 = std::min<int64_t>(n, g0 + r->slots);
     r->group.push_back({g0, g1});
-    const bool fuse = (g1 - g0 == 2) && gemm_takes_two_segments(T, I, r->sub[g0].c1 - r->sub[g0].c0,
-                                                                    r->sub[g0 + 1].c1 - r->sub[g0 + 1].c0);
+    const bool fuse = (g1 - g0 == 2) && gemm_takes_two_segments(T, I, width(g0), width(g0 + 1));
     if (fuse) r->pass.push_back({g0, g1});
     else
       for (int64_t j = g0; j < g1; ++j) r->pass.push_back({j, j + 1});
   }
+  // dW = X^T . dY[:, columns] uses no gathered weight, so its launches need not follow the staging groups:
+  // columns of `per` consecutive sub-slices share a launch, `per` chosen by the estimate.
+  int64_t per = r->slots;
+  {
+    double best = -1.0;
+    for (int64_t cand = r->slots; ; cand *= 2) {
+      if (cand > n) cand = n;
+      double t = 0.0;
+      for (int64_t a = 0; a < n; a += cand) t += gemm_estimate_us(I, span(a, std::min(n, a + cand)), T);
+      if (best < 0.0 || t < 0.97 * best) { best = t; per = cand; }
+      if (cand == n) break;
+    }
+  }
+  r->dw.clear();
+  for (int64_t a = 0; a < n; a += per) r->dw.push_back({a, std::min(n, a + per)});
   r->acc_bytes = (is_bwd && r->pass.size() > 1) ? static_cast<size_t>(T) * static_cast<size_t>(I) * 4 : 0;
   return OSDP_OK;
 }
@@ -380,25 +431,37 @@ osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_plan *plan
   char *ws = static_cast<char *>(workspace);
   const int n = static_cast<int>(r.sub.size());
   const bool overlap = two_streams && r.slots == 2 && n > 1;
-  std::vector<hipEvent_t> done(n, nullptr);
+  hipStream_t sg = overlap ? sp : sc;
+  hipEvent_t slot_free[2] = {nullptr, nullptr};  // recorded on the compute stream after the last GEMM that read the slot
   if (overlap) OSDP_HIP(edge(sc, sp));  // the staging area may still be in use by earlier compute-stream work
-  for (int j = 0; j < n; ++j) {
-    const Slice &s = r.sub[j];
-    void *slot = ws + static_cast<size_t>(j % r.slots) * r.slot_bytes;
-    hipStream_t sg = overlap ? sp : sc;
-    if (overlap && j >= 2) OSDP_HIP(hipStreamWaitEvent(sp, done[j - 2], 0));  // slot released by GEMM j-2
-    OSDP_HIP(do_gather(r, tab, s, slot, sg));
+  for (const Slice &launch : r.fwd) {
+    const int j0 = static_cast<int>(launch.c0), j1 = static_cast<int>(launch.c1);
+    void *slot_of[2] = {nullptr, nullptr};
+    int slot_id[2] = {0, 0};
+    for (int j = j0; j < j1; ++j) {
+      const int s = (j1 - j0 == 2) ? j - j0 : j % r.slots;
+      slot_id[j - j0] = s;
+      slot_of[j - j0] = ws + static_cast<size_t>(s) * r.slot_bytes;
+      if (overlap && slot_free[s]) OSDP_HIP(hipStreamWaitEvent(sp, slot_free[s], 0));  // slot released by its last reader
+      OSDP_HIP(do_gather(r, tab, r.sub[j], slot_of[j - j0], sg));
+    }
     if (overlap) OSDP_HIP(edge(sp, sc));
+    const Slice &s0 = r.sub[j0];
     GemmProblem g{};
-    g.M = static_cast<int32_t>(r.T); g.N = static_cast<int32_t>(s.c1 - s.c0); g.K = static_cast<int32_t>(r.I);
+    g.M = static_cast<int32_t>(r.T); g.N = static_cast<int32_t>(r.sub[j1 - 1].c1 - s0.c0); g.K = static_cast<int32_t>(r.I);
     g.A = X; g.lda = ldx; g.a_kcontig = true;
-    g.B = slot; g.ldb = s.c1 - s.c0; g.b_kcontig = false;
-    g.C = static_cast<uint16_t *>(Y) + s.c0; g.ldc = ldy;
+    g.B = slot_of[0]; g.ldb = s0.c1 - s0.c0; g.b_kcontig = false;
+    if (j1 - j0 == 2) {  // both staged slices in one launch
+      g.B2 = slot_of[1]; g.ldb2 = r.sub[j0 + 1].c1 - r.sub[j0 + 1].c0; g.n_split = static_cast<int32_t>(s0.c1 - s0.c0);
+    }
+    g.C = static_cast<uint16_t *>(Y) + s0.c0; g.ldc = ldy;
     g.epilogue = Epilogue::kBf16RowMajor;
     OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_FWD, g, sc));
-    if (overlap && j + 2 < n) {
-      OSDP_HIP(g_events.get(&done[j]));
-      OSDP_HIP(hipEventRecord(done[j], sc));
+    if (overlap && j1 < n) {
+      hipEvent_t ev;
+      OSDP_HIP(g_events.get(&ev));
+      OSDP_HIP(hipEventRecord(ev, sc));
+      for (int j = j0; j < j1; ++j) slot_free[slot_id[j - j0]] = ev;
     }
   }
   if (overlap) OSDP_HIP(edge(sc, sp));  // later copy-stream work may reuse the workspace
@@ -429,7 +492,7 @@ osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan
   hipStream_t sg = overlap ? sp : sc;
   hipEvent_t released = nullptr;  // recorded on the compute stream when a group's last GEMM has been enqueued
   if (overlap) OSDP_HIP(edge(sc, sp));
-  size_t next_pass = 0;
+  size_t next_pass = 0, next_dw = 0;
   for (const Slice &grp : r.group) {
     const int g0 = static_cast<int>(grp.c0), g1 = static_cast<int>(grp.c1);
     // gather every slice of the group into its slot once the previous group has released the slots
@@ -441,15 +504,17 @@ osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan
       OSDP_HIP(g_events.get(&gathered));
       OSDP_HIP(hipEventRecord(gathered, sp));
     }
-    // dW of the group's columns = X^T . dY[:, columns] needs no weights: it runs while the gathers are in flight
-    const int64_t gc0 = r.sub[g0].c0, gc1 = r.sub[g1 - 1].c1;
-    GemmProblem gw{};
-    gw.M = static_cast<int32_t>(r.I); gw.N = static_cast<int32_t>(gc1 - gc0); gw.K = static_cast<int32_t>(r.T);
-    gw.A = X; gw.lda = ldx; gw.a_kcontig = false;
-    gw.B = static_cast<const uint16_t *>(dY) + gc0; gw.ldb = lddy; gw.b_kcontig = false;
-    gw.epilogue = Epilogue::kBf16ShardMajor;
-    gw.layout = r.layout; gw.shards = gtab; gw.c0 = gc0;
-    OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DW, gw, sc));
+    // dW launches whose columns start in this group: they need no weights and run while the gathers are in flight
+    for (; next_dw < r.dw.size() && r.dw[next_dw].c0 < g1; ++next_dw) {
+      const int64_t gc0 = r.sub[r.dw[next_dw].c0].c0, gc1 = r.sub[r.dw[next_dw].c1 - 1].c1;
+      GemmProblem gw{};
+      gw.M = static_cast<int32_t>(r.I); gw.N = static_cast<int32_t>(gc1 - gc0); gw.K = static_cast<int32_t>(r.T);
+      gw.A = X; gw.lda = ldx; gw.a_kcontig = false;
+      gw.B = static_cast<const uint16_t *>(dY) + gc0; gw.ldb = lddy; gw.b_kcontig = false;
+      gw.epilogue = Epilogue::kBf16ShardMajor;
+      gw.layout = r.layout; gw.shards = gtab; gw.c0 = gc0;
+      OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DW, gw, sc));
+    }
     if (overlap) OSDP_HIP(hipStreamWaitEvent(sc, gathered, 0));
     // dX (+)= dY[:, columns] . Ws^T ; the fp32 partial sum is carried in the workspace between passes
     for (; next_pass < r.pass.size() && r.pass[next_pass].c1 <= g1; ++next_pass) {

@@ -219,22 +219,44 @@ double tile_cost(int M, int N, int BM, int BN, double penalty) {
   return static_cast<double>(rounds) * BM * BN * penalty;
 }
 
-bool fast_path(int M, int N, int K, int k_split) {
+bool fast_path(int M, int N, int K, int k_split, int n_split) {
   const char *force = getenv("OSDP_GEMM");  // testing: "generic" forces the bounds-checked kernel
-  return !(force && force[0] == 'g') && M % 128 == 0 && N % 128 == 0 && K % 64 == 0 && k_split % 64 == 0;
+  return !(force && force[0] == 'g') && M % 128 == 0 && N % 128 == 0 && K % 64 == 0 && k_split % 64 == 0 &&
+         n_split % 128 == 0;
+}
+
+// Tile shapes of the unchecked kernel and their measured cost per unit of tile area relative to 256 x 256.
+struct TileShape {
+  int bm, bn;
+  double penalty;
+};
+constexpr TileShape kTiles[4] = {{256, 256, 1.0}, {256, 128, 1.4}, {128, 256, 1.4}, {128, 128, 1.9}};
+
+// Cheapest tile for M x N; a column split must fall on a tile boundary.  -1: none divides the problem.
+int best_tile(int M, int N, int n_split, double *cost) {
+  int best = -1;
+  double best_cost = 0.0;
+  for (int i = 0; i < 4; ++i) {
+    if (n_split % kTiles[i].bn) continue;
+    const double c = tile_cost(M, N, kTiles[i].bm, kTiles[i].bn, kTiles[i].penalty);
+    if (c > 0.0 && (best < 0 || c < best_cost)) {
+      best = i;
+      best_cost = c;
+    }
+  }
+  if (cost) *cost = best_cost;
+  return best;
 }
 
 template <bool kAK, bool kBK, int kEpi, bool kAccIn>
 hipError_t launch_best(const GemmParams &p, hipStream_t stream) {
-  if (fast_path(p.M, p.N, p.K, p.k_split)) {
-    // penalties: measured throughput of each tile shape relative to 256 x 256 on large problems
-    const double c[4] = {tile_cost(p.M, p.N, 256, 256, 1.0), tile_cost(p.M, p.N, 256, 128, 1.4),
-                         tile_cost(p.M, p.N, 128, 256, 1.4), tile_cost(p.M, p.N, 128, 128, 1.9)};
-    int best = -1;
-    for (int i = 0; i < 4; ++i)
-      if (c[i] > 0.0 && (best < 0 || c[i] < c[best])) best = i;
+  if (fast_path(p.M, p.N, p.K, p.k_split, p.n_split)) {
+    int best = best_tile(p.M, p.N, p.n_split, nullptr);
     const char *t = getenv("OSDP_TILE");  // testing: force tile 0..3 when it divides the problem
-    if (t && t[0] >= '0' && t[0] <= '3' && c[t[0] - '0'] > 0.0) best = t[0] - '0';
+    if (t && t[0] >= '0' && t[0] <= '3') {
+      const TileShape &f = kTiles[t[0] - '0'];
+      if (p.M % f.bm == 0 && p.N % f.bn == 0 && p.n_split % f.bn == 0) best = t[0] - '0';
+    }
     switch (best) {
       case 0: return launch_dma<256, 256, 64, 128, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
       case 1: return launch_dma<256, 128, 64, 64, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
@@ -242,15 +264,32 @@ hipError_t launch_best(const GemmParams &p, hipStream_t stream) {
       case 3: return launch_dma<128, 128, 64, 64, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
     }
   }
-  if (p.k_split) return hipErrorInvalidValue;  // the bounds-checked kernel takes one B segment only
+  if (p.k_split || p.n_split) return hipErrorInvalidValue;  // the bounds-checked kernel takes one B segment only
   return launch_generic<kAK, kBK, kEpi, kAccIn>(p, stream);
 }
 
 }  // namespace
 
 bool gemm_takes_two_segments(int64_t M, int64_t N, int64_t k_first, int64_t k_second) {
-  return fast_path(static_cast<int>(M), static_cast<int>(N), static_cast<int>(k_first + k_second), static_cast<int>(k_first)) &&
+  return fast_path(static_cast<int>(M), static_cast<int>(N), static_cast<int>(k_first + k_second), static_cast<int>(k_first), 0) &&
          k_first > 0 && k_second > 0;
+}
+
+bool gemm_takes_two_column_segments(int64_t M, int64_t n_first, int64_t n_second, int64_t K) {
+  return n_first > 0 && n_second > 0 &&
+         fast_path(static_cast<int>(M), static_cast<int>(n_first + n_second), static_cast<int>(K), 0, static_cast<int>(n_first)) &&
+         best_tile(static_cast<int>(M), static_cast<int>(n_first + n_second), static_cast<int>(n_first), nullptr) >= 0;
+}
+
+double gemm_estimate_us(int64_t M, int64_t N, int64_t K) {
+  // one CU sustains about 4e6 flop per microsecond (1 PFLOP/s over 256 CUs) on 256 x 256 tiles
+  double cost = 0.0;
+  if (fast_path(static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), 0, 0) &&
+      best_tile(static_cast<int>(M), static_cast<int>(N), 0, &cost) >= 0)
+    return cost * 2.0 * static_cast<double>(K) / 4.0e6 + 6.0;
+  const double tiles = static_cast<double>((M + GBM - 1) / GBM) * static_cast<double>((N + GBN - 1) / GBN);
+  const double rounds = static_cast<double>(static_cast<long>((tiles + kCUs - 1) / kCUs));
+  return rounds * GBM * GBN * 4.0 * 2.0 * static_cast<double>(K) / 4.0e6 + 6.0;  // the checked kernel is about 4x slower per tile
 }
 
 hipError_t launch_gemm(const GemmProblem &q, hipStream_t stream) {
@@ -262,8 +301,11 @@ hipError_t launch_gemm(const GemmProblem &q, hipStream_t stream) {
   p.C = q.C; p.ldc = q.ldc;
   p.acc_in = q.acc_in; p.ld_acc = q.ld_acc;
   p.lay = q.layout; p.c0 = q.c0; p.shards = q.shards;
-  p.B2 = static_cast<const uint16_t *>(q.B2); p.ldb2 = q.ldb2; p.k_split = q.B2 ? q.k_split : 0;
+  p.B2 = static_cast<const uint16_t *>(q.B2); p.ldb2 = q.ldb2;
+  p.k_split = q.B2 ? q.k_split : 0; p.n_split = q.B2 ? q.n_split : 0;
   if (p.k_split && !(q.a_kcontig && q.b_kcontig)) return hipErrorInvalidValue;
+  if (p.n_split && !(q.a_kcontig && !q.b_kcontig)) return hipErrorInvalidValue;
+  if (p.k_split && p.n_split) return hipErrorInvalidValue;
   constexpr int kRow = static_cast<int>(Epilogue::kBf16RowMajor), kShard = static_cast<int>(Epilogue::kBf16ShardMajor),
                 kF32 = static_cast<int>(Epilogue::kF32Workspace);
   const bool acc = q.acc_in != nullptr;

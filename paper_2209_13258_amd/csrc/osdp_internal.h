@@ -37,11 +37,13 @@ struct GemmProblem {
   const void *B;     // b_kcontig: B[n*ldb + k], else B[k*ldb + n]
   int64_t ldb;
   bool b_kcontig;
-  // Optional second segment of a K-contiguous B: rows k >= k_split of the product come from
-  // B2[n*ldb2 + (k - k_split)].  Lets dX run over two staged slices in one pass.
+  // Optional second segment of B, so that one launch runs over two staged slices:
+  //   K-contiguous B (dX)     : rows k >= k_split of the product come from B2[n*ldb2 + (k - k_split)];
+  //   N-contiguous B (forward): columns n >= n_split come from B2[k*ldb2 + (n - n_split)].
   const void *B2;
   int64_t ldb2;
   int32_t k_split;
+  int32_t n_split;
   void *C;           // row-major outputs; unused for kBf16ShardMajor
   int64_t ldc;
   const float *acc_in;  // fp32 [M x N] with ld_acc added to the product first, or nullptr
@@ -58,6 +60,13 @@ hipError_t launch_gemm(const GemmProblem &p, hipStream_t stream);
 // Whether launch_gemm accepts a two-segment B (B2 / k_split) for an M x N product whose K range is
 // k_first columns from B followed by k_second columns from B2.
 bool gemm_takes_two_segments(int64_t M, int64_t N, int64_t k_first, int64_t k_second);
+
+// Whether launch_gemm accepts a two-segment N-contiguous B (B2 / n_split): N = n_first + n_second columns.
+bool gemm_takes_two_column_segments(int64_t M, int64_t n_first, int64_t n_second, int64_t K);
+
+// Rough duration in microseconds of one M x N x K GEMM launch (tile rounds over the CUs at the
+// throughput measured for each tile shape); only used to choose between launch groupings.
+double gemm_estimate_us(int64_t M, int64_t N, int64_t K);
 
 // Ws[r, c] = W[r, c0 + c] for r < I, c < w; Ws dense row-major [I x w].
 hipError_t launch_gather(const ShardTable &shards, const ShardLayout &layout, int64_t I, int64_t c0,

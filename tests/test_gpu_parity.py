@@ -94,9 +94,13 @@ def test_shard_padding_is_never_touched(H, oracle):
 
 
 # ------------------------------------------ bit identity across k and modes
+@pytest.mark.parametrize("pair", ["0", "1"])
 @pytest.mark.parametrize("T,I,O,N", [(300, 264, 640, 4), (128, 256, 1024, 2), (1024, 512, 2048, 8)])
-def test_split_is_bit_identical_to_unsplit(H, T, I, O, N):
-    _announce("bit-identity", T, I, O, N)
+def test_split_is_bit_identical_to_unsplit(H, T, I, O, N, pair, monkeypatch):
+    """Every k, staging mode and stream choice; forward both with one launch per slice and with
+    two staged slices per launch (the library's own choice is an estimate, so both are forced here)."""
+    _announce("bit-identity", T, I, O, N, "pair", pair)
+    monkeypatch.setenv("OSDP_FWD_PAIR", pair)
     import paper_2209_13258_amd as osdp
     d = wl.small_case(14, T, I, O, N)
     op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
