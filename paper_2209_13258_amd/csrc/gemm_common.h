@@ -19,6 +19,8 @@ struct GemmParams {
   int64_t ldb2;
   int32_t k_split;     // 0: none
   int32_t n_split;     // 0: none
+  int32_t map_mode;    // tile order experiments: 0 XCD-aware grouped (default), 1 grouped without XCD remap, 2 row-major
+  int32_t group_m;     // tile rows per group (0: default)
   void *C;
   int64_t ldc;
   const float *acc_in;
@@ -43,19 +45,22 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 // Tile index of this workgroup.  Workgroups are dealt round-robin to the 8 XCDs, each with its
 // own L2, so consecutive logical tile ids are first mapped onto one XCD; logical ids then walk
 // the tile grid in column-major groups of kGroupM tile rows, which keeps the tiles that run
-// together on an XCD inside a small patch of A row panels and B column panels.
+// together on an XCD inside a small patch of A row panels and B column panels (4 measured best of 2..16).
 constexpr int kXcds = 8;
-constexpr int kGroupM = 8;
+constexpr int kGroupM = 4;
 
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int *tm, int *tn) {
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int *tm, int *tn, int map_mode = 0, int group_m = 0) {
   const int nb = gridDim.x, bid = blockIdx.x;
   const int xcd = bid % kXcds, idx = bid / kXcds;
   const int base = nb / kXcds, rem = nb % kXcds;
-  const int pid = xcd * base + (xcd < rem ? xcd : rem) + idx;
-  const int per_group = kGroupM * tiles_n;
+  int pid = xcd * base + (xcd < rem ? xcd : rem) + idx;
+  if (map_mode >= 1) pid = bid;
+  if (map_mode == 2) { *tm = pid % tiles_m; *tn = pid / tiles_m; return; }
+  const int kG = group_m > 0 ? group_m : kGroupM;
+  const int per_group = kG * tiles_n;
   const int group = pid / per_group, in_group = pid - group * per_group;
-  const int first_m = group * kGroupM;
-  const int gm = (tiles_m - first_m) < kGroupM ? (tiles_m - first_m) : kGroupM;
+  const int first_m = group * kG;
+  const int gm = (tiles_m - first_m) < kG ? (tiles_m - first_m) : kG;
   *tm = first_m + in_group % gm;
   *tn = in_group / gm;
 }

@@ -119,7 +119,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
     if (tid < OSDP_MAX_SHARDS) s_tab[tid] = static_cast<uint16_t *>(p.shards.p[tid]);
   }
   int tm, tn;
-  tile_of_block(tiles_m, tiles_n, &tm, &tn);
+  tile_of_block(tiles_m, tiles_n, &tm, &tn, p.map_mode, p.group_m);
   const int m0 = tm * BM, n0 = tn * BN;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave / (BN / WN)) * WM, wn = (wave % (BN / WN)) * WN;
@@ -147,91 +147,106 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
         for (int i = 0; i < 16; ++i) acc[bm][bn][i] = 0.f;
   }
 
-  const uint32_t lds_base = lds_address(smem);
-  // K blocks still to be issued from the first B segment; afterwards B continues in the second one
-  int first_seg = (kBK && p.k_split) ? p.k_split / BK : nk;
+  // ---- global -> LDS: the LA + LB wave-level loads of one K block, issued in shares ------------------
+  constexpr int LA = OpA::kLoads, LB = OpB::kLoads, L = LA + LB;
+  // With two stages block it+1 must be complete before the barrier that sits one K step before the end
+  // of block it, so its loads are spread over the K steps before that barrier; with more stages they
+  // are spread over all K steps.
+  constexpr int kIssueSteps = (kStages == 2 && KS > 1) ? KS - 1 : KS;
+  int first_seg = (kBK && p.k_split) ? p.k_split / BK : nk;  // K blocks left in the first B segment
   int64_t lsB_cur = lsB;
-  auto issue = [&](int stage) {
-    const uint32_t s = lds_base + stage * (kStageElems * 2);
-    OpA::issue(gA, lsA, s, wave);
-    OpB::issue(gB, lsB_cur, s + OpA::kElems * 2, wave);
-    gA += bsA;
-    gB += bsB;
-    if (kBK && p.k_split && --first_seg == 0) {
-      gB = p.B2 + static_cast<int64_t>(n0) * p.ldb2 + OpB::lane_src(wave, lane, p.ldb2);
-      lsB_cur = OpB::load_stride(p.ldb2);
+  const uint32_t lds_base = lds_address(smem);
+  // loads [first, last) of the block that gA / gB point at, into `stage`; first / last are compile-time
+  auto issue_range = [&](int stage, int first, int last) {
+    const uint32_t sa = lds_base + stage * (kStageElems * 2);
+    const uint32_t sb = sa + OpA::kElems * 2;
+#pragma unroll
+    for (int i = 0; i < L; ++i) {
+      if (i < first || i >= last) continue;
+      if (i < LA) dma16(gA + i * lsA, sa + (wave + kWaves * i) * 1024);
+      else dma16(gB + (i - LA) * lsB_cur, sb + (wave + kWaves * (i - LA)) * 1024);
+    }
+    if (last == L) {  // block fully issued: move on
+      gA += bsA;
+      gB += bsB;
+      if (kBK && p.k_split && --first_seg == 0) {
+        gB = p.B2 + static_cast<int64_t>(n0) * p.ldb2 + OpB::lane_src(wave, lane, p.ldb2);
+        lsB_cur = OpB::load_stride(p.ldb2);
+      }
     }
   };
 
   // Prologue: K blocks 0 .. kStages-2 are put in flight, block 0 is awaited.
 #pragma unroll
   for (int s = 0; s < kStages - 1; ++s)
-    if (s < nk) issue(s);
-  if (nk >= kStages - 1) wait_vmcnt<(kStages - 2) * kLoadsPerStage>();
+    if (s < nk) issue_range(s, 0, L);
+  if (nk >= kStages - 1) wait_vmcnt<(kStages - 2) * L>();
   else wait_vmcnt<0>();
-  __syncthreads();
+  __builtin_amdgcn_s_barrier();
 
-  bf16x8 fa0[MB], fb0[NB], fa1[MB], fb1[NB];
-#define OSDP_FRAGS(FA, FB, KK)                                                                          \
-  {                                                                                                     \
-    _Pragma("unroll") for (int bm = 0; bm < MB; ++bm) FA[bm] = OpA::frag(cA, wm + bm * 32, KK, lane);   \
-    _Pragma("unroll") for (int bn = 0; bn < NB; ++bn) FB[bn] = OpB::frag(cB, wn + bn * 32, KK, lane);   \
-  }
-#define OSDP_MFMAS(FA, FB)                                                                              \
-  {                                                                                                     \
-    _Pragma("unroll") for (int bm = 0; bm < MB; ++bm)                                                   \
-    _Pragma("unroll") for (int bn = 0; bn < NB; ++bn)                                                   \
-      acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FB[bn], FA[bm], acc[bm][bn], 0, 0, 0);      \
-  }
 #ifndef OSDP_ABLATE
 #define OSDP_ABLATE 0  // timing experiments only: 1 no loads in the loop, 4 no fragment reads, 8 no MFMAs, 16 no wait/barrier
 #endif
-#if OSDP_ABLATE & 4
-  {
-    const uint16_t *cA = smem, *cB = smem + OpA::kElems;
-    OSDP_FRAGS(fa0, fb0, 0);
-    OSDP_FRAGS(fa1, fb1, 1);
-  }
-#undef OSDP_FRAGS
-#define OSDP_FRAGS(FA, FB, KK) {}
-#endif
-#if OSDP_ABLATE & 8
-#undef OSDP_MFMAS
-#define OSDP_MFMAS(FA, FB) { _Pragma("unroll") for (int bm = 0; bm < MB; ++bm) _Pragma("unroll") for (int bn = 0; bn < NB; ++bn) { acc[bm][bn][0] += (float)FA[bm][0] + (float)FB[bn][1]; } }
-#endif
-  int cur = 0, nxt = kStages - 1;  // stage holding block it; stage that receives block it + kStages - 1
-  for (int it = 0; it < nk; ++it) {
-    const uint16_t *cA = smem + cur * kStageElems;
+  bf16x8 fa[2][MB], fb[2][NB];
+  auto frags = [&](int stage, int kk, int buf) {
+    const uint16_t *cA = smem + stage * kStageElems;
     const uint16_t *cB = cA + OpA::kElems;
+#pragma unroll
+    for (int bm = 0; bm < MB; ++bm) fa[buf][bm] = OpA::frag(cA, wm + bm * 32, kk, lane);
+#pragma unroll
+    for (int bn = 0; bn < NB; ++bn) fb[buf][bn] = OpB::frag(cB, wn + bn * 32, kk, lane);
+  };
+  auto mfmas = [&](int buf) {
+#pragma unroll
+    for (int bm = 0; bm < MB; ++bm)
+#pragma unroll
+      for (int bn = 0; bn < NB; ++bn) {
+#if OSDP_ABLATE & 8
+        acc[bm][bn][0] += static_cast<float>(fa[buf][bm][0]) + static_cast<float>(fb[buf][bn][1]);
+#else
+        acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][bn], fa[buf][bm], acc[bm][bn], 0, 0, 0);
+#endif
+      }
+  };
+
+  // Steady state.  Per K block `it` (stage cur) and K step kk:
+  //   - the fragments of step kk+1 are read from LDS while the MFMAs of step kk run;
+  //   - a share of the loads of block it+kStages-1 goes out (stage nxt, freed by the previous barrier);
+  //   - after the MFMAs of the step before the last, every wave has all fragments of block it in
+  //     registers: block it+1 is awaited and the workgroup barrier is taken there, so that the last
+  //     step's MFMAs cover the first fragment reads of block it+1.
+  static_assert(KS == 2 || KS == 4, "K block of 32 or 64");
+  frags(0, 0, 0);
+  if (OSDP_ABLATE & 4) frags(0, 1, 1);
+  int cur = 0, nxt = kStages - 1;
+  for (int it = 0; it < nk; ++it) {
     const bool more = (it + kStages - 1 < nk) && !(OSDP_ABLATE & 1);
-    // the stage being refilled was read during block it-1; the barrier that ended it freed the stage
-    if (more) issue(nxt);
-    OSDP_FRAGS(fa0, fb0, 0);
-    OSDP_FRAGS(fa1, fb1, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    OSDP_MFMAS(fa0, fb0);
-    if (KS == 4) {
+    const bool follows = it + 1 < nk;
+    const int next_stage = (cur + 1 == kStages) ? 0 : cur + 1;
+#pragma unroll
+    for (int kk = 0; kk < KS; ++kk) {
+      if (!(OSDP_ABLATE & 4)) {
+        if (kk + 1 < KS) frags(cur, kk + 1, (kk + 1) & 1);
+        else if (follows) frags(next_stage, 0, 0);
+      }
+      if (more && kk < kIssueSteps) issue_range(nxt, kk * L / kIssueSteps, (kk + 1) * L / kIssueSteps);
       __builtin_amdgcn_sched_barrier(0);
-      OSDP_FRAGS(fa0, fb0, 2);
+      mfmas(kk & 1);
       __builtin_amdgcn_sched_barrier(0);
-      OSDP_MFMAS(fa1, fb1);
-      __builtin_amdgcn_sched_barrier(0);
-      OSDP_FRAGS(fa1, fb1, 3);
-      __builtin_amdgcn_sched_barrier(0);
-      OSDP_MFMAS(fa0, fb0);
+      if (kk == KS - 2 && !(OSDP_ABLATE & 16)) {
+        // loads issued after the last load of block it+1: the full blocks it+2 .. it+kStages-2 and the
+        // shares of block it+kStages-1 issued so far in this iteration
+        constexpr int kYounger = (kStages >= 3) ? (kStages - 3) * L + (KS - 1) * L / kIssueSteps : 0;
+        if (more) wait_vmcnt<kYounger>();
+        else wait_vmcnt<0>();
+        __builtin_amdgcn_s_waitcnt((15) | (7 << 4) | (0 << 8) | (3 << 14));  // lgkmcnt(0): this wave's LDS reads are done
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-    OSDP_MFMAS(fa1, fb1);
-    // block it+1 must have landed before anyone reads it: everything but the younger blocks is awaited
-    if (!(OSDP_ABLATE & 16)) {
-      if (more) wait_vmcnt<(kStages - 2) * kLoadsPerStage>();
-      else wait_vmcnt<0>();
-      __syncthreads();
-    }
-    cur = (cur + 1 == kStages) ? 0 : cur + 1;
+    cur = next_stage;
     nxt = (nxt + 1 == kStages) ? 0 : nxt + 1;
   }
-#undef OSDP_FRAGS
-#undef OSDP_MFMAS
 
   store_acc_tile<MB, NB, kEpi>(p, acc, m0 + wm, n0 + wn, l32, g, s_tab);
 }

@@ -257,6 +257,10 @@ hipError_t launch_best(const GemmParams &p, hipStream_t stream) {
       const TileShape &f = kTiles[t[0] - '0'];
       if (p.M % f.bm == 0 && p.N % f.bn == 0 && p.n_split % f.bn == 0) best = t[0] - '0';
     }
+    const char *st = getenv("OSDP_STAGES");  // testing: "4" = K block 32 with 4 LDS stages, "3" = 3 stages
+    if (best == 0 && st && st[0] == '4') return launch_dma<256, 256, 64, 128, 32, 4, kAK, kBK, kEpi, kAccIn>(p, stream);
+    if (best == 0 && st && st[0] == 'w') return launch_dma<256, 256, 128, 128, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
+    if (best == 0 && st && st[0] == '3') return launch_dma<256, 256, 64, 128, 32, 3, kAK, kBK, kEpi, kAccIn>(p, stream);
     switch (best) {
       case 0: return launch_dma<256, 256, 64, 128, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
       case 1: return launch_dma<256, 128, 64, 64, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
@@ -303,6 +307,9 @@ hipError_t launch_gemm(const GemmProblem &q, hipStream_t stream) {
   p.lay = q.layout; p.c0 = q.c0; p.shards = q.shards;
   p.B2 = static_cast<const uint16_t *>(q.B2); p.ldb2 = q.ldb2;
   p.k_split = q.B2 ? q.k_split : 0; p.n_split = q.B2 ? q.n_split : 0;
+  p.map_mode = 0; p.group_m = 0;
+  if (const char *m = getenv("OSDP_MAP")) p.map_mode = m[0] - '0';       // tile-order experiments
+  if (const char *m = getenv("OSDP_GROUP_M")) p.group_m = atoi(m);
   if (p.k_split && !(q.a_kcontig && q.b_kcontig)) return hipErrorInvalidValue;
   if (p.n_split && !(q.a_kcontig && !q.b_kcontig)) return hipErrorInvalidValue;
   if (p.k_split && p.n_split) return hipErrorInvalidValue;

@@ -95,7 +95,8 @@ def test_shard_padding_is_never_touched(H, oracle):
 
 # ------------------------------------------ bit identity across k and modes
 @pytest.mark.parametrize("pair", ["0", "1"])
-@pytest.mark.parametrize("T,I,O,N", [(300, 264, 640, 4), (128, 256, 1024, 2), (1024, 512, 2048, 8)])
+@pytest.mark.parametrize("T,I,O,N", [(300, 264, 640, 4), (128, 256, 1024, 2), (1024, 512, 2048, 8),
+                                     (256, 256, 640, 4)])  # last: k=1 takes the unchecked kernel, k=2 (320 columns) the checked one
 def test_split_is_bit_identical_to_unsplit(H, T, I, O, N, pair, monkeypatch):
     """Every k, staging mode and stream choice; forward both with one launch per slice and with
     two staged slices per launch (the library's own choice is an estimate, so both are forced here)."""
