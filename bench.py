@@ -127,12 +127,14 @@ def cpu_baseline(w, target_s=15.0):
         return fl, t
 
     oracle.build()
-    fl, t = one_pass(16)                      # calibration pass
-    rate = fl / max(t, 1e-9)
     per_token = sum(6 * op.I * op.O for op in w.ops)
-    Ts = int(min(w.T, max(16, target_s * rate / per_token)))
-    Ts = max(16, Ts // 16 * 16)
-    fl, t = one_pass(Ts)
+    Ts, fl, t = 16, 0, 0.0
+    for _ in range(3):                        # grow the sample until one pass takes about target_s
+        fl, t = one_pass(Ts)
+        if t >= 0.5 * target_s or Ts >= w.T:
+            break
+        rate = fl / max(t, 1e-9)
+        Ts = int(min(w.T, max(2 * Ts, target_s * rate / per_token))) // 16 * 16
     return {"value": round(fl / t / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.threads(), "kind": "oracle",
             "sample": f"first layer of the workload with T'={Ts} of {w.T} tokens (flops are linear in T), "
                       f"split route fwd+bwd, {t:.1f} s of CPU work"}

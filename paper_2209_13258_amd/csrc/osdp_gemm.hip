@@ -230,7 +230,8 @@ struct TileShape {
   int bm, bn;
   double penalty;
 };
-constexpr TileShape kTiles[4] = {{256, 256, 1.0}, {256, 128, 1.4}, {128, 256, 1.4}, {128, 128, 1.9}};
+// (8192^3 on MI355X: 256x256 K64 1.15 PFLOP/s; 256x128 and 128x256 with K32, two workgroups per CU, 1.02; 128x128 K64 0.97)
+constexpr TileShape kTiles[4] = {{256, 256, 1.0}, {256, 128, 1.12}, {128, 256, 1.12}, {128, 128, 1.18}};
 
 // Cheapest tile for M x N; a column split must fall on a tile boundary.  -1: none divides the problem.
 int best_tile(int M, int N, int n_split, double *cost) {
@@ -257,14 +258,10 @@ hipError_t launch_best(const GemmParams &p, hipStream_t stream) {
       const TileShape &f = kTiles[t[0] - '0'];
       if (p.M % f.bm == 0 && p.N % f.bn == 0 && p.n_split % f.bn == 0) best = t[0] - '0';
     }
-    const char *st = getenv("OSDP_STAGES");  // testing: "4" = K block 32 with 4 LDS stages, "3" = 3 stages
-    if (best == 0 && st && st[0] == '4') return launch_dma<256, 256, 64, 128, 32, 4, kAK, kBK, kEpi, kAccIn>(p, stream);
-    if (best == 0 && st && st[0] == 'w') return launch_dma<256, 256, 128, 128, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
-    if (best == 0 && st && st[0] == '3') return launch_dma<256, 256, 64, 128, 32, 3, kAK, kBK, kEpi, kAccIn>(p, stream);
     switch (best) {
       case 0: return launch_dma<256, 256, 64, 128, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
-      case 1: return launch_dma<256, 128, 64, 64, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
-      case 2: return launch_dma<128, 256, 64, 64, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
+      case 1: return launch_dma<256, 128, 64, 64, 32, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
+      case 2: return launch_dma<128, 256, 64, 64, 32, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
       case 3: return launch_dma<128, 128, 64, 64, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
     }
   }
