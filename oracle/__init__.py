@@ -39,8 +39,11 @@ def build(force: bool = False) -> Path:
 def _load():
     global _lib
     if _lib is None:
-        build()
-        lib = ctypes.CDLL(str(_LIB))
+        # OSDP_ORACLE_LIB: another build of osdp_oracle.c (the mutation test loads deliberately broken ones)
+        override = os.environ.get("OSDP_ORACLE_LIB")
+        if not override:
+            build()
+        lib = ctypes.CDLL(override or str(_LIB))
         lib.osdp_oracle_bf16_to_f64.restype = ctypes.c_double
         lib.osdp_oracle_bf16_to_f64.argtypes = [ctypes.c_uint16]
         lib.osdp_oracle_threads.restype = ctypes.c_int
