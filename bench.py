@@ -21,6 +21,15 @@ import time
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (vendor figure: 256 CUs x 2.4 GHz x 4096 flop/clk/CU)
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 
+# HBM-side traffic per launch (bytes, FETCH_SIZE + WRITE_SIZE of two rocprofv3 --pmc runs of this file, each scaled
+# by what the same counter read for the gather kernel, a plain copy of known size; all tile shapes of a kernel kind
+# together).  Source: profiles/hbm_traffic_config2_config3.md.  Only valid for the default plan of the workload.
+KIB = 1024
+MEASURED_TRAFFIC = {
+    2: {"gemm_fwd": (26845 + 6843) * KIB, "gemm_dw": (96630 + 4096) * KIB, "gemm_dx": (48358 + 32460) * KIB},
+    3: {"gemm_fwd": (393507 + 53070) * KIB, "gemm_dw": (491078 + 13068) * KIB, "gemm_dx": (427447 + 116504) * KIB},
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -165,7 +174,10 @@ def main():
     gemms = {k: v for k, v in kernels.items() if k.startswith("gemm")}
     dom = max(gemms, key=lambda k: gemms[k]["total_ms"])
     roofline = {"bound": "mfma", "kernel": dom, "achieved": gemms[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(gemms[dom]["tflops"] / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "unit": "TFLOP/s", "frac": round(gemms[dom]["tflops"] / PEAK_BF16_TFLOPS, 4),
+                "traffic": (MEASURED_TRAFFIC.get(a.config, {}).get(dom)
+                            if (a.k is None and a.staging == "auto" and not a.serial) else None),
+                "algorithmic_bytes": round(stats[dom]["bytes"] / stats[dom]["launches"]),
                 "avg_launch_us": gemms[dom]["avg_us"], "launches": gemms[dom]["launches"]}
 
     out = {

@@ -60,9 +60,7 @@ class OsdpError(RuntimeError):
 
 
 def _load() -> ctypes.CDLL:
-    import os
-    from pathlib import Path
-    path = Path(os.environ.get("OSDP_LIB", _build.LIB))  # OSDP_LIB: load another build of the same library
+    path = _build.LIB
     if not path.exists():
         raise ImportError(
             f"{path} is missing: build it first (python -m paper_2209_13258_amd.build); "

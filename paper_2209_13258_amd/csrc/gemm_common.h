@@ -19,8 +19,6 @@ struct GemmParams {
   int64_t ldb2;
   int32_t k_split;     // 0: none
   int32_t n_split;     // 0: none
-  int32_t map_mode;    // tile order experiments: 0 XCD-aware grouped (default), 1 grouped without XCD remap, 2 row-major
-  int32_t group_m;     // tile rows per group (0: default)
   void *C;
   int64_t ldc;
   const float *acc_in;
@@ -49,18 +47,15 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 constexpr int kXcds = 8;
 constexpr int kGroupM = 4;
 
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int *tm, int *tn, int map_mode = 0, int group_m = 0) {
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int *tm, int *tn) {
   const int nb = gridDim.x, bid = blockIdx.x;
   const int xcd = bid % kXcds, idx = bid / kXcds;
   const int base = nb / kXcds, rem = nb % kXcds;
-  int pid = xcd * base + (xcd < rem ? xcd : rem) + idx;
-  if (map_mode >= 1) pid = bid;
-  if (map_mode == 2) { *tm = pid % tiles_m; *tn = pid / tiles_m; return; }
-  const int kG = group_m > 0 ? group_m : kGroupM;
-  const int per_group = kG * tiles_n;
+  const int pid = xcd * base + (xcd < rem ? xcd : rem) + idx;
+  const int per_group = kGroupM * tiles_n;
   const int group = pid / per_group, in_group = pid - group * per_group;
-  const int first_m = group * kG;
-  const int gm = (tiles_m - first_m) < kG ? (tiles_m - first_m) : kG;
+  const int first_m = group * kGroupM;
+  const int gm = (tiles_m - first_m) < kGroupM ? (tiles_m - first_m) : kGroupM;
   *tm = first_m + in_group % gm;
   *tn = in_group / gm;
 }

@@ -119,7 +119,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
     if (tid < OSDP_MAX_SHARDS) s_tab[tid] = static_cast<uint16_t *>(p.shards.p[tid]);
   }
   int tm, tn;
-  tile_of_block(tiles_m, tiles_n, &tm, &tn, p.map_mode, p.group_m);
+  tile_of_block(tiles_m, tiles_n, &tm, &tn);
   const int m0 = tm * BM, n0 = tn * BN;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave / (BN / WN)) * WM, wn = (wave % (BN / WN)) * WN;
@@ -184,9 +184,6 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
   else wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
 
-#ifndef OSDP_ABLATE
-#define OSDP_ABLATE 0  // timing experiments only: 1 no loads in the loop, 4 no fragment reads, 8 no MFMAs, 16 no wait/barrier
-#endif
   bf16x8 fa[2][MB], fb[2][NB];
   auto frags = [&](int stage, int kk, int buf) {
     const uint16_t *cA = smem + stage * kStageElems;
@@ -201,11 +198,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
     for (int bm = 0; bm < MB; ++bm)
 #pragma unroll
       for (int bn = 0; bn < NB; ++bn) {
-#if OSDP_ABLATE & 8
-        acc[bm][bn][0] += static_cast<float>(fa[buf][bm][0]) + static_cast<float>(fb[buf][bn][1]);
-#else
         acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][bn], fa[buf][bm], acc[bm][bn], 0, 0, 0);
-#endif
       }
   };
 
@@ -217,23 +210,20 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
   //     step's MFMAs cover the first fragment reads of block it+1.
   static_assert(KS == 2 || KS == 4, "K block of 32 or 64");
   frags(0, 0, 0);
-  if (OSDP_ABLATE & 4) frags(0, 1, 1);
   int cur = 0, nxt = kStages - 1;
   for (int it = 0; it < nk; ++it) {
-    const bool more = (it + kStages - 1 < nk) && !(OSDP_ABLATE & 1);
+    const bool more = it + kStages - 1 < nk;
     const bool follows = it + 1 < nk;
     const int next_stage = (cur + 1 == kStages) ? 0 : cur + 1;
 #pragma unroll
     for (int kk = 0; kk < KS; ++kk) {
-      if (!(OSDP_ABLATE & 4)) {
-        if (kk + 1 < KS) frags(cur, kk + 1, (kk + 1) & 1);
-        else if (follows) frags(next_stage, 0, 0);
-      }
+      if (kk + 1 < KS) frags(cur, kk + 1, (kk + 1) & 1);
+      else if (follows) frags(next_stage, 0, 0);
       if (more && kk < kIssueSteps) issue_range(nxt, kk * L / kIssueSteps, (kk + 1) * L / kIssueSteps);
       __builtin_amdgcn_sched_barrier(0);
       mfmas(kk & 1);
       __builtin_amdgcn_sched_barrier(0);
-      if (kk == KS - 2 && !(OSDP_ABLATE & 16)) {
+      if (kk == KS - 2) {
         // loads issued after the last load of block it+1: the full blocks it+2 .. it+kStages-2 and the
         // shares of block it+kStages-1 issued so far in this iteration
         constexpr int kYounger = (kStages >= 3) ? (kStages - 3) * L + (KS - 1) * L / kIssueSteps : 0;

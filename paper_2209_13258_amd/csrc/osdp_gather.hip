@@ -6,8 +6,6 @@
 // start at flat index r*O + c0 of the shard-major matrix.  The kernel is a
 // pure 16-byte-vector copy and is bound by HBM bandwidth: it reads I*w*2
 // bytes and writes I*w*2 bytes.
-#include <cstdlib>
-
 #include "osdp_internal.h"
 
 namespace osdp {
@@ -80,17 +78,12 @@ hipError_t launch_gather(const ShardTable &shards, const ShardLayout &layout, in
   if (total == 0) return hipSuccess;
   // measured on MI355X: 8 vectors per thread are about twice as fast on slices up to ~32 MiB (few, long-lived
   // blocks), 4 vectors per thread with a wide grid reach 5.2 TB/s (read + write) on larger ones
-  unsigned max_blocks = 8192;
-  int unroll = (total * 16 <= (32ull << 20)) ? 8 : 4;
-  if (const char *e = getenv("OSDP_GATHER_BLOCKS")) max_blocks = static_cast<unsigned>(atoi(e));  // tuning hooks
-  if (const char *e = getenv("OSDP_GATHER_UNROLL")) unroll = atoi(e);
+  const unsigned max_blocks = 8192;
+  const int unroll = (total * 16 <= (32ull << 20)) ? 8 : 4;
   const bool rb = layout.rows_per_shard > 0;
   if (unroll == 8) {
     if (rb) launch_one<true, 8>(shards, layout, c0, vecs_per_row, total, max_blocks, staging, stream);
     else launch_one<false, 8>(shards, layout, c0, vecs_per_row, total, max_blocks, staging, stream);
-  } else if (unroll == 2) {
-    if (rb) launch_one<true, 2>(shards, layout, c0, vecs_per_row, total, max_blocks, staging, stream);
-    else launch_one<false, 2>(shards, layout, c0, vecs_per_row, total, max_blocks, staging, stream);
   } else {
     if (rb) launch_one<true, 4>(shards, layout, c0, vecs_per_row, total, max_blocks, staging, stream);
     else launch_one<false, 4>(shards, layout, c0, vecs_per_row, total, max_blocks, staging, stream);

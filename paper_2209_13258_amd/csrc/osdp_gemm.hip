@@ -304,9 +304,6 @@ hipError_t launch_gemm(const GemmProblem &q, hipStream_t stream) {
   p.lay = q.layout; p.c0 = q.c0; p.shards = q.shards;
   p.B2 = static_cast<const uint16_t *>(q.B2); p.ldb2 = q.ldb2;
   p.k_split = q.B2 ? q.k_split : 0; p.n_split = q.B2 ? q.n_split : 0;
-  p.map_mode = 0; p.group_m = 0;
-  if (const char *m = getenv("OSDP_MAP")) p.map_mode = m[0] - '0';       // tile-order experiments
-  if (const char *m = getenv("OSDP_GROUP_M")) p.group_m = atoi(m);
   if (p.k_split && !(q.a_kcontig && q.b_kcontig)) return hipErrorInvalidValue;
   if (p.n_split && !(q.a_kcontig && !q.b_kcontig)) return hipErrorInvalidValue;
   if (p.k_split && p.n_split) return hipErrorInvalidValue;
