@@ -75,6 +75,16 @@ def _load():
         lib.osdp_oracle_split_fwd.argtypes = [_i64] * 5 + [_p] * 4
         lib.osdp_oracle_split_bwd.restype = ctypes.c_int
         lib.osdp_oracle_split_bwd.argtypes = [_i64] * 5 + [_p] * 6
+        lib.osdp_oracle_row_slice_range.restype = None
+        lib.osdp_oracle_row_slice_range.argtypes = [_i64, _i64, _i64, _p, _p]
+        lib.osdp_oracle_gather_row_slice.restype = None
+        lib.osdp_oracle_gather_row_slice.argtypes = [_i64] * 5 + [_p, _p]
+        lib.osdp_oracle_peak_staging_bytes_rows.restype = _i64
+        lib.osdp_oracle_peak_staging_bytes_rows.argtypes = [_i64] * 5
+        lib.osdp_oracle_split_fwd_rows.restype = ctypes.c_int
+        lib.osdp_oracle_split_fwd_rows.argtypes = [_i64] * 5 + [_p] * 4
+        lib.osdp_oracle_split_bwd_rows.restype = ctypes.c_int
+        lib.osdp_oracle_split_bwd_rows.argtypes = [_i64] * 5 + [_p] * 6
         lib.osdp_oracle_sample_y.restype = None
         lib.osdp_oracle_sample_y.argtypes = [_i64] * 4 + [_p, _p, _i64, _p, _p, _p]
         lib.osdp_oracle_sample_dx.restype = None
@@ -280,6 +290,60 @@ def dense_from_f64_shards(dW_shards, I: int, O: int):
     """Dense [I x O] fp64 view of a shard-major fp64 gradient (drops the padding)."""
     flat = np.concatenate([np.asarray(s, dtype=np.float64).reshape(-1) for s in dW_shards])
     return flat[: I * O].reshape(I, O)
+
+
+# ------------------------------------- split route along the reduction dimension
+def row_slice_range(I: int, k: int, j: int):
+    """Row range [r0, r1) of W (= column range of X) of slice j of k when the reduction dimension is split."""
+    r0, r1 = _i64(), _i64()
+    _load().osdp_oracle_row_slice_range(I, k, j, ctypes.byref(r0), ctypes.byref(r1))
+    return int(r0.value), int(r1.value)
+
+
+def gather_row_slice(shards, I: int, O: int, k: int, j: int):
+    """Row slice j of k, dense row-major [w_j x O] bf16 bits."""
+    N = len(shards)
+    sh = _check_shards(shards, I, O, N)
+    r0, r1 = row_slice_range(I, k, j)
+    Ws = np.empty((r1 - r0, O), dtype=np.uint16)
+    _load().osdp_oracle_gather_row_slice(I, O, N, k, j, _ptr_array(sh), _ptr(Ws))
+    return Ws
+
+
+def peak_staging_bytes_rows(I: int, O: int, k: int, slots: int = 1, elem_bytes: int = 2) -> int:
+    return int(_load().osdp_oracle_peak_staging_bytes_rows(I, O, k, slots, elem_bytes))
+
+
+def split_fwd_rows(X, shards, O: int, k: int):
+    """Forward with the reduction dimension split (Section 3.3 as printed): (Y fp64, peak staging bytes)."""
+    X = _u16(X)
+    T, I = X.shape
+    N = len(shards)
+    sh = _check_shards(shards, I, O, N)
+    Y = np.empty((T, O), dtype=np.float64)
+    peak = _i64()
+    rc = _load().osdp_oracle_split_fwd_rows(T, I, O, N, k, _ptr(X), _ptr_array(sh), _ptr(Y), ctypes.byref(peak))
+    if rc != 0:
+        raise MemoryError("oracle allocation failed")
+    return Y, int(peak.value)
+
+
+def split_bwd_rows(X, dY, shards, O: int, k: int):
+    """Backward with the reduction dimension split: (dX fp64, dW shards fp64, peak staging bytes)."""
+    X = _u16(X)
+    T, I = X.shape
+    dY = _u16(dY, (T, O))
+    N = len(shards)
+    sh = _check_shards(shards, I, O, N)
+    L = shard_len(I, O, N)
+    dX = np.empty((T, I), dtype=np.float64)
+    dW = [np.zeros(L, dtype=np.float64) for _ in range(N)]
+    peak = _i64()
+    rc = _load().osdp_oracle_split_bwd_rows(T, I, O, N, k, _ptr(X), _ptr(dY), _ptr_array(sh), _ptr(dX),
+                                            _ptr_array(dW), ctypes.byref(peak))
+    if rc != 0:
+        raise MemoryError("oracle allocation failed")
+    return dX, dW, int(peak.value)
 
 
 # ------------------------------------------------------------ sampled entries

@@ -24,6 +24,10 @@
  *                      recombine; tracks the peak number of live staging
  *                      bytes.
  *
+ * The paper's own wording cuts the REDUCTION dimension instead (rows of W)
+ * and sums the slice outputs; that variant is the second split route below
+ * (osdp_oracle_*_rows).  Both recombine to the same unsplit operator.
+ *
  * Readings of points the paper leaves open (all restated in the design notes):
  *   - shard layout : flat row-major index f = r*O + c, shard length
  *                    L = ceil(I*O/N), element lives in shard f / L at offset
@@ -291,6 +295,107 @@ ORACLE_API int osdp_oracle_split_bwd(int64_t T, int64_t I, int64_t O, int64_t N,
     for (int64_t e = 0; e < T * I; ++e) dX[e] += part[e];
     free(part);
     free(dWj);
+    staging_free(&m, Ws, bytes);
+  }
+  if (peak_staging) *peak_staging = m.peak;
+  return 0;
+}
+
+/* ---- split route along the reduction dimension ---------------------------
+ * Section 3.3 as printed: the last dimension of the input and the first
+ * dimension of the operator are cut into slices, the slices are computed one
+ * after another and the results are summed.  Slice j holds the rows
+ * [r0_j, r1_j) of W, r0_j = floor(j*I/k):
+ *     Y                = sum_j X[:, r0_j:r1_j] . W[r0_j:r1_j, :]      (sum)
+ *     dX[:, r0_j:r1_j] = dY . W[r0_j:r1_j, :]^T                       (concatenate)
+ *     dW[r0_j:r1_j, :] = X[:, r0_j:r1_j]^T . dY                       (concatenate)
+ */
+ORACLE_API void osdp_oracle_row_slice_range(int64_t I, int64_t k, int64_t j, int64_t *r0, int64_t *r1) {
+  k = eff_k(k);
+  *r0 = (j * I) / k;
+  *r1 = ((j + 1) * I) / k;
+}
+
+/* Gather row slice j: Ws[r, c] = W[r0_j + r, c], dense row-major [w_j x O]. */
+ORACLE_API void osdp_oracle_gather_row_slice(int64_t I, int64_t O, int64_t N, int64_t k, int64_t j,
+                                             const uint16_t *const *shards, uint16_t *Ws) {
+  int64_t r0, r1;
+  osdp_oracle_row_slice_range(I, k, j, &r0, &r1);
+  for (int64_t r = r0; r < r1; ++r)
+    for (int64_t c = 0; c < O; ++c) {
+      int64_t s, off;
+      osdp_oracle_locate(I, O, N, r, c, &s, &off);
+      Ws[(r - r0) * O + c] = shards[s][off];
+    }
+}
+
+ORACLE_API int64_t osdp_oracle_peak_staging_bytes_rows(int64_t I, int64_t O, int64_t k, int64_t slots,
+                                                       int64_t elem_bytes) {
+  int64_t wmax = 0;
+  k = eff_k(k);
+  if (slots > k) slots = k;
+  for (int64_t j = 0; j < k; ++j) {
+    int64_t r0, r1;
+    osdp_oracle_row_slice_range(I, k, j, &r0, &r1);
+    if (r1 - r0 > wmax) wmax = r1 - r0;
+  }
+  return slots * wmax * O * elem_bytes;
+}
+
+ORACLE_API int osdp_oracle_split_fwd_rows(int64_t T, int64_t I, int64_t O, int64_t N, int64_t k,
+                                          const uint16_t *X, const uint16_t *const *shards, double *Y,
+                                          int64_t *peak_staging) {
+  staging_meter m = {0, 0};
+  k = eff_k(k);
+  for (int64_t e = 0; e < T * O; ++e) Y[e] = 0.0;
+  for (int64_t j = 0; j < k; ++j) {
+    int64_t r0, r1;
+    osdp_oracle_row_slice_range(I, k, j, &r0, &r1);
+    int64_t w = r1 - r0;
+    if (w == 0) continue;
+    int64_t bytes = w * O * (int64_t)sizeof(uint16_t);
+    uint16_t *Ws = staging_alloc(&m, bytes);
+    double *part = (double *)malloc((size_t)T * O * sizeof(double));
+    if (!Ws || !part) { free(Ws); free(part); return -1; }
+    osdp_oracle_gather_row_slice(I, O, N, k, j, shards, Ws);
+    osdp_oracle_matmul_fwd(T, w, O, X + r0, I, Ws, O, part); /* X[:, r0:r1] . Ws */
+    for (int64_t e = 0; e < T * O; ++e) Y[e] += part[e];
+    free(part);
+    staging_free(&m, Ws, bytes);
+  }
+  if (peak_staging) *peak_staging = m.peak;
+  return 0;
+}
+
+ORACLE_API int osdp_oracle_split_bwd_rows(int64_t T, int64_t I, int64_t O, int64_t N, int64_t k,
+                                          const uint16_t *X, const uint16_t *dY,
+                                          const uint16_t *const *shards, double *dX,
+                                          double *const *dW_shards, int64_t *peak_staging) {
+  staging_meter m = {0, 0};
+  k = eff_k(k);
+  for (int64_t j = 0; j < k; ++j) {
+    int64_t r0, r1;
+    osdp_oracle_row_slice_range(I, k, j, &r0, &r1);
+    int64_t w = r1 - r0;
+    if (w == 0) continue;
+    int64_t bytes = w * O * (int64_t)sizeof(uint16_t);
+    uint16_t *Ws = staging_alloc(&m, bytes);
+    double *dXj = (double *)malloc((size_t)T * w * sizeof(double));
+    double *dWj = (double *)malloc((size_t)w * O * sizeof(double));
+    if (!Ws || !dXj || !dWj) { free(Ws); free(dXj); free(dWj); return -1; }
+    osdp_oracle_gather_row_slice(I, O, N, k, j, shards, Ws);
+    osdp_oracle_matmul_dx(T, w, O, dY, O, Ws, O, dXj);      /* dY . Ws^T            */
+    osdp_oracle_matmul_dw(T, w, O, X + r0, I, dY, O, dWj);  /* X[:, r0:r1]^T . dY   */
+    for (int64_t t = 0; t < T; ++t)
+      memcpy(dX + t * I + r0, dXj + t * w, (size_t)w * sizeof(double));
+    for (int64_t r = 0; r < w; ++r)
+      for (int64_t c = 0; c < O; ++c) {
+        int64_t s, off;
+        osdp_oracle_locate(I, O, N, r0 + r, c, &s, &off);
+        dW_shards[s][off] = dWj[r * O + c];
+      }
+    free(dWj);
+    free(dXj);
     staging_free(&m, Ws, bytes);
   }
   if (peak_staging) *peak_staging = m.peak;

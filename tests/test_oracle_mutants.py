@@ -28,6 +28,12 @@ MUTANTS = {
     "fwd_concat_offset": ("memcpy(Y + t * O + c0, Yj + t * w, (size_t)w * sizeof(double));",
                           "memcpy(Y + t * O + j * w, Yj + t * w, (size_t)w * sizeof(double));"),
     "dw_scatter_column": ("dW_shards[s][off] = dWj[r * w + c];", "dW_shards[s][off] = dWj[r * w + (c + 1) % w];"),
+    "rows_fwd_wrong_x_offset": ("osdp_oracle_matmul_fwd(T, w, O, X + r0, I, Ws, O, part); /* X[:, r0:r1] . Ws */",
+                                "osdp_oracle_matmul_fwd(T, w, O, X, I, Ws, O, part); /* X[:, r0:r1] . Ws */"),
+    "rows_dx_concat_offset": ("memcpy(dX + t * I + r0, dXj + t * w, (size_t)w * sizeof(double));",
+                              "memcpy(dX + t * I + j * w, dXj + t * w, (size_t)w * sizeof(double));"),
+    "rows_dw_scatter_row": ("osdp_oracle_locate(I, O, N, r0 + r, c, &s, &off);\n        dW_shards[s][off] = dWj[r * O + c];",
+                            "osdp_oracle_locate(I, O, N, r0 + r, c, &s, &off);\n        dW_shards[s][off] = dWj[((r + 1) % w) * O + c];"),
     "widen_drops_sign": ("uint32_t u = ((uint32_t)b) << 16;", "uint32_t u = ((uint32_t)(b & 0x7fff)) << 16;"),
     "sample_dw_short_sum": ("    for (int64_t t = 0; t < T; ++t)\n      acc += osdp_oracle_bf16_to_f64(X[t * I + i]) * osdp_oracle_bf16_to_f64(dY[t * O + o]);",
                             "    for (int64_t t = 1; t < T; ++t)\n      acc += osdp_oracle_bf16_to_f64(X[t * I + i]) * osdp_oracle_bf16_to_f64(dY[t * O + o]);"),

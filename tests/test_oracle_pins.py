@@ -180,6 +180,32 @@ def test_split_route_reconstructs_the_unsplit_result(oracle, T, I, O, N, k):
         assert peak_f * k == oracle.weight_bytes(I, O, 2)
 
 
+@pytest.mark.parametrize("T,I,O,N,k", [
+    (9, 16, 24, 2, 4), (9, 16, 24, 4, 1), (5, 12, 20, 3, 6), (7, 10, 13, 4, 3), (4, 16, 8, 8, 16), (6, 7, 6, 5, 0)])
+def test_reduction_split_route_reconstructs_the_unsplit_result(oracle, T, I, O, N, k):
+    """Section 3.3 as printed: rows of W (the reduction dimension) are sliced and the outputs summed."""
+    d = wl.small_case(7, T, I, O, N, w_std=1.0)
+    X, dY, shards = d["X"], d["dY"], d["W_shards"]
+    ref = oracle.linear(X, shards, O, dY=dY)
+    W = np.concatenate(shards)[: I * O].reshape(I, O)
+    seen = np.zeros(I, dtype=np.int32)
+    for j in range(max(k, 1)):  # the row slices are the strided row views and cover every row once
+        r0, r1 = oracle.row_slice_range(I, k, j)
+        assert np.array_equal(oracle.gather_row_slice(shards, I, O, k, j), W[r0:r1])
+        seen[r0:r1] += 1
+    assert (seen == 1).all()
+    Y, peak_f = oracle.split_fwd_rows(X, shards, O, k)
+    dX, dWs, peak_b = oracle.split_bwd_rows(X, dY, shards, O, k)
+    # dX and dW are concatenations here: exact; Y regroups the sum over i into k partial sums
+    assert np.array_equal(dX, ref["dX"])
+    assert np.array_equal(oracle.dense_from_f64_shards(dWs, I, O), ref["dW"])
+    np.testing.assert_allclose(Y, ref["Y"], rtol=0, atol=1e-13 * np.abs(ref["Y"]).max() + 1e-300)
+    wmax = max(r1 - r0 for r0, r1 in (oracle.row_slice_range(I, k, j) for j in range(max(k, 1))))
+    assert peak_f == peak_b == wmax * O * 2 == oracle.peak_staging_bytes_rows(I, O, k, 1, 2)
+    if k >= 1 and I % k == 0:
+        assert peak_f * k == oracle.weight_bytes(I, O, 2)  # size / granularity
+
+
 def test_split_route_ignores_shard_padding(oracle):
     T, I, O, N, k = 4, 5, 7, 4, 3
     d = wl.small_case(5, T, I, O, N)
