@@ -8,7 +8,7 @@
  * operator is cut into k slices that are gathered and processed one after
  * another, so that only a slice of gathered weight is live at a time: the
  * gathered-weight peak drops from size(MatMul) to size(MatMul)/slice_granularity.
- * The slices are column slices of W (output features):
+ * By default the slices are column slices of W (output features):
  *
  *     forward  : Y[:, c0_j:c1_j]  = X . Ws_j                     (concatenate)
  *     backward : dW[:, c0_j:c1_j] = X^T . dY[:, c0_j:c1_j]       (concatenate)
@@ -16,6 +16,18 @@
  *
  * where Ws_j[I x w_j] is slice j gathered from the N shards into a staging
  * buffer.  All three recombine to exactly the unsplit product.
+ *
+ * A plan may instead cut an operator along W's rows (input features), which is
+ * the scheme Section 3.3 prints: the input is cut along its last dimension, the
+ * weight along its first, and the partial products are added up:
+ *
+ *     forward  : Y                = sum_j X[:, r0_j:r1_j] . Wr_j      (sum)
+ *     backward : dW[r0_j:r1_j, :] = X[:, r0_j:r1_j]^T . dY            (concatenate)
+ *                dX[:, r0_j:r1_j] = dY . Wr_j^T                       (concatenate)
+ *
+ * with Wr_j[h_j x O] the gathered row slice, r0_j = floor(j*I/k).  The staging
+ * law is the same (size(MatMul)/k per live slice); the sum now sits in the
+ * forward pass.
  *
  * Conventions
  *   - Plain C ABI: no C++ or framework types.  Every "device" pointer is a HIP
@@ -42,7 +54,7 @@
  *     osdp_last_error() gives a thread-local message for the last failure.
  *
  * Shapes the GPU kernels accept (else OSDP_ERR_UNSUPPORTED): I, O, every slice
- * bound c0_j, the shard length L and every leading dimension are multiples of
+ * bound c0_j (or r0_j), the shard length L and every leading dimension are multiples of
  * 8 elements (16-byte vectors); pointers are 16-byte aligned; N <= 64;
  * T, I, O < 2^31.
  */
@@ -86,6 +98,13 @@ typedef enum {
                               as two half-width sub-slices so that the gather still overlaps      */
 } osdp_staging_mode;
 
+/* Which dimension of W the k slices cut. */
+typedef enum {
+  OSDP_SPLIT_OUT_FEATURES = 0, /* columns of W: Y and dW concatenate, dX is summed                   */
+  OSDP_SPLIT_IN_FEATURES = 1   /* rows of W, the forward product's reduction dimension (Section 3.3
+                                  as printed): Y is summed, dW and dX concatenate                     */
+} osdp_split_dim;
+
 /* The per-operator execution plan (the paper's plan vector p over the n
  * operators, Section 3.1), extended by the slice granularity of each operator
  * (Section 3.3).  All arrays are host memory.  A NULL plan means "use
@@ -97,10 +116,15 @@ typedef struct {
                             /* Only NULL / all slices set is supported (Section 3.3 describes  */
                             /* mixing DP and ZDP slices; not built here).                      */
   int32_t staging;          /* an osdp_staging_mode                                            */
+  const uint8_t *split_dim_per_op; /* [n_ops] or NULL (= all OSDP_SPLIT_OUT_FEATURES): an       */
+                            /* osdp_split_dim per operator                                     */
 } osdp_plan;
 
 /* Column range [*c0, *c1) of slice j for shape->O and shape->k. Host only. */
 OSDP_API osdp_status osdp_slice_range(const osdp_shape *shape, int32_t slice_j, int64_t *c0, int64_t *c1);
+
+/* Row range [*r0, *r1) of slice j when W is cut along its rows: r0 = floor(j*I/k). Host only. */
+OSDP_API osdp_status osdp_row_slice_range(const osdp_shape *shape, int32_t slice_j, int64_t *r0, int64_t *r1);
 
 /* Section 3.3, re-gathering of one slice: Ws_j[r, c] = W[r, c0_j + c].
  *   w_shards : host array of shape->N device pointers (bf16 shard buffers)
@@ -111,10 +135,19 @@ OSDP_API osdp_status osdp_split_linear_gather_slice(const osdp_shape *shape, int
                                            const void *const *w_shards, void *staging,
                                            void *stream);
 
+/* The same for a row slice (Section 3.3: the weight cut along its first dimension):
+ * Wr_j[r, c] = W[r0_j + r, c].
+ *   staging  : device, dense row-major [h_j x O] bf16, >= h_j*O*2 bytes, written in full
+ * Row bounds must be multiples of 8. Pure copy: bit-exact. */
+OSDP_API osdp_status osdp_split_linear_gather_row_slice(const osdp_shape *shape, int32_t slice_j,
+                                               const void *const *w_shards, void *staging,
+                                               void *stream);
+
 /* Bytes of workspace a forward (is_bwd = 0) or backward (is_bwd != 0) call
  * needs, and how many of them hold gathered weights at the peak
  * (Section 3.3: size(MatMul)/slice_granularity per live slice).
- * Workspace layout: [staging slots][fp32 dX accumulator T*I, backward with more than one dX pass].
+ * Workspace layout: [staging slots][fp32 accumulator: T*I for dX, backward with column slices and more than
+ * one dX launch; T*O for Y, forward with row slices and more than one launch].
  * With OSDP_STAGING_AUTO the total covers both the one-stream and the two-stream call.
  * Either output pointer may be NULL. Host only. */
 OSDP_API osdp_status osdp_split_linear_workspace_bytes(const osdp_shape *shape, const osdp_plan *plan,
@@ -128,7 +161,11 @@ OSDP_API osdp_status osdp_split_linear_workspace_bytes(const osdp_shape *shape, 
  *   workspace: device, 256-byte aligned, >= osdp_split_linear_workspace_bytes(.., 0, ..)
  *   stream_compute : hipStream_t the GEMMs run on
  *   stream_copy    : hipStream_t the gathers run on; NULL or == stream_compute = no overlap
- * Y is bit-identical for every k, staging mode and stream choice. */
+ * With row slices (plan->split_dim_per_op): for j = 0..k-1 gather row slice j, then
+ * Y += X[:, r0_j:r1_j] . Wr_j, the sum carried in fp32 (through the workspace between launches) in ascending
+ * j and rounded to bf16 once.
+ * Y is bit-identical for every k, staging mode and stream choice (row slices: when every slice height is a
+ * multiple of 16). */
 OSDP_API osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index,
                                   const void *X, int64_t ldx, const void *const *w_shards,
                                   void *Y, int64_t ldy, void *workspace, size_t workspace_bytes,
@@ -144,8 +181,9 @@ OSDP_API osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_p
  * between passes.
  *   dY : device [T x O], lddy >= O       dX : device [T x I], lddx >= I
  *   dw_shards : host array of N device pointers, each L elements
- * dW is bit-identical for every k; dX is too when every slice width is a
- * multiple of 16. */
+ * With row slices: dW[r0_j:r1_j, :] = X[:, r0_j:r1_j]^T . dY and dX[:, r0_j:r1_j] = dY . Wr_j^T, no sum.
+ * dW is bit-identical for every k and split dimension; dX is too when every slice width is a
+ * multiple of 16 (row slices: always). */
 OSDP_API osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index,
                                   const void *X, int64_t ldx, const void *dY, int64_t lddy,
                                   const void *const *w_shards, void *dX, int64_t lddx,

@@ -24,6 +24,9 @@ OSDP_STAGING_SINGLE = 1
 OSDP_STAGING_DOUBLE = 2
 OSDP_STAGING_HALF = 3
 
+OSDP_SPLIT_OUT_FEATURES = 0
+OSDP_SPLIT_IN_FEATURES = 1
+
 OSDP_KERNEL_GATHER = 0
 OSDP_KERNEL_GEMM_FWD = 1
 OSDP_KERNEL_GEMM_DW = 2
@@ -32,8 +35,8 @@ OSDP_KERNEL_KINDS = 4
 KERNEL_NAMES = ("gather", "gemm_fwd", "gemm_dw", "gemm_dx")
 
 EXPORTS = (
-    "osdp_slice_range", "osdp_split_linear_gather_slice", "osdp_split_linear_workspace_bytes",
-    "osdp_split_linear_fwd", "osdp_split_linear_bwd", "osdp_profile_begin", "osdp_profile_end",
+    "osdp_slice_range", "osdp_row_slice_range", "osdp_split_linear_gather_slice",
+    "osdp_split_linear_gather_row_slice", "osdp_split_linear_workspace_bytes", "osdp_split_linear_fwd", "osdp_split_linear_bwd", "osdp_profile_begin", "osdp_profile_end",
     "osdp_strerror", "osdp_last_error", "osdp_version",
 )
 
@@ -45,7 +48,8 @@ class osdp_shape(ctypes.Structure):
 
 class osdp_plan(ctypes.Structure):
     _fields_ = [("n_ops", ctypes.c_int32), ("k_per_op", ctypes.POINTER(ctypes.c_int32)),
-                ("zdp_mask", ctypes.POINTER(ctypes.c_uint64)), ("staging", ctypes.c_int32)]
+                ("zdp_mask", ctypes.POINTER(ctypes.c_uint64)), ("staging", ctypes.c_int32),
+                ("split_dim_per_op", ctypes.POINTER(ctypes.c_uint8))]
 
 
 class osdp_kernel_stats(ctypes.Structure):
@@ -69,7 +73,9 @@ def _load() -> ctypes.CDLL:
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     shp, pln = ctypes.POINTER(osdp_shape), ctypes.POINTER(osdp_plan)
     lib.osdp_slice_range.argtypes = [shp, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    lib.osdp_row_slice_range.argtypes = [shp, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
     lib.osdp_split_linear_gather_slice.argtypes = [shp, i32, vp, vp, vp]
+    lib.osdp_split_linear_gather_row_slice.argtypes = [shp, i32, vp, vp, vp]
     lib.osdp_split_linear_workspace_bytes.argtypes = [shp, pln, i32, i32, ctypes.POINTER(ctypes.c_size_t),
                                                       ctypes.POINTER(ctypes.c_size_t)]
     lib.osdp_split_linear_fwd.argtypes = [shp, pln, i32, vp, i64, vp, vp, i64, vp, ctypes.c_size_t, vp, vp]
@@ -77,7 +83,8 @@ def _load() -> ctypes.CDLL:
                                           ctypes.c_size_t, vp, vp]
     lib.osdp_profile_begin.argtypes = [i32]
     lib.osdp_profile_end.argtypes = [ctypes.POINTER(osdp_kernel_stats)]
-    for name in ("osdp_slice_range", "osdp_split_linear_gather_slice", "osdp_split_linear_workspace_bytes",
+    for name in ("osdp_slice_range", "osdp_row_slice_range", "osdp_split_linear_gather_slice",
+                 "osdp_split_linear_gather_row_slice", "osdp_split_linear_workspace_bytes",
                  "osdp_split_linear_fwd", "osdp_split_linear_bwd", "osdp_profile_begin", "osdp_profile_end"):
         getattr(lib, name).restype = ctypes.c_int
     lib.osdp_strerror.argtypes = [ctypes.c_int]
@@ -98,19 +105,22 @@ def _check(status: int) -> None:
 
 @dataclass
 class Plan:
-    """Per-operator slice granularities (and, optionally, ZDP masks) plus the staging mode."""
+    """Per-operator slice granularities (and, optionally, ZDP masks and split dimensions) plus the staging mode."""
     k_per_op: Sequence[int]
     staging: int = OSDP_STAGING_AUTO
     zdp_mask: Optional[Sequence[int]] = None
+    split_dim_per_op: Optional[Sequence[int]] = None
 
     def to_c(self):
         n = len(self.k_per_op)
         ks = (ctypes.c_int32 * n)(*self.k_per_op)
         mask = (ctypes.c_uint64 * n)(*self.zdp_mask) if self.zdp_mask is not None else None
+        dims = (ctypes.c_uint8 * n)(*self.split_dim_per_op) if self.split_dim_per_op is not None else None
         p = osdp_plan(n, ctypes.cast(ks, ctypes.POINTER(ctypes.c_int32)),
                       ctypes.cast(mask, ctypes.POINTER(ctypes.c_uint64)) if mask is not None else None,
-                      self.staging)
-        return p, (ks, mask)  # keep the arrays alive with the struct
+                      self.staging,
+                      ctypes.cast(dims, ctypes.POINTER(ctypes.c_uint8)) if dims is not None else None)
+        return p, (ks, mask, dims)  # keep the arrays alive with the struct
 
 
 def _shape(T, I, O, N, k):
@@ -145,6 +155,13 @@ def osdp_slice_range(O: int, k: int, j: int, T: int = 1, I: int = 8, N: int = 1)
     return c0.value, c1.value
 
 
+def osdp_row_slice_range(I: int, k: int, j: int, T: int = 1, O: int = 8, N: int = 1):
+    r0, r1 = ctypes.c_int64(), ctypes.c_int64()
+    shape = _shape(T, I, O, N, k)
+    _check(lib.osdp_row_slice_range(ctypes.byref(shape), j, ctypes.byref(r0), ctypes.byref(r1)))
+    return r0.value, r1.value
+
+
 def osdp_split_linear_workspace_bytes(T, I, O, N, k, is_bwd: bool, plan: Optional[Plan] = None, op_index: int = 0):
     """Returns (total workspace bytes, peak gathered-weight staging bytes)."""
     shape = _shape(T, I, O, N, k)
@@ -160,6 +177,13 @@ def osdp_split_linear_gather_slice(I, O, k, j, w_shards, staging, stream=None, T
     shape = _shape(T, I, O, len(w_shards), k)
     _check(lib.osdp_split_linear_gather_slice(ctypes.byref(shape), j, _ptrs(w_shards),
                                               int(staging.data_ptr()), _stream(stream)))
+
+
+def osdp_split_linear_gather_row_slice(I, O, k, j, w_shards, staging, stream=None, T: int = 1):
+    """Gathers row slice j of k from the shard tensors into ``staging`` (dense [h_j x O])."""
+    shape = _shape(T, I, O, len(w_shards), k)
+    _check(lib.osdp_split_linear_gather_row_slice(ctypes.byref(shape), j, _ptrs(w_shards),
+                                                  int(staging.data_ptr()), _stream(stream)))
 
 
 def osdp_split_linear_fwd(X, w_shards, Y, k, workspace, *, plan: Optional[Plan] = None, op_index: int = 0,

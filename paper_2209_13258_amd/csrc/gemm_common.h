@@ -24,7 +24,8 @@ struct GemmParams {
   const float *acc_in;
   int64_t ld_acc;
   ShardLayout lay;
-  int64_t c0;
+  int64_t c0;          // shard-major epilogue: column of the full matrix where C starts
+  int64_t r0;          // shard-major epilogue: row of the full matrix where C starts
   ShardTable shards;
 };
 
@@ -107,11 +108,12 @@ __device__ __forceinline__ void store_acc_tile(const GemmParams &p, const f32x16
           } else {
             int s;
             int64_t off;
+            const int row = m + static_cast<int>(p.r0);
             if (p.lay.rows_per_shard > 0) {
-              s = m / p.lay.rows_per_shard;
-              off = static_cast<int64_t>(m - s * p.lay.rows_per_shard) * p.lay.O + p.c0 + n;
+              s = row / p.lay.rows_per_shard;
+              off = static_cast<int64_t>(row - s * p.lay.rows_per_shard) * p.lay.O + p.c0 + n;
             } else {
-              const int64_t f = static_cast<int64_t>(m) * p.lay.O + p.c0 + n;
+              const int64_t f = static_cast<int64_t>(row) * p.lay.O + p.c0 + n;
               s = static_cast<int>(f / p.lay.L);
               off = f - static_cast<int64_t>(s) * p.lay.L;
             }

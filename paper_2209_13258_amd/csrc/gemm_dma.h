@@ -126,10 +126,12 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
   const int l32 = lane & 31, g = lane >> 5;
 
   const uint16_t *gA = (kAK ? p.A + static_cast<int64_t>(m0) * p.lda : p.A + m0) + OpA::lane_src(wave, lane, p.lda);
-  // an N-contiguous B may come in two column segments (two staged slices): the tile lies in one of them
-  const bool second = !kBK && p.n_split && n0 >= p.n_split;
-  const uint16_t *tileB = kBK ? p.B + static_cast<int64_t>(n0) * p.ldb : (second ? p.B2 + (n0 - p.n_split) : p.B + n0);
+  // B may come in two column segments (two staged slices): the tile lies in one of them
+  const bool second = p.n_split && n0 >= p.n_split;
+  const uint16_t *baseB = second ? p.B2 : p.B;
   const int64_t ldb = second ? p.ldb2 : p.ldb;
+  const int nB = second ? n0 - p.n_split : n0;
+  const uint16_t *tileB = kBK ? baseB + static_cast<int64_t>(nB) * ldb : baseB + nB;
   const uint16_t *gB = tileB + OpB::lane_src(wave, lane, ldb);
   const int64_t lsA = OpA::load_stride(p.lda), lsB = OpB::load_stride(ldb);
   const int64_t bsA = OpA::block_stride(p.lda), bsB = OpB::block_stride(ldb);
@@ -153,8 +155,8 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
   // of block it, so its loads are spread over the K steps before that barrier; with more stages they
   // are spread over all K steps.
   constexpr int kIssueSteps = (kStages == 2 && KS > 1) ? KS - 1 : KS;
-  int first_seg = (kBK && p.k_split) ? p.k_split / BK : nk;  // K blocks left in the first B segment
-  int64_t lsB_cur = lsB;
+  int first_seg = p.k_split ? p.k_split / BK : nk;  // K blocks left in the first B segment
+  int64_t lsB_cur = lsB, bsB_cur = bsB;
   const uint32_t lds_base = lds_address(smem);
   // loads [first, last) of the block that gA / gB point at, into `stage`; first / last are compile-time
   auto issue_range = [&](int stage, int first, int last) {
@@ -168,10 +170,11 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
     }
     if (last == L) {  // block fully issued: move on
       gA += bsA;
-      gB += bsB;
-      if (kBK && p.k_split && --first_seg == 0) {
-        gB = p.B2 + static_cast<int64_t>(n0) * p.ldb2 + OpB::lane_src(wave, lane, p.ldb2);
+      gB += bsB_cur;
+      if (p.k_split && --first_seg == 0) {  // B continues in its second K segment
+        gB = (kBK ? p.B2 + static_cast<int64_t>(n0) * p.ldb2 : p.B2 + n0) + OpB::lane_src(wave, lane, p.ldb2);
         lsB_cur = OpB::load_stride(p.ldb2);
+        bsB_cur = OpB::block_stride(p.ldb2);
       }
     }
   };

@@ -48,6 +48,8 @@ size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // ---- slice planning ---------------------------------------------------------
+// A range [c0, c1) along the split dimension of W: columns (output features), or rows (input features, the
+// reduction dimension of the forward product) when Resolved::rows is set.  Also used for ranges of sub-slice indices.
 struct Slice {
   int64_t c0, c1;
 };
@@ -55,27 +57,28 @@ struct Slice {
 struct Resolved {
   int64_t T, I, O;
   int32_t N, k;
+  bool rows;                 // W is cut along its rows (the reduction dimension) instead of its columns
+  int64_t D;                 // the dimension of W that is not cut: I for column slices, O for row slices
   int32_t mode;              // resolved osdp_staging_mode (never AUTO)
   int32_t slots;             // staging slots in the workspace
-  std::vector<Slice> sub;    // the column ranges processed one after another
+  std::vector<Slice> sub;    // the ranges processed one after another
   ShardLayout layout;
   size_t slot_bytes;         // one staging slot, rounded up to kSlotAlign
   size_t peak_staging;       // gathered-weight bytes live at the peak (unrounded)
-  size_t acc_bytes;          // fp32 dX accumulator (backward with more than one dX pass)
+  size_t acc_bytes;          // fp32 accumulator T x D (more than one accumulating launch: dX for column slices, Y for row slices)
   // launch plan; every entry is a range [c0, c1) of sub-slice indices
   std::vector<Slice> fwd;    // forward GEMM launches: one sub-slice, or two staged ones in one launch
   std::vector<Slice> group;  // backward: sub-slices staged together
-  std::vector<Slice> pass;   // backward: dX passes
+  std::vector<Slice> pass;   // backward: dX launches
   std::vector<Slice> dw;     // backward: dW launches (dW needs no staged weights, so these may span groups)
 };
 
 // Rough duration of one gather launch in microseconds (read + write of the slice at about 3 TB/s).
-double gather_estimate_us(int64_t I, int64_t w) { return 4.0 * static_cast<double>(I) * static_cast<double>(w) / 3.0e6 + 6.0; }
+double gather_estimate_us(int64_t elems) { return 4.0 * static_cast<double>(elems) / 3.0e6 + 6.0; }
 
-
-void slice_bounds(int64_t O, int64_t k, int64_t j, int64_t *c0, int64_t *c1) {
-  *c0 = (j * O) / k;
-  *c1 = ((j + 1) * O) / k;
+void slice_bounds(int64_t len, int64_t k, int64_t j, int64_t *c0, int64_t *c1) {
+  *c0 = (j * len) / k;
+  *c1 = ((j + 1) * len) / k;
 }
 
 osdp_status check_shape(const osdp_shape *s) {
@@ -88,14 +91,19 @@ osdp_status check_shape(const osdp_shape *s) {
   return OSDP_OK;
 }
 
-// Resolves k and the staging mode, checks what the kernels need and lists the sub-slices.
+// Resolves k, the split dimension and the staging mode, checks what the kernels need and lists the sub-slices.
 // `overlap_possible`: two distinct streams were given (or, for the size query, assumed).
+//
+// With column slices the forward launches write disjoint column ranges of Y and the dX launches add up; with
+// row slices it is the other way round (Y adds up over the slices, dX is written range by range).  Both cases
+// are planned as "concatenating" and "accumulating" launches over the sub-slices.
 osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, bool overlap_possible,
                     bool is_bwd, Resolved *r) {
   osdp_status st = check_shape(shape);
   if (st != OSDP_OK) return st;
   int64_t k = shape->k;
   int32_t mode = OSDP_STAGING_AUTO;
+  bool rows = false;
   const uint64_t *mask = nullptr;
   if (plan) {
     if (plan->n_ops <= 0) return fail(OSDP_ERR_INVALID_ARG, "plan->n_ops must be positive");
@@ -107,15 +115,22 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
     if (mode < OSDP_STAGING_AUTO || mode > OSDP_STAGING_HALF)
       return fail(OSDP_ERR_INVALID_ARG, "unknown staging mode %d", mode);
     if (plan->zdp_mask) mask = plan->zdp_mask + op_index;
+    if (plan->split_dim_per_op) {
+      const uint8_t d = plan->split_dim_per_op[op_index];
+      if (d != OSDP_SPLIT_OUT_FEATURES && d != OSDP_SPLIT_IN_FEATURES)
+        return fail(OSDP_ERR_INVALID_ARG, "unknown split dimension %d", static_cast<int>(d));
+      rows = d == OSDP_SPLIT_IN_FEATURES;
+    }
   }
   if (k == 0) k = 1;
-  if (k > shape->O) return fail(OSDP_ERR_INVALID_ARG, "k = %lld exceeds O = %lld", (long long)k, (long long)shape->O);
+  const int64_t T = shape->T, I = shape->I, O = shape->O;
+  const int64_t len = rows ? I : O;  // length of the split dimension
+  if (k > len) return fail(OSDP_ERR_INVALID_ARG, "k = %lld exceeds %s = %lld", (long long)k, rows ? "I" : "O", (long long)len);
   if (mask) {
     const uint64_t want = k >= 64 ? ~0ull : ((1ull << k) - 1ull);
     if (k > 64 || (*mask & want) != want)
       return fail(OSDP_ERR_UNSUPPORTED, "slices in DP mode (zdp_mask with cleared bits) are not supported");
   }
-  const int64_t T = shape->T, I = shape->I, O = shape->O;
   const int32_t N = shape->N;
   if (T >= (1ll << 31) || I >= (1ll << 31) || O >= (1ll << 31))
     return fail(OSDP_ERR_UNSUPPORTED, "T, I, O must be below 2^31");
@@ -127,16 +142,19 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
   if (mode == OSDP_STAGING_AUTO) mode = (overlap_possible && k > 1) ? OSDP_STAGING_DOUBLE : OSDP_STAGING_SINGLE;
   if (k == 1 && mode == OSDP_STAGING_DOUBLE) mode = OSDP_STAGING_SINGLE;
 
+  const int64_t D = rows ? O : I;
   r->T = T; r->I = I; r->O = O; r->N = N; r->k = static_cast<int32_t>(k); r->mode = mode;
+  r->rows = rows; r->D = D;
   r->layout.O = O; r->layout.L = L; r->layout.N = N;
   r->layout.rows_per_shard = (I % N == 0) ? static_cast<int32_t>(I / N) : 0;
   r->sub.clear();
   int64_t wmax = 0;
+  const char *what = rows ? "rows" : "columns";
   for (int64_t j = 0; j < k; ++j) {
     int64_t c0, c1;
-    slice_bounds(O, k, j, &c0, &c1);
+    slice_bounds(len, k, j, &c0, &c1);
     if (c0 % 8 || c1 % 8)
-      return fail(OSDP_ERR_UNSUPPORTED, "slice %lld = [%lld, %lld) is not aligned to 8 columns", (long long)j, (long long)c0, (long long)c1);
+      return fail(OSDP_ERR_UNSUPPORTED, "slice %lld = [%lld, %lld) is not aligned to 8 %s", (long long)j, (long long)c0, (long long)c1, what);
     if (mode == OSDP_STAGING_HALF) {
       if ((c1 - c0) % 16)
         return fail(OSDP_ERR_UNSUPPORTED, "half-slice staging needs slice widths that are multiples of 16 (slice %lld has %lld)", (long long)j, (long long)(c1 - c0));
@@ -150,33 +168,49 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
     }
   }
   r->slots = (mode == OSDP_STAGING_SINGLE) ? 1 : 2;
-  if (static_cast<uint64_t>(I) * static_cast<uint64_t>(wmax) / 8 >= (1ull << 32))
-    return fail(OSDP_ERR_UNSUPPORTED, "slice of %lld x %lld elements is too large for the gather kernel", (long long)I, (long long)wmax);
-  const size_t slice_bytes = static_cast<size_t>(I) * static_cast<size_t>(wmax) * 2;
+  if (static_cast<uint64_t>(D) * static_cast<uint64_t>(wmax) / 8 >= (1ull << 32))
+    return fail(OSDP_ERR_UNSUPPORTED, "slice of %lld x %lld elements is too large for the gather kernel", (long long)D, (long long)wmax);
+  const size_t slice_bytes = static_cast<size_t>(D) * static_cast<size_t>(wmax) * 2;
   r->slot_bytes = round_up(slice_bytes, kSlotAlign);
   r->peak_staging = slice_bytes * r->slots;
   const int64_t n = static_cast<int64_t>(r->sub.size());
   auto width = [&](int64_t j) { return r->sub[j].c1 - r->sub[j].c0; };
   auto span = [&](int64_t a, int64_t b) { return r->sub[b - 1].c1 - r->sub[a].c0; };
+  // one launch over sub-slices [a, b): concatenating (T x span x D) or accumulating (T x D x span)
+  auto concat_us = [&](int64_t a, int64_t b) { return gemm_estimate_us(T, span(a, b), D); };
+  auto accum_us = [&](int64_t a, int64_t b) { return gemm_estimate_us(T, D, span(a, b)); };
+  auto can_pair = [&](bool concat, int64_t j) {
+    return concat ? gemm_takes_two_column_segments(T, width(j), width(j + 1), D)
+                  : gemm_takes_two_segments(T, D, width(j), width(j + 1));
+  };
+  const bool fwd_concat = !rows, bwd_concat = rows;
 
-  // Forward: with two slots, two staged slices may share one GEMM launch (twice the columns, so fewer
-  // half-empty rounds of tiles) at the price of exposing their gathers; taken when the estimate says it pays.
+  // Forward: with two slots, two staged slices may share one GEMM launch (column slices: twice the columns, so
+  // fewer half-empty rounds of tiles; row slices: one trip of the fp32 partial sum through the workspace less)
+  // at the price of exposing their gathers; taken when the estimate says it pays.
   r->fwd.clear();
   bool pair_fwd = r->slots == 2 && n >= 2;
   if (pair_fwd) {
     double t_single = 0.0, t_pair = 0.0;
+    const double acc_trip_us = 8.0 * static_cast<double>(T) * static_cast<double>(D) / 3.0e6;  // fp32 out and back in
     for (int64_t j = 0; j + 1 < n; j += 2) {
-      pair_fwd = pair_fwd && gemm_takes_two_column_segments(T, width(j), width(j + 1), I);
+      pair_fwd = pair_fwd && can_pair(fwd_concat, j);
       if (!pair_fwd) break;
-      t_single += gemm_estimate_us(T, width(j), I) + gemm_estimate_us(T, width(j + 1), I);
-      t_pair += gemm_estimate_us(T, span(j, j + 2), I) + gather_estimate_us(I, width(j)) + gather_estimate_us(I, width(j + 1));
+      const double exposed = gather_estimate_us(D * width(j)) + gather_estimate_us(D * width(j + 1));
+      if (fwd_concat) {
+        t_single += concat_us(j, j + 1) + concat_us(j + 1, j + 2);
+        t_pair += concat_us(j, j + 2) + exposed;
+      } else {
+        t_single += accum_us(j, j + 1) + accum_us(j + 1, j + 2) + acc_trip_us;
+        t_pair += accum_us(j, j + 2) + exposed;
+      }
     }
     pair_fwd = pair_fwd && t_pair < 0.97 * t_single;
     if (const char *f = getenv("OSDP_FWD_PAIR")) {  // testing: "0" never pairs, "1" pairs whenever the kernel can
       if (f[0] == '0') pair_fwd = false;
       if (f[0] == '1') {
         pair_fwd = true;
-        for (int64_t j = 0; j + 1 < n; j += 2) pair_fwd = pair_fwd && gemm_takes_two_column_segments(T, width(j), width(j + 1), I);
+        for (int64_t j = 0; j + 1 < n; j += 2) pair_fwd = pair_fwd && can_pair(fwd_concat, j);
       }
     }
   }
@@ -186,34 +220,39 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
     j += step;
   }
 
-  // Backward processes the sub-slices in groups of `slots` (all staged at once): one dX pass per group
-  // when the widths allow it, else one dX pass per sub-slice.
+  // Backward processes the sub-slices in groups of `slots` (all staged at once): one dX launch per group
+  // when the widths allow it, else one per sub-slice.
   r->group.clear();
   r->pass.clear();
   for (int64_t g0 = 0; g0 < n; g0 += r->slots) {
     const int64_t g1 = std::min<int64_t>(n, g0 + r->slots);
     r->group.push_back({g0, g1});
-    const bool fuse = (g1 - g0 == 2) && gemm_takes_two_segments(T, I, width(g0), width(g0 + 1));
+    const bool fuse = (g1 - g0 == 2) && can_pair(bwd_concat, g0);
     if (fuse) r->pass.push_back({g0, g1});
     else
       for (int64_t j = g0; j < g1; ++j) r->pass.push_back({j, j + 1});
   }
-  // dW = X^T . dY[:, columns] uses no gathered weight, so its launches need not follow the staging groups:
-  // columns of `per` consecutive sub-slices share a launch, `per` chosen by the estimate.
+  // dW uses no gathered weight (column slices: dW[:, cols] = X^T . dY[:, cols]; row slices: dW[rows, :] =
+  // X[:, rows]^T . dY), so its launches need not follow the staging groups: the ranges of `per` consecutive
+  // sub-slices share a launch, `per` chosen by the estimate.
   int64_t per = r->slots;
   {
     double best = -1.0;
     for (int64_t cand = r->slots; ; cand *= 2) {
       if (cand > n) cand = n;
       double t = 0.0;
-      for (int64_t a = 0; a < n; a += cand) t += gemm_estimate_us(I, span(a, std::min(n, a + cand)), T);
+      for (int64_t a = 0; a < n; a += cand) {
+        const int64_t w = span(a, std::min(n, a + cand));
+        t += rows ? gemm_estimate_us(w, O, T) : gemm_estimate_us(I, w, T);
+      }
       if (best < 0.0 || t < 0.97 * best) { best = t; per = cand; }
       if (cand == n) break;
     }
   }
   r->dw.clear();
   for (int64_t a = 0; a < n; a += per) r->dw.push_back({a, std::min(n, a + per)});
-  r->acc_bytes = (is_bwd && r->pass.size() > 1) ? static_cast<size_t>(T) * static_cast<size_t>(I) * 4 : 0;
+  const size_t accumulating = is_bwd ? (bwd_concat ? 0 : r->pass.size()) : (fwd_concat ? 0 : r->fwd.size());
+  r->acc_bytes = accumulating > 1 ? static_cast<size_t>(T) * static_cast<size_t>(D) * 4 : 0;
   return OSDP_OK;
 }
 
@@ -341,9 +380,11 @@ hipError_t timed(int kind, double flops, double bytes, hipStream_t stream, F &&l
 
 hipError_t do_gather(const Resolved &r, const ShardTable &tab, const Slice &s, void *slot, hipStream_t stream) {
   const int64_t w = s.c1 - s.c0;
-  const double bytes = 2.0 * static_cast<double>(r.I) * static_cast<double>(w) * 2.0;
-  return timed(OSDP_KERNEL_GATHER, 0.0, bytes, stream,
-               [&] { return launch_gather(tab, r.layout, r.I, s.c0, w, slot, stream); });
+  const double bytes = 2.0 * static_cast<double>(r.D) * static_cast<double>(w) * 2.0;
+  return timed(OSDP_KERNEL_GATHER, 0.0, bytes, stream, [&] {
+    return r.rows ? launch_gather(tab, r.layout, s.c0, w, 0, r.O, slot, stream)
+                  : launch_gather(tab, r.layout, 0, r.I, s.c0, w, slot, stream);
+  });
 }
 
 hipError_t do_gemm(int kind, const GemmProblem &g, hipStream_t stream) {
@@ -351,6 +392,69 @@ hipError_t do_gemm(int kind, const GemmProblem &g, hipStream_t stream) {
   const double out_bytes = g.epilogue == Epilogue::kF32Workspace ? 4.0 : 2.0;
   const double bytes = 2.0 * M * K + 2.0 * K * N + out_bytes * M * N + (g.acc_in ? 4.0 * M * N : 0.0);
   return timed(kind, 2.0 * M * N * K, bytes, stream, [&] { return launch_gemm(g, stream); });
+}
+
+// The GEMM that consumes the staged sub-slices [j0, j1): one in B0, or two in B0 and B1.
+//   forward : act = X,  out = Y;   backward : act = dY, out = dX.
+// A staged column slice is [I x w] row-major, a staged row slice [w x O] row-major; the forward product reads
+// it as B[k][n] = Ws[k][n], the backward one as B[k][n] = Ws[n][k].
+// Concatenating launches (forward with column slices, dX with row slices) write columns [c0, c0 + span) of out.
+// Accumulating launches (dX with column slices, forward with row slices) add act[:, c0 : c0 + span] . B to the
+// running fp32 sum: launch `idx` of `count` reads the sum from `acc` unless it is the first and writes it back
+// unless it is the last, which rounds into out.
+GemmProblem weight_gemm(const Resolved &r, bool is_fwd, int j0, int j1, const void *B0, const void *B1, const void *act,
+                        int64_t ld_act, void *out, int64_t ld_out, float *acc, size_t idx, size_t count) {
+  const Slice &s0 = r.sub[j0];
+  const int64_t w0 = s0.c1 - s0.c0, span = r.sub[j1 - 1].c1 - s0.c0;
+  const bool two = j1 - j0 == 2;
+  const bool concat = is_fwd != r.rows;
+  GemmProblem g{};
+  g.M = static_cast<int32_t>(r.T);
+  g.a_kcontig = true;
+  g.lda = ld_act;
+  g.B = B0; g.ldb = r.rows ? r.O : w0; g.b_kcontig = !is_fwd;
+  if (two) { g.B2 = B1; g.ldb2 = r.rows ? r.O : span - w0; }
+  if (concat) {
+    g.N = static_cast<int32_t>(span); g.K = static_cast<int32_t>(r.D);
+    g.A = act;
+    if (two) g.n_split = static_cast<int32_t>(w0);
+    g.C = static_cast<uint16_t *>(out) + s0.c0; g.ldc = ld_out;
+    g.epilogue = Epilogue::kBf16RowMajor;
+  } else {
+    g.N = static_cast<int32_t>(r.D); g.K = static_cast<int32_t>(span);
+    g.A = static_cast<const uint16_t *>(act) + s0.c0;
+    if (two) g.k_split = static_cast<int32_t>(w0);
+    if (idx > 0) { g.acc_in = acc; g.ld_acc = r.D; }
+    if (idx + 1 == count) {
+      g.C = out; g.ldc = ld_out; g.epilogue = Epilogue::kBf16RowMajor;
+    } else {
+      g.C = acc; g.ldc = r.D; g.epilogue = Epilogue::kF32Workspace;
+    }
+  }
+  return g;
+}
+
+// dW over the sub-slices [j0, j1), written into the shard-major gradient: column slices give
+// dW[:, c0:c1] = X^T . dY[:, c0:c1], row slices dW[c0:c1, :] = X[:, c0:c1]^T . dY.
+GemmProblem dw_gemm(const Resolved &r, int j0, int j1, const void *X, int64_t ldx, const void *dY, int64_t lddy,
+                    const ShardTable &gtab) {
+  const int64_t c0 = r.sub[j0].c0, c1 = r.sub[j1 - 1].c1;
+  GemmProblem g{};
+  g.K = static_cast<int32_t>(r.T);
+  g.lda = ldx; g.a_kcontig = false;
+  g.ldb = lddy; g.b_kcontig = false;
+  if (r.rows) {
+    g.M = static_cast<int32_t>(c1 - c0); g.N = static_cast<int32_t>(r.O);
+    g.A = static_cast<const uint16_t *>(X) + c0; g.B = dY;
+    g.r0 = c0;
+  } else {
+    g.M = static_cast<int32_t>(r.I); g.N = static_cast<int32_t>(c1 - c0);
+    g.A = X; g.B = static_cast<const uint16_t *>(dY) + c0;
+    g.c0 = c0;
+  }
+  g.epilogue = Epilogue::kBf16ShardMajor;
+  g.layout = r.layout; g.shards = gtab;
+  return g;
 }
 
 }  // namespace
@@ -373,15 +477,24 @@ const char *osdp_strerror(osdp_status status) {
   return "unknown status";
 }
 
-osdp_status osdp_slice_range(const osdp_shape *shape, int32_t slice_j, int64_t *c0, int64_t *c1) {
+static osdp_status slice_range_along(const osdp_shape *shape, bool rows, int32_t slice_j, int64_t *c0, int64_t *c1) {
   osdp_status st = check_shape(shape);
   if (st != OSDP_OK) return st;
-  if (!c0 || !c1) return fail(OSDP_ERR_INVALID_ARG, "c0 / c1 is NULL");
+  if (!c0 || !c1) return fail(OSDP_ERR_INVALID_ARG, "range output pointer is NULL");
   const int64_t k = shape->k == 0 ? 1 : shape->k;
-  if (k > shape->O) return fail(OSDP_ERR_INVALID_ARG, "k = %lld exceeds O = %lld", (long long)k, (long long)shape->O);
+  const int64_t len = rows ? shape->I : shape->O;
+  if (k > len) return fail(OSDP_ERR_INVALID_ARG, "k = %lld exceeds %s = %lld", (long long)k, rows ? "I" : "O", (long long)len);
   if (slice_j < 0 || slice_j >= k) return fail(OSDP_ERR_INVALID_ARG, "slice %d outside [0, %lld)", slice_j, (long long)k);
-  slice_bounds(shape->O, k, slice_j, c0, c1);
+  slice_bounds(len, k, slice_j, c0, c1);
   return OSDP_OK;
+}
+
+osdp_status osdp_slice_range(const osdp_shape *shape, int32_t slice_j, int64_t *c0, int64_t *c1) {
+  return slice_range_along(shape, false, slice_j, c0, c1);
+}
+
+osdp_status osdp_row_slice_range(const osdp_shape *shape, int32_t slice_j, int64_t *r0, int64_t *r1) {
+  return slice_range_along(shape, true, slice_j, r0, r1);
 }
 
 osdp_status osdp_split_linear_workspace_bytes(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index,
@@ -398,10 +511,10 @@ osdp_status osdp_split_linear_workspace_bytes(const osdp_shape *shape, const osd
   return OSDP_OK;
 }
 
-osdp_status osdp_split_linear_gather_slice(const osdp_shape *shape, int32_t slice_j, const void *const *w_shards,
-                                           void *staging, void *stream) {
+static osdp_status gather_one(const osdp_shape *shape, uint8_t split_dim, int32_t slice_j, const void *const *w_shards,
+                              void *staging, void *stream) {
   Resolved r;
-  osdp_plan plan = {1, nullptr, nullptr, OSDP_STAGING_SINGLE};
+  osdp_plan plan = {1, nullptr, nullptr, OSDP_STAGING_SINGLE, &split_dim};
   osdp_status st = resolve(shape, &plan, 0, false, false, &r);
   if (st != OSDP_OK) return st;
   if (slice_j < 0 || slice_j >= r.k) return fail(OSDP_ERR_INVALID_ARG, "slice %d outside [0, %d)", slice_j, r.k);
@@ -412,6 +525,16 @@ osdp_status osdp_split_linear_gather_slice(const osdp_shape *shape, int32_t slic
   if (!aligned16(staging)) return fail(OSDP_ERR_UNSUPPORTED, "staging is not 16-byte aligned");
   OSDP_HIP(do_gather(r, tab, r.sub[slice_j], staging, static_cast<hipStream_t>(stream)));
   return OSDP_OK;
+}
+
+osdp_status osdp_split_linear_gather_slice(const osdp_shape *shape, int32_t slice_j, const void *const *w_shards,
+                                           void *staging, void *stream) {
+  return gather_one(shape, OSDP_SPLIT_OUT_FEATURES, slice_j, w_shards, staging, stream);
+}
+
+osdp_status osdp_split_linear_gather_row_slice(const osdp_shape *shape, int32_t slice_j, const void *const *w_shards,
+                                               void *staging, void *stream) {
+  return gather_one(shape, OSDP_SPLIT_IN_FEATURES, slice_j, w_shards, staging, stream);
 }
 
 osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, const void *X,
@@ -429,13 +552,14 @@ osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_plan *plan
   if ((st = check_workspace(r, workspace, workspace_bytes)) != OSDP_OK) return st;
 
   char *ws = static_cast<char *>(workspace);
+  float *acc = reinterpret_cast<float *>(ws + r.slot_bytes * r.slots);  // row slices: Y's fp32 partial sum
   const int n = static_cast<int>(r.sub.size());
   const bool overlap = two_streams && r.slots == 2 && n > 1;
   hipStream_t sg = overlap ? sp : sc;
   hipEvent_t slot_free[2] = {nullptr, nullptr};  // recorded on the compute stream after the last GEMM that read the slot
   if (overlap) OSDP_HIP(edge(sc, sp));  // the staging area may still be in use by earlier compute-stream work
-  for (const Slice &launch : r.fwd) {
-    const int j0 = static_cast<int>(launch.c0), j1 = static_cast<int>(launch.c1);
+  for (size_t li = 0; li < r.fwd.size(); ++li) {
+    const int j0 = static_cast<int>(r.fwd[li].c0), j1 = static_cast<int>(r.fwd[li].c1);
     void *slot_of[2] = {nullptr, nullptr};
     int slot_id[2] = {0, 0};
     for (int j = j0; j < j1; ++j) {
@@ -446,16 +570,7 @@ osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_plan *plan
       OSDP_HIP(do_gather(r, tab, r.sub[j], slot_of[j - j0], sg));
     }
     if (overlap) OSDP_HIP(edge(sp, sc));
-    const Slice &s0 = r.sub[j0];
-    GemmProblem g{};
-    g.M = static_cast<int32_t>(r.T); g.N = static_cast<int32_t>(r.sub[j1 - 1].c1 - s0.c0); g.K = static_cast<int32_t>(r.I);
-    g.A = X; g.lda = ldx; g.a_kcontig = true;
-    g.B = slot_of[0]; g.ldb = s0.c1 - s0.c0; g.b_kcontig = false;
-    if (j1 - j0 == 2) {  // both staged slices in one launch
-      g.B2 = slot_of[1]; g.ldb2 = r.sub[j0 + 1].c1 - r.sub[j0 + 1].c0; g.n_split = static_cast<int32_t>(s0.c1 - s0.c0);
-    }
-    g.C = static_cast<uint16_t *>(Y) + s0.c0; g.ldc = ldy;
-    g.epilogue = Epilogue::kBf16RowMajor;
+    const GemmProblem g = weight_gemm(r, /*is_fwd=*/true, j0, j1, slot_of[0], slot_of[1], X, ldx, Y, ldy, acc, li, r.fwd.size());
     OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_FWD, g, sc));
     if (overlap && j1 < n) {
       hipEvent_t ev;
@@ -486,7 +601,7 @@ osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan
   if ((st = check_workspace(r, workspace, workspace_bytes)) != OSDP_OK) return st;
 
   char *ws = static_cast<char *>(workspace);
-  float *acc = reinterpret_cast<float *>(ws + r.slot_bytes * r.slots);
+  float *acc = reinterpret_cast<float *>(ws + r.slot_bytes * r.slots);  // column slices: dX's fp32 partial sum
   const int n = static_cast<int>(r.sub.size());
   const bool overlap = two_streams && r.slots == 2 && n > 1;
   hipStream_t sg = overlap ? sp : sc;
@@ -504,39 +619,18 @@ osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan
       OSDP_HIP(g_events.get(&gathered));
       OSDP_HIP(hipEventRecord(gathered, sp));
     }
-    // dW launches whose columns start in this group: they need no weights and run while the gathers are in flight
+    // dW launches whose range starts in this group: they need no weights and run while the gathers are in flight
     for (; next_dw < r.dw.size() && r.dw[next_dw].c0 < g1; ++next_dw) {
-      const int64_t gc0 = r.sub[r.dw[next_dw].c0].c0, gc1 = r.sub[r.dw[next_dw].c1 - 1].c1;
-      GemmProblem gw{};
-      gw.M = static_cast<int32_t>(r.I); gw.N = static_cast<int32_t>(gc1 - gc0); gw.K = static_cast<int32_t>(r.T);
-      gw.A = X; gw.lda = ldx; gw.a_kcontig = false;
-      gw.B = static_cast<const uint16_t *>(dY) + gc0; gw.ldb = lddy; gw.b_kcontig = false;
-      gw.epilogue = Epilogue::kBf16ShardMajor;
-      gw.layout = r.layout; gw.shards = gtab; gw.c0 = gc0;
+      const GemmProblem gw = dw_gemm(r, static_cast<int>(r.dw[next_dw].c0), static_cast<int>(r.dw[next_dw].c1), X, ldx, dY, lddy, gtab);
       OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DW, gw, sc));
     }
     if (overlap) OSDP_HIP(hipStreamWaitEvent(sc, gathered, 0));
-    // dX (+)= dY[:, columns] . Ws^T ; the fp32 partial sum is carried in the workspace between passes
+    // the dX launches of the group (column slices: the fp32 partial sum is carried in the workspace between them)
     for (; next_pass < r.pass.size() && r.pass[next_pass].c1 <= g1; ++next_pass) {
       const int j0 = static_cast<int>(r.pass[next_pass].c0), j1 = static_cast<int>(r.pass[next_pass].c1);
-      const Slice &s0 = r.sub[j0];
-      const int64_t w0 = s0.c1 - s0.c0;
-      GemmProblem gx{};
-      gx.M = static_cast<int32_t>(r.T); gx.N = static_cast<int32_t>(r.I);
-      gx.K = static_cast<int32_t>(r.sub[j1 - 1].c1 - s0.c0);
-      gx.A = static_cast<const uint16_t *>(dY) + s0.c0; gx.lda = lddy; gx.a_kcontig = true;
-      gx.B = ws + static_cast<size_t>(j0 - g0) * r.slot_bytes; gx.ldb = w0; gx.b_kcontig = true;
-      if (j1 - j0 == 2) {  // both staged slices in one pass
-        gx.B2 = ws + static_cast<size_t>(j0 + 1 - g0) * r.slot_bytes;
-        gx.ldb2 = r.sub[j0 + 1].c1 - r.sub[j0 + 1].c0;
-        gx.k_split = static_cast<int32_t>(w0);
-      }
-      if (next_pass > 0) { gx.acc_in = acc; gx.ld_acc = r.I; }
-      if (next_pass + 1 == r.pass.size()) {
-        gx.C = dX; gx.ldc = lddx; gx.epilogue = Epilogue::kBf16RowMajor;
-      } else {
-        gx.C = acc; gx.ldc = r.I; gx.epilogue = Epilogue::kF32Workspace;
-      }
+      const GemmProblem gx = weight_gemm(r, /*is_fwd=*/false, j0, j1, ws + static_cast<size_t>(j0 - g0) * r.slot_bytes,
+                                         ws + static_cast<size_t>(j0 + 1 - g0) * r.slot_bytes, dY, lddy, dX, lddx, acc,
+                                         next_pass, r.pass.size());
       OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DX, gx, sc));
     }
     if (overlap && g1 < n) {

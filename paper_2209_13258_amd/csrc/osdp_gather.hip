@@ -3,7 +3,8 @@
 //
 // On one GPU the N shards are N device buffers, so the all-gather of a slice
 // becomes a strided copy: row r of the slice is w contiguous elements that
-// start at flat index r*O + c0 of the shard-major matrix.  The kernel is a
+// start at flat index r*O + c0 of the shard-major matrix (a row slice, the reduction-dimension
+// split, is the same copy with c0 = 0, w = O and a row offset).  The kernel is a
 // pure 16-byte-vector copy and is bound by HBM bandwidth: it reads I*w*2
 // bytes and writes I*w*2 bytes.
 #include "osdp_internal.h"
@@ -19,7 +20,7 @@ constexpr int kThreads = 256;
 // v % vecs_per_row.
 template <bool kRowBlock, int kUnroll>
 __global__ __launch_bounds__(kThreads) void gather_slice_kernel(
-    ShardTable shards, ShardLayout lay, uint64_t c0, uint32_t vecs_per_row, uint64_t total_vecs,
+    ShardTable shards, ShardLayout lay, uint32_t r0, uint64_t c0, uint32_t vecs_per_row, uint64_t total_vecs,
     uint4 *__restrict__ dst) {
   __shared__ const uint16_t *s_tab[OSDP_MAX_SHARDS];
   if (threadIdx.x < OSDP_MAX_SHARDS)
@@ -36,8 +37,9 @@ __global__ __launch_bounds__(kThreads) void gather_slice_kernel(
       if (v < total_vecs) {
         // total_vecs < 2^32 is checked by the host, so 32-bit division is enough here
         const uint32_t v32 = static_cast<uint32_t>(v);
-        const uint32_t r = v32 / vecs_per_row;
-        const uint32_t cv = v32 - r * vecs_per_row;
+        const uint32_t rd = v32 / vecs_per_row;  // row of the destination
+        const uint32_t cv = v32 - rd * vecs_per_row;
+        const uint32_t r = r0 + rd;              // row of the full matrix
         uint32_t s;
         uint64_t off;
         if (kRowBlock) {
@@ -62,19 +64,19 @@ __global__ __launch_bounds__(kThreads) void gather_slice_kernel(
 }  // namespace
 
 template <bool kRowBlock, int kUnroll>
-void launch_one(const ShardTable &shards, const ShardLayout &layout, int64_t c0, uint64_t vecs_per_row, uint64_t total,
+void launch_one(const ShardTable &shards, const ShardLayout &layout, int64_t r0, int64_t c0, uint64_t vecs_per_row, uint64_t total,
                 unsigned max_blocks, void *staging, hipStream_t stream) {
   uint64_t blocks = (total + kThreads * kUnroll - 1) / (kThreads * kUnroll);
   if (blocks > max_blocks) blocks = max_blocks;
   hipLaunchKernelGGL((gather_slice_kernel<kRowBlock, kUnroll>), dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, stream,
-                     shards, layout, static_cast<uint64_t>(c0), static_cast<uint32_t>(vecs_per_row), total,
+                     shards, layout, static_cast<uint32_t>(r0), static_cast<uint64_t>(c0), static_cast<uint32_t>(vecs_per_row), total,
                      static_cast<uint4 *>(staging));
 }
 
-hipError_t launch_gather(const ShardTable &shards, const ShardLayout &layout, int64_t I, int64_t c0,
+hipError_t launch_gather(const ShardTable &shards, const ShardLayout &layout, int64_t r0, int64_t rows, int64_t c0,
                          int64_t w, void *staging, hipStream_t stream) {
   const uint64_t vecs_per_row = static_cast<uint64_t>(w) / 8;
-  const uint64_t total = static_cast<uint64_t>(I) * vecs_per_row;
+  const uint64_t total = static_cast<uint64_t>(rows) * vecs_per_row;
   if (total == 0) return hipSuccess;
   // measured on MI355X: 8 vectors per thread are about twice as fast on slices up to ~32 MiB (few, long-lived
   // blocks), 4 vectors per thread with a wide grid reach 5.2 TB/s (read + write) on larger ones
@@ -82,11 +84,11 @@ hipError_t launch_gather(const ShardTable &shards, const ShardLayout &layout, in
   const int unroll = (total * 16 <= (32ull << 20)) ? 8 : 4;
   const bool rb = layout.rows_per_shard > 0;
   if (unroll == 8) {
-    if (rb) launch_one<true, 8>(shards, layout, c0, vecs_per_row, total, max_blocks, staging, stream);
-    else launch_one<false, 8>(shards, layout, c0, vecs_per_row, total, max_blocks, staging, stream);
+    if (rb) launch_one<true, 8>(shards, layout, r0, c0, vecs_per_row, total, max_blocks, staging, stream);
+    else launch_one<false, 8>(shards, layout, r0, c0, vecs_per_row, total, max_blocks, staging, stream);
   } else {
-    if (rb) launch_one<true, 4>(shards, layout, c0, vecs_per_row, total, max_blocks, staging, stream);
-    else launch_one<false, 4>(shards, layout, c0, vecs_per_row, total, max_blocks, staging, stream);
+    if (rb) launch_one<true, 4>(shards, layout, r0, c0, vecs_per_row, total, max_blocks, staging, stream);
+    else launch_one<false, 4>(shards, layout, r0, c0, vecs_per_row, total, max_blocks, staging, stream);
   }
   return hipGetLastError();
 }

@@ -160,11 +160,12 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
           } else {
             int s;
             int64_t off;
+            const int row = m + static_cast<int>(p.r0);
             if (p.lay.rows_per_shard > 0) {
-              s = m / p.lay.rows_per_shard;
-              off = static_cast<int64_t>(m - s * p.lay.rows_per_shard) * p.lay.O + p.c0 + n;
+              s = row / p.lay.rows_per_shard;
+              off = static_cast<int64_t>(row - s * p.lay.rows_per_shard) * p.lay.O + p.c0 + n;
             } else {
-              const int64_t f = static_cast<int64_t>(m) * p.lay.O + p.c0 + n;
+              const int64_t f = static_cast<int64_t>(row) * p.lay.O + p.c0 + n;
               s = static_cast<int>(f / p.lay.L);
               off = f - static_cast<int64_t>(s) * p.lay.L;
             }
@@ -301,18 +302,19 @@ hipError_t launch_gemm(const GemmProblem &q, hipStream_t stream) {
   p.B = static_cast<const uint16_t *>(q.B); p.ldb = q.ldb;
   p.C = q.C; p.ldc = q.ldc;
   p.acc_in = q.acc_in; p.ld_acc = q.ld_acc;
-  p.lay = q.layout; p.c0 = q.c0; p.shards = q.shards;
+  p.lay = q.layout; p.c0 = q.c0; p.r0 = q.r0; p.shards = q.shards;
   p.B2 = static_cast<const uint16_t *>(q.B2); p.ldb2 = q.ldb2;
   p.k_split = q.B2 ? q.k_split : 0; p.n_split = q.B2 ? q.n_split : 0;
-  if (p.k_split && !(q.a_kcontig && q.b_kcontig)) return hipErrorInvalidValue;
-  if (p.n_split && !(q.a_kcontig && !q.b_kcontig)) return hipErrorInvalidValue;
+  if ((p.k_split || p.n_split) && !q.a_kcontig) return hipErrorInvalidValue;  // dW never takes a second segment
   if (p.k_split && p.n_split) return hipErrorInvalidValue;
   constexpr int kRow = static_cast<int>(Epilogue::kBf16RowMajor), kShard = static_cast<int>(Epilogue::kBf16ShardMajor),
                 kF32 = static_cast<int>(Epilogue::kF32Workspace);
   const bool acc = q.acc_in != nullptr;
-  // The three GEMMs of the split linear layer and the four accumulate forms of dX are the only combinations built.
-  if (q.a_kcontig && !q.b_kcontig && q.epilogue == Epilogue::kBf16RowMajor && !acc)
-    return launch_best<true, false, kRow, false>(p, stream);                       // forward
+  // The three GEMMs of the split linear layer, with the four accumulate forms for forward and dX, are the only combinations built.
+  if (q.a_kcontig && !q.b_kcontig) {                                               // forward (accumulating when the reduction dimension is split)
+    if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_best<true, false, kRow, true>(p, stream) : launch_best<true, false, kRow, false>(p, stream);
+    if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_best<true, false, kF32, true>(p, stream) : launch_best<true, false, kF32, false>(p, stream);
+  }
   if (!q.a_kcontig && !q.b_kcontig && q.epilogue == Epilogue::kBf16ShardMajor && !acc)
     return launch_best<false, false, kShard, false>(p, stream);                    // dW
   if (q.a_kcontig && q.b_kcontig) {                                                // dX

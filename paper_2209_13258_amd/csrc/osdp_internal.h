@@ -37,9 +37,9 @@ struct GemmProblem {
   const void *B;     // b_kcontig: B[n*ldb + k], else B[k*ldb + n]
   int64_t ldb;
   bool b_kcontig;
-  // Optional second segment of B, so that one launch runs over two staged slices:
-  //   K-contiguous B (dX)     : rows k >= k_split of the product come from B2[n*ldb2 + (k - k_split)];
-  //   N-contiguous B (forward): columns n >= n_split come from B2[k*ldb2 + (n - n_split)].
+  // Optional second segment of B (same layout as B, leading dimension ldb2), so that one launch runs
+  // over two staged slices: k_split > 0: rows k >= k_split of the product come from B2 (k counted from
+  // k_split); n_split > 0: columns n >= n_split come from B2 (n counted from n_split).  Not both.
   const void *B2;
   int64_t ldb2;
   int32_t k_split;
@@ -52,6 +52,7 @@ struct GemmProblem {
   ShardLayout layout;   // kBf16ShardMajor only
   ShardTable shards;    // kBf16ShardMajor only
   int64_t c0;           // kBf16ShardMajor only: column offset of C inside the full matrix
+  int64_t r0;           // kBf16ShardMajor only: row offset of C inside the full matrix
 };
 
 // Enqueue on `stream`.  Returns hipSuccess or the launch error.
@@ -68,8 +69,8 @@ bool gemm_takes_two_column_segments(int64_t M, int64_t n_first, int64_t n_second
 // throughput measured for each tile shape); only used to choose between launch groupings.
 double gemm_estimate_us(int64_t M, int64_t N, int64_t K);
 
-// Ws[r, c] = W[r, c0 + c] for r < I, c < w; Ws dense row-major [I x w].
-hipError_t launch_gather(const ShardTable &shards, const ShardLayout &layout, int64_t I, int64_t c0,
+// Ws[r, c] = W[r0 + r, c0 + c] for r < rows, c < w; Ws dense row-major [rows x w].
+hipError_t launch_gather(const ShardTable &shards, const ShardLayout &layout, int64_t r0, int64_t rows, int64_t c0,
                          int64_t w, void *staging, hipStream_t stream);
 
 }  // namespace osdp

@@ -300,3 +300,159 @@ def test_config5_layer_stack(H, oracle):
         H.assert_close("dX", got["dX"][r, c], oracle.sample_dx(d["dY"], d["W_shards"], op.I, r, c))
         r, c = g.integers(0, op.I, ns), g.integers(0, op.O, ns)
         H.assert_close("dW", got["dW"][r, c], oracle.sample_dw(d["X"], d["dY"], r, c))
+
+
+# ------------------------------ the split along W's rows (the reduction dimension of the forward product)
+def _rows_plan(k, mode=0):
+    import paper_2209_13258_amd as osdp
+    return osdp.Plan([k], staging=mode, split_dim_per_op=[osdp.OSDP_SPLIT_IN_FEATURES])
+
+
+@pytest.mark.parametrize("I,O,N,k", [
+    (256, 1024, 2, 4),      # config 1
+    (96, 64, 4, 3),         # row-block shards, a slice spans more than one shard
+    (48, 40, 6, 2),         # N does not divide I: general flat map (L = 320), shard edges inside rows
+    (64, 24, 64, 8),        # many tiny shards, L = 24: every row spans shards
+    (4096, 1024, 8, 8),     # config 2 down
+    (520, 264, 8, 1),       # unsplit, ragged sizes
+])
+def test_gather_row_slice_bit_exact(H, oracle, I, O, N, k):
+    _announce("gather rows", I, O, N, k)
+    import paper_2209_13258_amd as osdp
+    d = wl.small_case(31, 8, I, O, N)
+    shards = [H.to_dev(s) for s in d["W_shards"]]
+    for j in range(max(k, 1)):
+        r0, r1 = oracle.row_slice_range(I, k, j)
+        stg = torch.full(((r1 - r0) * O + 64,), float("nan"), dtype=torch.bfloat16, device="cuda")
+        osdp.osdp_split_linear_gather_row_slice(I, O, k, j, shards, stg)
+        torch.cuda.synchronize()
+        got = H.to_bits(stg)
+        ref = oracle.gather_row_slice(d["W_shards"], I, O, k, j)
+        assert ref.shape == (r1 - r0, O)
+        assert np.array_equal(got[: ref.size].reshape(ref.shape), ref)
+        assert (got[ref.size:] == 0x7FC0).all()  # nothing written past the slice
+
+
+SMALL_ROWS = [
+    # T, I, O, N, k
+    (128, 256, 1024, 2, 4),   # config 1
+    (300, 264, 528, 4, 3),    # ragged in every dimension, 88-row slices
+    (77, 136, 200, 1, 1),     # unsplit
+    (513, 640, 384, 8, 5),    # 128-row slices, T one past a tile edge
+    (200, 1040, 72, 5, 2),    # general flat shard map
+    (64, 64, 512, 8, 8),      # 8-row slices: half an MFMA K step
+    (1, 8, 8, 1, 1),          # smallest legal problem
+]
+
+
+@pytest.mark.parametrize("T,I,O,N,k", SMALL_ROWS)
+def test_row_split_fwd_bwd_match_oracle(H, oracle, T, I, O, N, k):
+    _announce("small rows", T, I, O, N, k)
+    d = wl.small_case(32, T, I, O, N) if (T, I, O) != (128, 256, 1024) else \
+        wl.operator_inputs(1, 0, 0, T, I, O, N)
+    op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+    plan = _rows_plan(k)
+    op.fwd(k, plan=plan)
+    op.bwd(k, plan=plan)
+    got = op.results()
+    ref = oracle.linear(d["X"], d["W_shards"], O, dY=d["dY"])
+    for name in ("Y", "dX", "dW"):
+        H.assert_close(f"{name} rows T{T} I{I} O{O} N{N} k{k}", got[name], ref[name])
+    # the oracle's own row-split route (the scheme of Section 3.3 step by step)
+    Ys, _ = oracle.split_fwd_rows(d["X"], d["W_shards"], O, k)
+    H.assert_close("Y vs row-split route", got["Y"], Ys)
+    dXs, dWs, _ = oracle.split_bwd_rows(d["X"], d["dY"], d["W_shards"], O, k)
+    H.assert_close("dX vs row-split route", got["dX"], dXs)
+    H.assert_close("dW vs row-split route", got["dW"], oracle.dense_from_f64_shards(dWs, I, O))
+
+
+@pytest.mark.parametrize("pair", ["0", "1"])
+@pytest.mark.parametrize("T,I,O,N", [(300, 640, 264, 4), (128, 1024, 256, 2), (1024, 2048, 512, 8),
+                                     (256, 640, 256, 4)])  # last: k=1 takes the unchecked kernel, k=2 (320 rows) the checked one for dW
+def test_row_split_is_bit_identical_to_unsplit(H, T, I, O, N, pair, monkeypatch):
+    """dW and dX are concatenated, so they equal the unsplit result bit for bit for every k, staging mode,
+    stream choice and launch grouping; Y is a sum carried in the fp32 accumulator and is bit-identical when
+    the slice height is a multiple of the MFMA's 16-deep K step."""
+    _announce("bit-identity rows", T, I, O, N, "pair", pair)
+    monkeypatch.setenv("OSDP_FWD_PAIR", pair)
+    import paper_2209_13258_amd as osdp
+    d = wl.small_case(33, T, I, O, N)
+    op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+    op.fwd(1)
+    op.bwd(1)
+    base = op.results()
+    sc, sp = H.streams()
+    for k in (0, 2, 4, 5, 8, 16):
+        if I % max(k, 1) or (I // max(k, 1)) % 8:
+            continue
+        for mode in (osdp.OSDP_STAGING_SINGLE, osdp.OSDP_STAGING_DOUBLE, osdp.OSDP_STAGING_HALF):
+            if mode == osdp.OSDP_STAGING_HALF and (I // max(k, 1)) % 16:
+                continue
+            for two_streams in (False, True):
+                plan = _rows_plan(k, mode)
+                op2 = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+                torch.cuda.synchronize()
+                with torch.cuda.stream(sc):
+                    st = (sc, sp) if two_streams else (sc, None)
+                    op2.fwd(k, plan=plan, streams=st)
+                    op2.bwd(k, plan=plan, streams=st)
+                sc.synchronize()
+                got = {"Y": H.to_bits(op2.Y), "dX": H.to_bits(op2.dX),
+                       "dW": np.concatenate([H.to_bits(s) for s in op2.dW])[: I * O].reshape(I, O)}
+                tag = f"k={k} mode={mode} two_streams={two_streams}"
+                assert np.array_equal(got["dW"], base["dW"]), f"dW differs from k=1 ({tag})"
+                assert np.array_equal(got["dX"], base["dX"]), f"dX differs from k=1 ({tag})"
+                height = I // max(k, 1) // (2 if mode == osdp.OSDP_STAGING_HALF else 1)
+                if height % 16 == 0:
+                    assert np.array_equal(got["Y"], base["Y"]), f"Y differs from k=1 ({tag})"
+                else:
+                    assert not np.isnan(H.widen(got["Y"])).any()
+
+
+def test_mixed_split_dimensions_share_one_workspace(H, oracle):
+    """A plan vector that cuts some operators by columns and some by rows, run as a stack on two streams."""
+    import paper_2209_13258_amd as osdp
+    shapes = [(256, 128, 384, 4), (256, 384, 128, 4), (256, 128, 512, 4), (256, 512, 128, 4)]
+    plan = osdp.Plan([3, 2, 4, 4], split_dim_per_op=[0, 1, 1, 0])
+    ops, data = [], []
+    for n, (T, I, O, N) in enumerate(shapes):
+        d = wl.small_case(40 + n, T, I, O, N)
+        data.append(d)
+        ops.append(H.Operator(d["X"], d["dY"], d["W_shards"], O))
+    need = max(max(osdp.osdp_split_linear_workspace_bytes(T, I, O, N, 0, b, plan, n)[0] for b in (False, True))
+               for n, (T, I, O, N) in enumerate(shapes))
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    sc, sp = H.streams()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(sc):
+        for rep in range(2):
+            for n, op in enumerate(ops):
+                op.ws = ws
+                op.fwd(0, plan=plan, op_index=n, streams=(sc, sp))
+            for n, op in reversed(list(enumerate(ops))):
+                op.bwd(0, plan=plan, op_index=n, streams=(sc, sp))
+    sc.synchronize()
+    for op, d, (T, I, O, N) in zip(ops, data, shapes):
+        got = op.results()
+        ref = oracle.linear(d["X"], d["W_shards"], O, dY=d["dY"])
+        for name in ("Y", "dX", "dW"):
+            H.assert_close(name, got[name], ref[name])
+
+
+@pytest.mark.parametrize("k", [2, 4, 8])
+def test_config2_ffn_pair_row_split(H, oracle, k):
+    """Config 2 at full size with both operators cut along their input features."""
+    import paper_2209_13258_amd as osdp
+    w = wl.workload(2, k)
+    for n, op in enumerate(w.ops):
+        dev, _ = _sampled_check(H, oracle, 2, n, op, w.T, w.N, k, plan=_rows_plan(k))
+        _, peak = osdp.osdp_split_linear_workspace_bytes(w.T, op.I, op.O, w.N, k, False, _rows_plan(k))
+        assert peak == oracle.peak_staging_bytes_rows(op.I, op.O, k, 2, 2)
+
+
+def test_config3_layer_with_row_split_plan(H, oracle):
+    import paper_2209_13258_amd as osdp
+    w = wl.workload(3)
+    plan = osdp.Plan([op.k for op in w.ops], split_dim_per_op=[osdp.OSDP_SPLIT_IN_FEATURES] * len(w.ops))
+    for n, op in enumerate(w.ops):
+        _sampled_check_plan(H, oracle, 3, n, op, w, plan)

@@ -22,7 +22,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(osdp.binding.osdp_shape) == 32
-    assert ctypes.sizeof(osdp.binding.osdp_plan) == 32
+    assert ctypes.sizeof(osdp.binding.osdp_plan) == 40
     assert ctypes.sizeof(osdp.binding.osdp_kernel_stats) == 32
 
 
@@ -33,6 +33,61 @@ def test_slice_ranges_agree_with_oracle(oracle, O, k):
         return
     for j in range(max(k, 1)):
         assert osdp.osdp_slice_range(O, k, j) == oracle.slice_range(O, k, j)
+
+
+@pytest.mark.parametrize("I", [8, 24, 1024, 10240])
+@pytest.mark.parametrize("k", [0, 1, 2, 3, 4, 8, 16])
+def test_row_slice_ranges_agree_with_oracle(oracle, I, k):
+    if max(k, 1) > I:
+        return
+    for j in range(max(k, 1)):
+        assert osdp.osdp_row_slice_range(I, k, j) == oracle.row_slice_range(I, k, j)
+    with pytest.raises(osdp.OsdpError) as e:
+        osdp.osdp_row_slice_range(I, k, max(k, 1))
+    assert e.value.status == osdp.binding.OSDP_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("T,I,O,N,k", [(128, 256, 1024, 2, 4), (8192, 1024, 4096, 8, 8), (16384, 10240, 2560, 8, 4),
+                                       (4096, 32768, 8192, 8, 16), (200, 96, 64, 3, 2), (64, 64, 64, 1, 0)])
+def test_row_split_workspace_and_peak_staging_follow_the_law(oracle, T, I, O, N, k):
+    """Section 3.3 as printed (weight cut along its first dimension): the same size / granularity law; the fp32
+    partial sum now belongs to the forward pass (T x O) and the backward pass needs none."""
+    rows = [osdp.OSDP_SPLIT_IN_FEATURES]
+    single = osdp.Plan([k], staging=osdp.OSDP_STAGING_SINGLE, split_dim_per_op=rows)
+    double = osdp.Plan([k], staging=osdp.OSDP_STAGING_DOUBLE, split_dim_per_op=rows)
+    half = osdp.Plan([k], staging=osdp.OSDP_STAGING_HALF, split_dim_per_op=rows)
+    keff = max(k, 1)
+    acc = T * O * 4
+    for is_bwd in (False, True):
+        tot1, peak1 = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, is_bwd, single)
+        tot2, peak2 = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, is_bwd, double)
+        toth, peakh = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, is_bwd, half)
+        assert peak1 == oracle.peak_staging_bytes_rows(I, O, k, 1, 2) == oracle.weight_bytes(I, O, 2) // keff
+        assert peak2 == oracle.peak_staging_bytes_rows(I, O, k, 2, 2)
+        assert peakh == peak1
+        if is_bwd:
+            assert (tot1, tot2, toth) == (peak1, peak2, peakh)
+        else:
+            assert tot1 == peak1 + (acc if keff > 1 else 0)  # one slot: one launch per slice
+            # two slots: pairs of slices may share a launch, so k = 2 may need no partial sum at all
+            assert tot2 - peak2 in ((0, acc) if keff == 2 else (acc,) if keff > 2 else (0,))
+            assert toth - peakh in ((0, acc) if keff == 1 else (acc,))
+    # the unsplit operator is the same whichever dimension the plan names
+    assert osdp.osdp_split_linear_workspace_bytes(T, I, O, N, 1, True, osdp.Plan([1], split_dim_per_op=rows)) == \
+        osdp.osdp_split_linear_workspace_bytes(T, I, O, N, 1, True, osdp.Plan([1]))
+
+
+def test_row_split_rejects_what_the_kernels_cannot_take():
+    rows = [osdp.OSDP_SPLIT_IN_FEATURES]
+    for args, status in [((128, 8, 1024, 2, 16), -1),      # k > I
+                         ((128, 264, 1024, 2, 2), -2),     # row bound 132 not a multiple of 8
+                         ((128, 256, 1024, 2, 3), -2)]:
+        with pytest.raises(osdp.OsdpError) as e:
+            osdp.osdp_split_linear_workspace_bytes(*args, False, osdp.Plan([args[4]], split_dim_per_op=rows))
+        assert e.value.status == status, (args, str(e.value))
+    with pytest.raises(osdp.OsdpError) as e:
+        osdp.osdp_split_linear_workspace_bytes(128, 256, 1024, 2, 2, False, osdp.Plan([2], split_dim_per_op=[7]))
+    assert e.value.status == osdp.binding.OSDP_ERR_INVALID_ARG
 
 
 @pytest.mark.parametrize("T,I,O,N,k", [(128, 256, 1024, 2, 4), (8192, 1024, 4096, 8, 8), (16384, 10240, 2560, 8, 4),
@@ -149,6 +204,12 @@ def test_argument_errors_are_raised_before_anything_is_enqueued():
     with pytest.raises(osdp.OsdpError) as e:
         osdp.osdp_split_linear_gather_slice(I, O, k, 4, shards, _FakeTensor(0x50000, (1,)))
     assert e.value.status == -1  # slice index out of range
+    with pytest.raises(osdp.OsdpError) as e:
+        osdp.osdp_split_linear_gather_row_slice(I, O, k, 4, shards, _FakeTensor(0x50000, (1,)))
+    assert e.value.status == -1
+    with pytest.raises(osdp.OsdpError) as e:
+        osdp.osdp_split_linear_gather_row_slice(I, O, k, 0, shards, _FakeTensor(0x50008, (1,)))
+    assert e.value.status == -2  # misaligned staging
 
 
 def test_profile_end_without_begin_is_an_error():
