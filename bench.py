@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--config", type=int, default=2, help="workload: index into BASELINE.json configs (1-based)")
     ap.add_argument("--k", type=int, default=None, help="slice granularity (default: the workload's own)")
     ap.add_argument("--staging", choices=["auto", "single", "double", "half"], default="auto")
+    ap.add_argument("--split-dim", choices=["out", "in"], default="out",
+                    help="cut W along its output features (columns) or its input features (rows, the reduction dimension)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the k sweep and the extra workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--serial", action="store_true", help="one stream: no gather/GEMM overlap")
@@ -48,7 +50,7 @@ def parse():
 class Stack:
     """All operators of a workload resident on the GPU, with one shared workspace."""
 
-    def __init__(self, w, staging, torch, osdp, seed=0):
+    def __init__(self, w, staging, torch, osdp, seed=0, rows=False):
         self.w, self.torch, self.osdp = w, torch, osdp
         g = torch.Generator(device="cuda")
         g.manual_seed(220913258 + seed)
@@ -67,11 +69,13 @@ class Stack:
                     dW=[torch.empty((L,), device="cuda", dtype=bf) for _ in range(w.N)],
                 )
                 self.ops.append(d)
-        self.plan = osdp.Plan([op.k for op in w.ops], staging=staging)
+        dims = [osdp.OSDP_SPLIT_IN_FEATURES if rows else osdp.OSDP_SPLIT_OUT_FEATURES] * len(w.ops)
+        self.plan = osdp.Plan([op.k for op in w.ops], staging=staging, split_dim_per_op=dims)
         need, self.peak_staging = 0, 0
         for n, op in enumerate(w.ops):
-            tot, peak = osdp.osdp_split_linear_workspace_bytes(w.T, op.I, op.O, w.N, 0, True, self.plan, n)
-            need, self.peak_staging = max(need, tot), max(self.peak_staging, peak)
+            for is_bwd in (False, True):
+                tot, peak = osdp.osdp_split_linear_workspace_bytes(w.T, op.I, op.O, w.N, 0, is_bwd, self.plan, n)
+                need, self.peak_staging = max(need, tot), max(self.peak_staging, peak)
         self.workspace_bytes = need
         self.ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
         self.sc, self.sp = torch.cuda.Stream(), torch.cuda.Stream()
@@ -118,7 +122,7 @@ def kernel_table(stats):
     return out
 
 
-def cpu_baseline(w, target_s=15.0):
+def cpu_baseline(w, target_s=15.0, rows=False):
     """The oracle's split route on a token sub-sample of the same workload, all host threads."""
     import numpy as np
     import oracle
@@ -129,8 +133,12 @@ def cpu_baseline(w, target_s=15.0):
         for n, op in enumerate(w.ops):
             d = wl.operator_inputs(w.cfg, 0, n, Ts, op.I, op.O, w.N)
             t0 = time.perf_counter()
-            oracle.split_fwd(d["X"], d["W_shards"], op.O, op.k)
-            oracle.split_bwd(d["X"], d["dY"], d["W_shards"], op.O, op.k)
+            if rows:
+                oracle.split_fwd_rows(d["X"], d["W_shards"], op.O, op.k)
+                oracle.split_bwd_rows(d["X"], d["dY"], d["W_shards"], op.O, op.k)
+            else:
+                oracle.split_fwd(d["X"], d["W_shards"], op.O, op.k)
+                oracle.split_bwd(d["X"], d["dY"], d["W_shards"], op.O, op.k)
             t += time.perf_counter() - t0
             fl += 6 * Ts * op.I * op.O
         return fl, t
@@ -165,7 +173,8 @@ def main():
     staging = {"auto": osdp.OSDP_STAGING_AUTO, "single": osdp.OSDP_STAGING_SINGLE,
                "double": osdp.OSDP_STAGING_DOUBLE, "half": osdp.OSDP_STAGING_HALF}[a.staging]
     w = wl.workload(a.config, a.k)
-    st = Stack(w, staging, torch, osdp)
+    rows = a.split_dim == "in"
+    st = Stack(w, staging, torch, osdp, rows=rows)
     flops = wl.flops(w)
 
     ms, _ = st.run(a.steps, a.warmup, serial=a.serial)
@@ -176,7 +185,7 @@ def main():
     roofline = {"bound": "mfma", "kernel": dom, "achieved": gemms[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(gemms[dom]["tflops"] / PEAK_BF16_TFLOPS, 4),
                 "traffic": (MEASURED_TRAFFIC.get(a.config, {}).get(dom)
-                            if (a.k is None and a.staging == "auto" and not a.serial) else None),
+                            if (a.k is None and a.staging == "auto" and not a.serial and not rows) else None),
                 "algorithmic_bytes": round(stats[dom]["bytes"] / stats[dom]["launches"]),
                 "avg_launch_us": gemms[dom]["avg_us"], "launches": gemms[dom]["launches"]}
 
@@ -187,7 +196,8 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "baseline_config": a.config, "T": w.T, "N_shards": w.N, "layers": w.layers,
                    "ops": {op.name: {"I": op.I, "O": op.O, "k": op.k} for op in w.ops},
-                   "staging": a.staging, "overlap": not a.serial},
+                   "staging": a.staging, "overlap": not a.serial,
+                   "split_dim": "in_features" if rows else "out_features"},
         "frac_bf16_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3),
         "workspace_mb": round(st.workspace_bytes / 2 ** 20, 3),
@@ -202,7 +212,7 @@ def main():
             wk = wl.workload(a.config, k)
             del st
             torch.cuda.empty_cache()
-            st = Stack(wk, staging, torch, osdp)
+            st = Stack(wk, staging, torch, osdp, rows=rows)
             msk, _ = st.run(max(5, a.steps // 2), max(2, a.warmup // 2), serial=a.serial)
             mss, _ = st.run(max(5, a.steps // 2), 2, serial=True)
             _, sk = st.run(max(5, a.steps // 4), 2, serial=a.serial, profile=True)
@@ -213,19 +223,26 @@ def main():
                              "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3),
                              "gather_gbs": kt.get("gather", {}).get("gbs_algorithmic"),
                              "gather_frac_hbm_peak": round(kt.get("gather", {}).get("gbs_algorithmic", 0) / PEAK_HBM_GBS, 4)}
+            if k > 1:  # the same granularity with W cut along the other dimension
+                del st
+                torch.cuda.empty_cache()
+                st = Stack(wk, staging, torch, osdp, rows=not rows)
+                mso, _ = st.run(max(5, a.steps // 2), max(2, a.warmup // 2), serial=a.serial)
+                sweep[str(k)]["tflops_other_split_dim"] = round(wl.flops(wk) / (mso * 1e-3) / 1e12, 2)
+                sweep[str(k)]["peak_staging_mb_other_split_dim"] = round(st.peak_staging / 2 ** 20, 3)
         out["k_sweep"] = sweep
         if a.config == 2:  # the h = 2560 layer under its plan vector, where the 70 % target applies
             del st
             torch.cuda.empty_cache()
             w3 = wl.workload(3)
-            st = Stack(w3, staging, torch, osdp)
+            st = Stack(w3, staging, torch, osdp, rows=rows)
             ms3, _ = st.run(10, 3, serial=a.serial)
             tf3 = wl.flops(w3) / (ms3 * 1e-3) / 1e12
             out["also"] = {"workload": w3.name, "plan": {op.name: op.k for op in w3.ops}, "ms_per_step": round(ms3, 4),
                            "tflops": round(tf3, 2), "frac_bf16_mfma_peak": round(tf3 / PEAK_BF16_TFLOPS, 4),
                            "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3)}
     if not a.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(w)
+        out["cpu_baseline"] = cpu_baseline(w, rows=rows)
     print(json.dumps(out), flush=True)
     return 0
 
