@@ -42,6 +42,7 @@ def parse():
     ap.add_argument("--split-dim", choices=["out", "in"], default="out",
                     help="cut W along its output features (columns) or its input features (rows, the reduction dimension)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the k sweep and the extra workload")
+    ap.add_argument("--no-auto", action="store_true", help="skip the automatic slice-granularity table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--serial", action="store_true", help="one stream: no gather/GEMM overlap")
     return ap.parse_args()
@@ -50,7 +51,7 @@ def parse():
 class Stack:
     """All operators of a workload resident on the GPU, with one shared workspace."""
 
-    def __init__(self, w, staging, torch, osdp, seed=0, rows=False):
+    def __init__(self, w, staging, torch, osdp, seed=0, rows=False, plan=None):
         self.w, self.torch, self.osdp = w, torch, osdp
         g = torch.Generator(device="cuda")
         g.manual_seed(220913258 + seed)
@@ -70,7 +71,7 @@ class Stack:
                 )
                 self.ops.append(d)
         dims = [osdp.OSDP_SPLIT_IN_FEATURES if rows else osdp.OSDP_SPLIT_OUT_FEATURES] * len(w.ops)
-        self.plan = osdp.Plan([op.k for op in w.ops], staging=staging, split_dim_per_op=dims)
+        self.plan = plan or osdp.Plan([op.k for op in w.ops], staging=staging, split_dim_per_op=dims)
         need, self.peak_staging = 0, 0
         for n, op in enumerate(w.ops):
             for is_bwd in (False, True):
@@ -119,6 +120,47 @@ def kernel_table(stats):
             e["frac_mfma_peak"] = round(e["tflops"] / PEAK_BF16_TFLOPS, 4)
         e["gbs_algorithmic"] = round(s["bytes"] / (s["ms"] * 1e-3) / 1e9, 1)
         out[name] = e
+    return out
+
+
+def auto_granularity(st, osdp, torch, steps, warmup):
+    """Every (k, split dimension, staging) candidate of each operator timed by the library on the stack's own
+    buffers, and what the selection rule picks: fastest overall, least gathered weight within 10 % of it, and the
+    fastest within the peak staging of the stack's own plan; the step is then timed under that last choice."""
+    names = {osdp.OSDP_STAGING_SINGLE: "single", osdp.OSDP_STAGING_DOUBLE: "double", osdp.OSDP_STAGING_HALF: "half"}
+    out, picked = {}, []
+    for d in st.ops[:len(st.w.ops)]:
+        op = d["op"]
+        cands = osdp.osdp_granularity_candidates(st.w.T, op.I, op.O, st.w.N, [1, 2, 4, 8, 16])
+        ws = torch.empty(max(c.workspace for c in cands), dtype=torch.uint8, device="cuda")
+        with torch.cuda.stream(st.sc):
+            osdp.osdp_granularity_measure(d["X"], d["dY"], d["W"], d["Y"], d["dX"], d["dW"], ws, cands, warmup=2, reps=5,
+                                          stream_compute=st.sc, stream_copy=st.sp)
+        torch.cuda.synchronize()
+
+        def show(i):
+            c = cands[i]
+            return {"k": c.k, "split_dim": "in" if c.split_dim else "out", "staging": names[c.staging],
+                    "peak_staging_mb": round(c.peak_weight_staging / 2 ** 20, 3), "workspace_mb": round(c.workspace / 2 ** 20, 3),
+                    "ms": round(c.ms, 4), "tflops": round(6 * st.w.T * op.I * op.O / (c.ms * 1e-3) / 1e12, 1)}
+        same_budget = osdp.osdp_granularity_select(cands, st.peak_staging, 0, 0.0)
+        picked.append(cands[same_budget])
+        out[op.name] = {"candidates": len(cands),
+                        "fastest": show(osdp.osdp_granularity_select(cands, 0, 0, 0.0)),
+                        "fastest_within_default_peak_staging": show(same_budget),
+                        "least_staging_within_10pct": show(osdp.osdp_granularity_select(cands, 0, 0, 0.10)),
+                        "table": [show(i) for i in range(len(cands))]}
+    # the whole step under the per-operator choices
+    plan = osdp.Plan([c.k for c in picked], split_dim_per_op=[c.split_dim for c in picked],
+                     staging_per_op=[c.staging for c in picked])
+    tuned = Stack(st.w, 0, torch, osdp, plan=plan)
+    ms = min(tuned.run(steps, warmup)[0] for _ in range(2))
+    import workloads as wl
+    out["step_under_chosen_plan"] = {"k_per_op": list(plan.k_per_op), "split_dim_per_op": list(plan.split_dim_per_op),
+                                     "staging_per_op": [names[m] for m in plan.staging_per_op], "ms_per_step": round(ms, 4),
+                                     "tflops": round(wl.flops(st.w) / (ms * 1e-3) / 1e12, 2),
+                                     "peak_staging_mb": round(tuned.peak_staging / 2 ** 20, 3),
+                                     "workspace_mb": round(tuned.workspace_bytes / 2 ** 20, 3)}
     return out
 
 
@@ -206,6 +248,8 @@ def main():
         "kernels": kernels,
     }
 
+    if not a.no_auto:
+        out["auto_granularity"] = auto_granularity(st, osdp, torch, max(5, a.steps // 2), max(2, a.warmup // 2))
     if not a.no_sweep:
         sweep = {}
         for k in (w.k_sweep or ()):

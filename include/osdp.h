@@ -118,6 +118,8 @@ typedef struct {
   int32_t staging;          /* an osdp_staging_mode                                            */
   const uint8_t *split_dim_per_op; /* [n_ops] or NULL (= all OSDP_SPLIT_OUT_FEATURES): an       */
                             /* osdp_split_dim per operator                                     */
+  const int32_t *staging_per_op;   /* [n_ops] or NULL (= `staging` for all): an                  */
+                            /* osdp_staging_mode per operator                                  */
 } osdp_plan;
 
 /* Column range [*c0, *c1) of slice j for shape->O and shape->k. Host only. */
@@ -189,6 +191,63 @@ OSDP_API osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_p
                                   const void *const *w_shards, void *dX, int64_t lddx,
                                   void *const *dw_shards, void *workspace, size_t workspace_bytes,
                                   void *stream_compute, void *stream_copy);
+
+/* ---- automatic slice granularity ------------------------------------------
+ * Section 4.3 (effectiveness of operator splitting) observes that the best
+ * granularity depends on the operator: small operators pay time for every extra
+ * slice, large ones need many slices before the gathered-weight peak stops
+ * falling, and leaves open how to suggest a granularity per operator from the
+ * model description and the device.  Here: enumerate the (granularity, split
+ * dimension, staging mode) combinations the kernels take for the operator's
+ * shape, time each on this device with the operator's own buffers, and select
+ * by a fixed rule. */
+
+typedef struct {
+  int32_t k;                  /* slice granularity, >= 1                                  */
+  int32_t staging;            /* OSDP_STAGING_SINGLE, _DOUBLE or _HALF                    */
+  int32_t split_dim;          /* an osdp_split_dim                                        */
+  int32_t reserved;           /* 0                                                        */
+  size_t peak_weight_staging; /* gathered-weight bytes live at the peak (Section 3.3 law) */
+  size_t workspace;           /* workspace bytes that cover the forward and the backward  */
+  double ms;                  /* one forward + backward in milliseconds; 0 = not measured */
+} osdp_granularity_candidate;
+
+/* Lists the combinations that osdp_split_linear_fwd / _bwd accept for this
+ * shape (shape->k is ignored): for every k of k_list (host, n_k entries >= 1;
+ * NULL = 1, 2, 3, 4, 6, 8, 12, 16), in the order given, for the column split
+ * then the row split, for SINGLE, DOUBLE, HALF staging.  Combinations that
+ * resolve to the same execution are listed once (k = 1: one SINGLE entry).
+ * Writes at most `capacity` entries to out (ms = 0) and the full count to
+ * *count; out may be NULL when capacity is 0. Host only. */
+OSDP_API osdp_status osdp_granularity_candidates(const osdp_shape *shape, const int32_t *k_list, int32_t n_k,
+                                                 osdp_granularity_candidate *out, int32_t capacity, int32_t *count);
+
+/* Times every candidate on the current device: `warmup` untimed and `reps`
+ * timed repetitions of osdp_split_linear_fwd followed by osdp_split_linear_bwd
+ * with the candidate's plan, HIP events on stream_compute, and stores the mean
+ * in cands[i].ms.  Buffers as for those two calls; workspace_bytes must cover
+ * the largest candidate (OSDP_ERR_WORKSPACE otherwise, before anything runs).
+ * Synchronises stream_compute once per candidate.  Y, dX and dW end up holding
+ * the last candidate's (valid) results. */
+OSDP_API osdp_status osdp_granularity_measure(const osdp_shape *shape, const void *X, int64_t ldx, const void *dY,
+                                              int64_t lddy, const void *const *w_shards, void *Y, int64_t ldy,
+                                              void *dX, int64_t lddx, void *const *dw_shards, void *workspace,
+                                              size_t workspace_bytes, void *stream_compute, void *stream_copy,
+                                              osdp_granularity_candidate *cands, int32_t n, int32_t warmup,
+                                              int32_t reps);
+
+/* The selection rule. Host only.  Among the measured candidates (ms > 0) whose
+ * peak_weight_staging is at most staging_budget bytes and whose workspace (the
+ * staging slots plus the fp32 partial sum) is at most workspace_budget bytes
+ * (0 = no limit, each), let t* be the smallest ms.  Of those with ms <= (1 + max_slowdown) * t*, the one
+ * with the smallest peak_weight_staging is chosen; ties go to the smaller ms,
+ * then to the lower index.  max_slowdown = 0 picks the fastest candidate that
+ * fits; a large max_slowdown picks the smallest peak ("fully optimise the
+ * memory footprint at an acceptable additional time cost").
+ * OSDP_ERR_UNSUPPORTED when no measured candidate fits the budgets. */
+OSDP_API osdp_status osdp_granularity_select(const osdp_granularity_candidate *cands, int32_t n,
+                                             size_t staging_budget, size_t workspace_budget,
+                                             double max_slowdown, int32_t *chosen);
 
 /* ---- per-kernel timing (for benchmarks) --------------------------------- */
 

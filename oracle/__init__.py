@@ -346,6 +346,34 @@ def split_bwd_rows(X, dY, shards, O: int, k: int):
     return dX, dW, int(peak.value)
 
 
+# ------------------------------------------------ choice of the slice granularity
+def granularity_select(table, staging_budget: int = 0, workspace_budget: int = 0, max_slowdown: float = 0.0):
+    """The rule by which a granularity is picked from measured candidates (Section 4.3 leaves the choice open;
+    its discussion asks for the memory footprint to be reduced as far as the time cost stays acceptable).
+
+    ``table`` is a sequence of (peak_weight_staging bytes, workspace bytes, milliseconds); an entry with
+    milliseconds <= 0 has not been measured.  A budget of 0 means no limit.  Returns the index of the chosen
+    entry, or None when nothing fits: of the entries that fit both budgets, those no slower than
+    (1 + max_slowdown) times the fastest are kept, and the one with the least gathered weight wins
+    (then the faster, then the earlier one).
+    """
+    fits = []
+    for i, (peak, ws, ms) in enumerate(table):
+        if ms <= 0:
+            continue
+        if staging_budget and peak > staging_budget:
+            continue
+        if workspace_budget and ws > workspace_budget:
+            continue
+        fits.append(i)
+    if not fits:
+        return None
+    fastest = min(table[i][2] for i in fits)
+    keep = [i for i in fits if table[i][2] <= (1.0 + max_slowdown) * fastest]
+    keep.sort(key=lambda i: (table[i][0], table[i][2], i))
+    return keep[0]
+
+
 # ------------------------------------------------------------ sampled entries
 def _idx(a):
     return np.ascontiguousarray(a, dtype=np.int64)

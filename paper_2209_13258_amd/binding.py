@@ -36,7 +36,9 @@ KERNEL_NAMES = ("gather", "gemm_fwd", "gemm_dw", "gemm_dx")
 
 EXPORTS = (
     "osdp_slice_range", "osdp_row_slice_range", "osdp_split_linear_gather_slice",
-    "osdp_split_linear_gather_row_slice", "osdp_split_linear_workspace_bytes", "osdp_split_linear_fwd", "osdp_split_linear_bwd", "osdp_profile_begin", "osdp_profile_end",
+    "osdp_split_linear_gather_row_slice", "osdp_split_linear_workspace_bytes", "osdp_split_linear_fwd",
+    "osdp_split_linear_bwd", "osdp_granularity_candidates", "osdp_granularity_measure",
+    "osdp_granularity_select", "osdp_profile_begin", "osdp_profile_end",
     "osdp_strerror", "osdp_last_error", "osdp_version",
 )
 
@@ -49,7 +51,14 @@ class osdp_shape(ctypes.Structure):
 class osdp_plan(ctypes.Structure):
     _fields_ = [("n_ops", ctypes.c_int32), ("k_per_op", ctypes.POINTER(ctypes.c_int32)),
                 ("zdp_mask", ctypes.POINTER(ctypes.c_uint64)), ("staging", ctypes.c_int32),
-                ("split_dim_per_op", ctypes.POINTER(ctypes.c_uint8))]
+                ("split_dim_per_op", ctypes.POINTER(ctypes.c_uint8)),
+                ("staging_per_op", ctypes.POINTER(ctypes.c_int32))]
+
+
+class osdp_granularity_candidate(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_int32), ("staging", ctypes.c_int32), ("split_dim", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("peak_weight_staging", ctypes.c_size_t),
+                ("workspace", ctypes.c_size_t), ("ms", ctypes.c_double)]
 
 
 class osdp_kernel_stats(ctypes.Structure):
@@ -81,11 +90,18 @@ def _load() -> ctypes.CDLL:
     lib.osdp_split_linear_fwd.argtypes = [shp, pln, i32, vp, i64, vp, vp, i64, vp, ctypes.c_size_t, vp, vp]
     lib.osdp_split_linear_bwd.argtypes = [shp, pln, i32, vp, i64, vp, i64, vp, vp, i64, vp, vp,
                                           ctypes.c_size_t, vp, vp]
+    cnd = ctypes.POINTER(osdp_granularity_candidate)
+    lib.osdp_granularity_candidates.argtypes = [shp, ctypes.POINTER(i32), i32, cnd, i32, ctypes.POINTER(i32)]
+    lib.osdp_granularity_measure.argtypes = [shp, vp, i64, vp, i64, vp, vp, i64, vp, i64, vp, vp, ctypes.c_size_t,
+                                             vp, vp, cnd, i32, i32, i32]
+    lib.osdp_granularity_select.argtypes = [cnd, i32, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_double,
+                                            ctypes.POINTER(i32)]
     lib.osdp_profile_begin.argtypes = [i32]
     lib.osdp_profile_end.argtypes = [ctypes.POINTER(osdp_kernel_stats)]
     for name in ("osdp_slice_range", "osdp_row_slice_range", "osdp_split_linear_gather_slice",
                  "osdp_split_linear_gather_row_slice", "osdp_split_linear_workspace_bytes",
-                 "osdp_split_linear_fwd", "osdp_split_linear_bwd", "osdp_profile_begin", "osdp_profile_end"):
+                 "osdp_split_linear_fwd", "osdp_split_linear_bwd", "osdp_granularity_candidates",
+                 "osdp_granularity_measure", "osdp_granularity_select", "osdp_profile_begin", "osdp_profile_end"):
         getattr(lib, name).restype = ctypes.c_int
     lib.osdp_strerror.argtypes = [ctypes.c_int]
     lib.osdp_strerror.restype = ctypes.c_char_p
@@ -110,17 +126,20 @@ class Plan:
     staging: int = OSDP_STAGING_AUTO
     zdp_mask: Optional[Sequence[int]] = None
     split_dim_per_op: Optional[Sequence[int]] = None
+    staging_per_op: Optional[Sequence[int]] = None
 
     def to_c(self):
         n = len(self.k_per_op)
         ks = (ctypes.c_int32 * n)(*self.k_per_op)
         mask = (ctypes.c_uint64 * n)(*self.zdp_mask) if self.zdp_mask is not None else None
         dims = (ctypes.c_uint8 * n)(*self.split_dim_per_op) if self.split_dim_per_op is not None else None
+        modes = (ctypes.c_int32 * n)(*self.staging_per_op) if self.staging_per_op is not None else None
         p = osdp_plan(n, ctypes.cast(ks, ctypes.POINTER(ctypes.c_int32)),
                       ctypes.cast(mask, ctypes.POINTER(ctypes.c_uint64)) if mask is not None else None,
                       self.staging,
-                      ctypes.cast(dims, ctypes.POINTER(ctypes.c_uint8)) if dims is not None else None)
-        return p, (ks, mask, dims)  # keep the arrays alive with the struct
+                      ctypes.cast(dims, ctypes.POINTER(ctypes.c_uint8)) if dims is not None else None,
+                      ctypes.cast(modes, ctypes.POINTER(ctypes.c_int32)) if modes is not None else None)
+        return p, (ks, mask, dims, modes)  # keep the arrays alive with the struct
 
 
 def _shape(T, I, O, N, k):
@@ -211,6 +230,41 @@ def osdp_split_linear_bwd(X, dY, w_shards, dX, dw_shards, k, workspace, *, plan:
                                      int(dX.data_ptr()), dX.stride(0), _ptrs(dw_shards),
                                      int(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                                      _stream(stream_compute), _stream(stream_copy)))
+
+
+def osdp_granularity_candidates(T, I, O, N, k_list: Optional[Sequence[int]] = None):
+    """The (k, staging mode, split dimension) combinations the kernels take for this shape, as a ctypes array."""
+    shape = _shape(T, I, O, N, 0)
+    ks = (ctypes.c_int32 * len(k_list))(*k_list) if k_list is not None else None
+    nk = len(k_list) if k_list is not None else 0
+    count = ctypes.c_int32()
+    _check(lib.osdp_granularity_candidates(ctypes.byref(shape), ks, nk, None, 0, ctypes.byref(count)))
+    out = (osdp_granularity_candidate * max(count.value, 1))()
+    _check(lib.osdp_granularity_candidates(ctypes.byref(shape), ks, nk, out, count.value, ctypes.byref(count)))
+    return (osdp_granularity_candidate * count.value).from_buffer(out) if count.value else \
+        (osdp_granularity_candidate * 0)()
+
+
+def osdp_granularity_measure(X, dY, w_shards, Y, dX, dw_shards, workspace, cands, *, warmup: int = 2, reps: int = 5,
+                             stream_compute=None, stream_copy=None) -> None:
+    """Times one forward + backward per candidate on the GPU and fills ``cands[i].ms``."""
+    T, I = X.shape
+    O = dY.shape[1]
+    shape = _shape(T, I, O, len(w_shards), 0)
+    _check(lib.osdp_granularity_measure(ctypes.byref(shape), int(X.data_ptr()), X.stride(0), int(dY.data_ptr()),
+                                        dY.stride(0), _ptrs(w_shards), int(Y.data_ptr()), Y.stride(0),
+                                        int(dX.data_ptr()), dX.stride(0), _ptrs(dw_shards),
+                                        int(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                                        _stream(stream_compute), _stream(stream_copy), cands, len(cands), warmup, reps))
+
+
+def osdp_granularity_select(cands, staging_budget: int = 0, workspace_budget: int = 0,
+                            max_slowdown: float = 0.0) -> int:
+    """Index of the candidate the selection rule picks."""
+    chosen = ctypes.c_int32(-1)
+    _check(lib.osdp_granularity_select(cands, len(cands), int(staging_budget), int(workspace_budget),
+                                       float(max_slowdown), ctypes.byref(chosen)))
+    return chosen.value
 
 
 def osdp_profile_begin(max_launches: int = 1 << 16) -> None:

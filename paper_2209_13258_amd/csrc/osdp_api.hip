@@ -111,7 +111,7 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
       return fail(OSDP_ERR_INVALID_ARG, "op_index %d outside the plan's %d operators", op_index, plan->n_ops);
     if (plan->k_per_op) k = plan->k_per_op[op_index];
     if (k < 0) return fail(OSDP_ERR_INVALID_ARG, "plan k must be >= 0 (got %lld)", (long long)k);
-    mode = plan->staging;
+    mode = plan->staging_per_op ? plan->staging_per_op[op_index] : plan->staging;
     if (mode < OSDP_STAGING_AUTO || mode > OSDP_STAGING_HALF)
       return fail(OSDP_ERR_INVALID_ARG, "unknown staging mode %d", mode);
     if (plan->zdp_mask) mask = plan->zdp_mask + op_index;
@@ -640,6 +640,130 @@ osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan
   }
   if (overlap) OSDP_HIP(edge(sc, sp));
   return OSDP_OK;
+}
+
+osdp_status osdp_granularity_candidates(const osdp_shape *shape, const int32_t *k_list, int32_t n_k,
+                                        osdp_granularity_candidate *out, int32_t capacity, int32_t *count) {
+  osdp_status st = check_shape(shape);
+  if (st != OSDP_OK) return st;
+  if (!count) return fail(OSDP_ERR_INVALID_ARG, "count is NULL");
+  if (capacity < 0 || (capacity > 0 && !out)) return fail(OSDP_ERR_INVALID_ARG, "out is NULL or capacity negative");
+  static const int32_t kDefault[] = {1, 2, 3, 4, 6, 8, 12, 16};
+  if (!k_list) {
+    k_list = kDefault;
+    n_k = static_cast<int32_t>(sizeof kDefault / sizeof kDefault[0]);
+  }
+  if (n_k <= 0) return fail(OSDP_ERR_INVALID_ARG, "n_k must be positive");
+  int32_t n = 0;
+  for (int32_t i = 0; i < n_k; ++i) {
+    const int32_t k = k_list[i];
+    if (k < 1) return fail(OSDP_ERR_INVALID_ARG, "k_list[%d] = %d is below 1", i, k);
+    for (uint8_t dim : {uint8_t(OSDP_SPLIT_OUT_FEATURES), uint8_t(OSDP_SPLIT_IN_FEATURES)})
+      for (int32_t mode : {int32_t(OSDP_STAGING_SINGLE), int32_t(OSDP_STAGING_DOUBLE), int32_t(OSDP_STAGING_HALF)}) {
+        // the unsplit operator is the same execution whichever dimension is named, and has nothing to double-buffer
+        if (k == 1 && (mode == OSDP_STAGING_DOUBLE || (mode == OSDP_STAGING_SINGLE && dim != OSDP_SPLIT_OUT_FEATURES))) continue;
+        osdp_plan plan = {1, &k, nullptr, mode, &dim};
+        Resolved f, b;
+        if (resolve(shape, &plan, 0, true, false, &f) != OSDP_OK) continue;  // the kernels do not take this combination
+        if (resolve(shape, &plan, 0, true, true, &b) != OSDP_OK) continue;
+        if (n < capacity) {
+          osdp_granularity_candidate &c = out[n];
+          c.k = k; c.staging = mode; c.split_dim = dim; c.reserved = 0;
+          c.peak_weight_staging = f.peak_staging;
+          c.workspace = std::max(workspace_total(f), workspace_total(b));
+          c.ms = 0.0;
+        }
+        ++n;
+      }
+  }
+  t_last_error.clear();
+  *count = n;
+  return OSDP_OK;
+}
+
+osdp_status osdp_granularity_select(const osdp_granularity_candidate *cands, int32_t n, size_t staging_budget,
+                                    size_t workspace_budget, double max_slowdown, int32_t *chosen) {
+  if (!cands || n <= 0) return fail(OSDP_ERR_INVALID_ARG, "no candidates");
+  if (!chosen) return fail(OSDP_ERR_INVALID_ARG, "chosen is NULL");
+  if (!(max_slowdown >= 0.0)) return fail(OSDP_ERR_INVALID_ARG, "max_slowdown must be >= 0");
+  auto fits = [&](const osdp_granularity_candidate &c) {
+    return c.ms > 0.0 && (staging_budget == 0 || c.peak_weight_staging <= staging_budget) &&
+           (workspace_budget == 0 || c.workspace <= workspace_budget);
+  };
+  double fastest = -1.0;
+  for (int32_t i = 0; i < n; ++i)
+    if (fits(cands[i]) && (fastest < 0.0 || cands[i].ms < fastest)) fastest = cands[i].ms;
+  if (fastest < 0.0)
+    return fail(OSDP_ERR_UNSUPPORTED, "no measured candidate fits the budgets (gathered weights %zu bytes, workspace %zu bytes)",
+                staging_budget, workspace_budget);
+  const double limit = (1.0 + max_slowdown) * fastest;
+  int32_t best = -1;
+  for (int32_t i = 0; i < n; ++i) {
+    const osdp_granularity_candidate &c = cands[i];
+    if (!fits(c) || c.ms > limit) continue;
+    if (best < 0 || c.peak_weight_staging < cands[best].peak_weight_staging ||
+        (c.peak_weight_staging == cands[best].peak_weight_staging && c.ms < cands[best].ms))
+      best = i;
+  }
+  *chosen = best;
+  return OSDP_OK;
+}
+
+osdp_status osdp_granularity_measure(const osdp_shape *shape, const void *X, int64_t ldx, const void *dY, int64_t lddy,
+                                     const void *const *w_shards, void *Y, int64_t ldy, void *dX, int64_t lddx,
+                                     void *const *dw_shards, void *workspace, size_t workspace_bytes, void *stream_compute,
+                                     void *stream_copy, osdp_granularity_candidate *cands, int32_t n, int32_t warmup,
+                                     int32_t reps) {
+  osdp_status st = check_shape(shape);
+  if (st != OSDP_OK) return st;
+  if (!cands || n <= 0) return fail(OSDP_ERR_INVALID_ARG, "no candidates");
+  if (warmup < 0 || reps < 1) return fail(OSDP_ERR_INVALID_ARG, "warmup must be >= 0 and reps >= 1");
+  hipStream_t sc = static_cast<hipStream_t>(stream_compute), sp = static_cast<hipStream_t>(stream_copy);
+  const bool two_streams = sp != nullptr && sp != sc;
+  // everything is checked for every candidate before the first launch
+  for (int32_t i = 0; i < n; ++i) {
+    const osdp_granularity_candidate &c = cands[i];
+    const uint8_t dim = static_cast<uint8_t>(c.split_dim);
+    osdp_plan plan = {1, &c.k, nullptr, c.staging, &dim};
+    if (c.k < 1 || c.split_dim < 0 || c.split_dim > 1) return fail(OSDP_ERR_INVALID_ARG, "candidate %d is malformed", i);
+    for (int is_bwd = 0; is_bwd < 2; ++is_bwd) {
+      Resolved r;
+      if ((st = resolve(shape, &plan, 0, two_streams, is_bwd != 0, &r)) != OSDP_OK) return st;
+      if ((st = check_workspace(r, workspace, workspace_bytes)) != OSDP_OK) return st;
+    }
+  }
+  hipEvent_t t0 = nullptr, t1 = nullptr;
+  OSDP_HIP(hipEventCreate(&t0));
+  hipError_t e = hipEventCreate(&t1);
+  if (e != hipSuccess) {
+    (void)hipEventDestroy(t0);
+    return fail_hip(e, "hipEventCreate");
+  }
+  st = OSDP_OK;
+  for (int32_t i = 0; i < n && st == OSDP_OK; ++i) {
+    osdp_granularity_candidate &c = cands[i];
+    const uint8_t dim = static_cast<uint8_t>(c.split_dim);
+    osdp_plan plan = {1, &c.k, nullptr, c.staging, &dim};
+    for (int32_t rep = -warmup; rep < reps && st == OSDP_OK; ++rep) {
+      if (rep == 0 && (e = hipEventRecord(t0, sc)) != hipSuccess) st = fail_hip(e, "hipEventRecord");
+      if (st == OSDP_OK)
+        st = osdp_split_linear_fwd(shape, &plan, 0, X, ldx, w_shards, Y, ldy, workspace, workspace_bytes, stream_compute, stream_copy);
+      if (st == OSDP_OK)
+        st = osdp_split_linear_bwd(shape, &plan, 0, X, ldx, dY, lddy, w_shards, dX, lddx, dw_shards, workspace,
+                                   workspace_bytes, stream_compute, stream_copy);
+    }
+    if (st != OSDP_OK) break;
+    float ms = 0.f;
+    if ((e = hipEventRecord(t1, sc)) != hipSuccess || (e = hipEventSynchronize(t1)) != hipSuccess ||
+        (e = hipEventElapsedTime(&ms, t0, t1)) != hipSuccess) {
+      st = fail_hip(e, "timing a candidate");
+      break;
+    }
+    c.ms = static_cast<double>(ms) / reps;
+  }
+  (void)hipEventDestroy(t0);
+  (void)hipEventDestroy(t1);
+  return st;
 }
 
 osdp_status osdp_profile_begin(int32_t max_launches) {

@@ -22,7 +22,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(osdp.binding.osdp_shape) == 32
-    assert ctypes.sizeof(osdp.binding.osdp_plan) == 40
+    assert ctypes.sizeof(osdp.binding.osdp_plan) == 48
+    assert ctypes.sizeof(osdp.binding.osdp_granularity_candidate) == 40
     assert ctypes.sizeof(osdp.binding.osdp_kernel_stats) == 32
 
 
@@ -130,6 +131,18 @@ def test_plan_vector_selects_k():
     with pytest.raises(osdp.OsdpError) as e:
         osdp.osdp_split_linear_workspace_bytes(16384, 2560, 10240, 8, 1, False, plan, 4)
     assert e.value.status == osdp.binding.OSDP_ERR_INVALID_ARG
+
+
+def test_plan_vector_selects_staging_and_split_dimension_per_operator(oracle):
+    T, I, O, N = 256, 512, 1024, 4
+    plan = osdp.Plan([4, 4, 4, 4], staging=osdp.OSDP_STAGING_DOUBLE, split_dim_per_op=[0, 1, 0, 1],
+                     staging_per_op=[osdp.OSDP_STAGING_SINGLE, osdp.OSDP_STAGING_SINGLE, osdp.OSDP_STAGING_DOUBLE,
+                                     osdp.OSDP_STAGING_HALF])
+    peaks = [osdp.osdp_split_linear_workspace_bytes(T, I, O, N, 0, True, plan, n)[1] for n in range(4)]
+    one = oracle.peak_staging_bytes(I, O, 4, 1, 2)
+    assert peaks == [one, oracle.peak_staging_bytes_rows(I, O, 4, 1, 2), 2 * one, one]
+    with pytest.raises(osdp.OsdpError):
+        osdp.osdp_split_linear_workspace_bytes(T, I, O, N, 0, True, osdp.Plan([4], staging_per_op=[9]))
 
 
 def test_dp_slices_are_rejected_as_unsupported():

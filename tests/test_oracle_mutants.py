@@ -26,12 +26,12 @@ MUTANTS = {
     "gather_reversed_columns": ("Ws[r * w + c] = shards[s][off];", "Ws[r * w + (w - 1 - c)] = shards[s][off];"),
     "staging_ignores_uneven_slices": ("return slots * wmax * I * elem_bytes;", "return slots * (O / k) * I * elem_bytes;"),
     "fwd_concat_offset": ("memcpy(Y + t * O + c0, Yj + t * w, (size_t)w * sizeof(double));",
-                          "memcpy(Y + t * O + j * w, Yj + t * w, (size_t)w * sizeof(double));"),
+                          "memcpy(Y + t * O + (O - c0 - w), Yj + t * w, (size_t)w * sizeof(double));"),
     "dw_scatter_column": ("dW_shards[s][off] = dWj[r * w + c];", "dW_shards[s][off] = dWj[r * w + (c + 1) % w];"),
     "rows_fwd_wrong_x_offset": ("osdp_oracle_matmul_fwd(T, w, O, X + r0, I, Ws, O, part); /* X[:, r0:r1] . Ws */",
                                 "osdp_oracle_matmul_fwd(T, w, O, X, I, Ws, O, part); /* X[:, r0:r1] . Ws */"),
     "rows_dx_concat_offset": ("memcpy(dX + t * I + r0, dXj + t * w, (size_t)w * sizeof(double));",
-                              "memcpy(dX + t * I + j * w, dXj + t * w, (size_t)w * sizeof(double));"),
+                              "memcpy(dX + t * I + (I - r0 - w), dXj + t * w, (size_t)w * sizeof(double));"),
     "rows_dw_scatter_row": ("osdp_oracle_locate(I, O, N, r0 + r, c, &s, &off);\n        dW_shards[s][off] = dWj[r * O + c];",
                             "osdp_oracle_locate(I, O, N, r0 + r, c, &s, &off);\n        dW_shards[s][off] = dWj[((r + 1) % w) * O + c];"),
     "widen_drops_sign": ("uint32_t u = ((uint32_t)b) << 16;", "uint32_t u = ((uint32_t)(b & 0x7fff)) << 16;"),
