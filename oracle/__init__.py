@@ -85,6 +85,11 @@ def _load():
         lib.osdp_oracle_split_fwd_rows.argtypes = [_i64] * 5 + [_p] * 4
         lib.osdp_oracle_split_bwd_rows.restype = ctypes.c_int
         lib.osdp_oracle_split_bwd_rows.argtypes = [_i64] * 5 + [_p] * 6
+        lib.osdp_oracle_split_fwd_mixed.restype = ctypes.c_int
+        lib.osdp_oracle_split_fwd_mixed.argtypes = [_i64] * 5 + [ctypes.c_int, ctypes.c_uint64, _p, _p, _p, _i64, _p, _p]
+        lib.osdp_oracle_split_bwd_mixed.restype = ctypes.c_int
+        lib.osdp_oracle_split_bwd_mixed.argtypes = [_i64] * 5 + [ctypes.c_int, ctypes.c_uint64, _p, _p, _p, _p, _i64,
+                                                                 _p, _p, _p, _p]
         lib.osdp_oracle_sample_y.restype = None
         lib.osdp_oracle_sample_y.argtypes = [_i64] * 4 + [_p, _p, _i64, _p, _p, _p]
         lib.osdp_oracle_sample_dx.restype = None
@@ -344,6 +349,76 @@ def split_bwd_rows(X, dY, shards, O: int, k: int):
     if rc != 0:
         raise MemoryError("oracle allocation failed")
     return dX, dW, int(peak.value)
+
+
+# ------------------------------------------------------ slices in DP or ZDP mode
+def _dp_pointers(w_dp, k, zdp_mask, rows_needed, cols_needed, ld_dp):
+    """ctypes array of k weight pointers; a DP slice must cover (rows - 1) * ld + cols elements."""
+    keep, ptrs = [], []
+    for j in range(k):
+        if (zdp_mask >> j) & 1:
+            ptrs.append(None)        # never looked at
+            continue
+        a = np.ascontiguousarray(w_dp[j], dtype=np.uint16).reshape(-1)
+        need = (rows_needed[j] - 1) * ld_dp + cols_needed[j]
+        if a.size < need:
+            raise ValueError(f"DP slice {j} holds {a.size} elements, {need} needed")
+        keep.append(a)
+        ptrs.append(a.ctypes.data)
+    return (ctypes.c_void_p * k)(*ptrs), keep
+
+
+def _slice_shapes(I, O, k, rows):
+    keff = max(k, 1)
+    rng = [row_slice_range(I, k, j) if rows else slice_range(O, k, j) for j in range(keff)]
+    sr = [(b - a) if rows else I for a, b in rng]
+    sc = [O if rows else (b - a) for a, b in rng]
+    return keff, sr, sc
+
+
+def split_fwd_mixed(X, shards, O: int, k: int, zdp_mask: int, w_dp, ld_dp: int, rows: bool = False):
+    """Forward with every slice in its own mode (Section 3.3, last paragraph): bit j of zdp_mask set = slice j is
+    gathered from the shards, clear = slice j is read where it lies in w_dp[j] (leading dimension ld_dp).
+    Returns (Y fp64, peak staging bytes)."""
+    X = _u16(X)
+    T, I = X.shape
+    N = len(shards)
+    sh = _check_shards(shards, I, O, N)
+    keff, sr, sc = _slice_shapes(I, O, k, rows)
+    ptrs, keep = _dp_pointers(w_dp, keff, zdp_mask, sr, sc, ld_dp)
+    Y = np.empty((T, O), dtype=np.float64)
+    peak = _i64()
+    rc = _load().osdp_oracle_split_fwd_mixed(T, I, O, N, k, int(rows), zdp_mask, _ptr(X), _ptr_array(sh), ptrs, ld_dp,
+                                             _ptr(Y), ctypes.byref(peak))
+    if rc != 0:
+        raise MemoryError("oracle allocation failed")
+    del keep
+    return Y, int(peak.value)
+
+
+def split_bwd_mixed(X, dY, shards, O: int, k: int, zdp_mask: int, w_dp, ld_dp: int, rows: bool = False):
+    """Backward with every slice in its own mode.  Returns (dX fp64, dW shards fp64 with NaN wherever no ZDP slice
+    wrote, list of per-slice DP gradients [slice rows x ld_dp] fp64 (None for ZDP slices; NaN outside the slice's
+    columns), peak staging bytes)."""
+    X = _u16(X)
+    T, I = X.shape
+    dY = _u16(dY, (T, O))
+    N = len(shards)
+    sh = _check_shards(shards, I, O, N)
+    L = shard_len(I, O, N)
+    keff, sr, sc = _slice_shapes(I, O, k, rows)
+    ptrs, keep = _dp_pointers(w_dp, keff, zdp_mask, sr, sc, ld_dp)
+    dX = np.empty((T, I), dtype=np.float64)
+    dW = [np.full(L, np.nan, dtype=np.float64) for _ in range(N)]
+    dw_dp = [None if (zdp_mask >> j) & 1 else np.full((sr[j], ld_dp), np.nan, dtype=np.float64) for j in range(keff)]
+    dptrs = (ctypes.c_void_p * keff)(*[None if a is None else a.ctypes.data for a in dw_dp])
+    peak = _i64()
+    rc = _load().osdp_oracle_split_bwd_mixed(T, I, O, N, k, int(rows), zdp_mask, _ptr(X), _ptr(dY), _ptr_array(sh), ptrs,
+                                             ld_dp, _ptr(dX), _ptr_array(dW), dptrs, ctypes.byref(peak))
+    if rc != 0:
+        raise MemoryError("oracle allocation failed")
+    del keep
+    return dX, dW, dw_dp, int(peak.value)
 
 
 # ------------------------------------------------ choice of the slice granularity

@@ -402,6 +402,133 @@ ORACLE_API int osdp_oracle_split_bwd_rows(int64_t T, int64_t I, int64_t O, int64
   return 0;
 }
 
+/* ---- slices treated one by one: DP or ZDP ---------------------------------
+ * Section 3.3, last paragraph: once an operator is cut into slices, each slice
+ * can be given its own mode.  A ZDP slice lives in the shards and is gathered
+ * before every use (as above); a DP slice is replicated, so it is used where it
+ * lies and nothing is staged for it, and its gradient is a full (unsharded)
+ * array of the slice's shape.  Bit j of zdp_mask set: slice j is ZDP.
+ * w_dp[j] (DP slices only) is the slice, row-major with leading dimension
+ * ld_dp: [I x w_j] for column slices, [h_j x O] for row slices (rows != 0);
+ * dw_dp[j] receives its gradient in the same shape (fp64).  Entries of ZDP
+ * slices in w_dp / dw_dp are not looked at, nor are the shards' elements that
+ * belong to DP slices; dW_shards is written for ZDP slices only. */
+static void slice_range_along(int64_t I, int64_t O, int64_t k, int rows, int64_t j, int64_t *a0, int64_t *a1) {
+  if (rows) osdp_oracle_row_slice_range(I, k, j, a0, a1);
+  else osdp_oracle_slice_range(O, k, j, a0, a1);
+}
+
+ORACLE_API int osdp_oracle_split_fwd_mixed(int64_t T, int64_t I, int64_t O, int64_t N, int64_t k, int rows,
+                                           uint64_t zdp_mask, const uint16_t *X,
+                                           const uint16_t *const *shards, const uint16_t *const *w_dp,
+                                           int64_t ld_dp, double *Y, int64_t *peak_staging) {
+  staging_meter m = {0, 0};
+  k = eff_k(k);
+  if (rows)
+    for (int64_t e = 0; e < T * O; ++e) Y[e] = 0.0;
+  for (int64_t j = 0; j < k; ++j) {
+    int64_t a0, a1;
+    slice_range_along(I, O, k, rows, j, &a0, &a1);
+    int64_t w = a1 - a0;
+    if (w == 0) continue;
+    int zdp = (int)((zdp_mask >> j) & 1u);
+    int64_t bytes = (rows ? w * O : I * w) * (int64_t)sizeof(uint16_t);
+    uint16_t *Ws = NULL;
+    const uint16_t *Wj;   /* the slice's weights and their leading dimension */
+    int64_t ldw;
+    if (zdp) {
+      Ws = staging_alloc(&m, bytes);
+      if (!Ws) return -1;
+      if (rows) osdp_oracle_gather_row_slice(I, O, N, k, j, shards, Ws);
+      else osdp_oracle_gather_slice(I, O, N, k, j, shards, Ws);
+      Wj = Ws;
+      ldw = rows ? O : w;
+    } else {
+      Wj = w_dp[j];
+      ldw = ld_dp;
+    }
+    if (rows) {
+      double *part = (double *)malloc((size_t)T * O * sizeof(double));
+      if (!part) { free(Ws); return -1; }
+      osdp_oracle_matmul_fwd(T, w, O, X + a0, I, Wj, ldw, part);
+      for (int64_t e = 0; e < T * O; ++e) Y[e] += part[e];
+      free(part);
+    } else {
+      double *Yj = (double *)malloc((size_t)T * w * sizeof(double));
+      if (!Yj) { free(Ws); return -1; }
+      osdp_oracle_matmul_fwd(T, I, w, X, I, Wj, ldw, Yj);
+      for (int64_t t = 0; t < T; ++t)
+        memcpy(Y + t * O + a0, Yj + t * w, (size_t)w * sizeof(double));
+      free(Yj);
+    }
+    if (zdp) staging_free(&m, Ws, bytes);
+  }
+  if (peak_staging) *peak_staging = m.peak;
+  return 0;
+}
+
+ORACLE_API int osdp_oracle_split_bwd_mixed(int64_t T, int64_t I, int64_t O, int64_t N, int64_t k, int rows,
+                                           uint64_t zdp_mask, const uint16_t *X, const uint16_t *dY,
+                                           const uint16_t *const *shards, const uint16_t *const *w_dp,
+                                           int64_t ld_dp, double *dX, double *const *dW_shards,
+                                           double *const *dw_dp, int64_t *peak_staging) {
+  staging_meter m = {0, 0};
+  k = eff_k(k);
+  if (!rows)
+    for (int64_t e = 0; e < T * I; ++e) dX[e] = 0.0;
+  for (int64_t j = 0; j < k; ++j) {
+    int64_t a0, a1;
+    slice_range_along(I, O, k, rows, j, &a0, &a1);
+    int64_t w = a1 - a0;
+    if (w == 0) continue;
+    int zdp = (int)((zdp_mask >> j) & 1u);
+    int64_t sr = rows ? w : I, sc = rows ? O : w;   /* the slice is sr x sc */
+    int64_t bytes = sr * sc * (int64_t)sizeof(uint16_t);
+    uint16_t *Ws = NULL;
+    const uint16_t *Wj;
+    int64_t ldw;
+    if (zdp) {
+      Ws = staging_alloc(&m, bytes);
+      if (!Ws) return -1;
+      if (rows) osdp_oracle_gather_row_slice(I, O, N, k, j, shards, Ws);
+      else osdp_oracle_gather_slice(I, O, N, k, j, shards, Ws);
+      Wj = Ws;
+      ldw = sc;
+    } else {
+      Wj = w_dp[j];
+      ldw = ld_dp;
+    }
+    double *dWj = (double *)malloc((size_t)sr * sc * sizeof(double));
+    double *part = (double *)malloc((size_t)T * sr * sizeof(double));   /* dY-side product, T x (rows of the slice) */
+    if (!dWj || !part) { free(Ws); free(dWj); free(part); return -1; }
+    if (rows) {
+      osdp_oracle_matmul_dw(T, w, O, X + a0, I, dY, O, dWj);   /* X[:, a0:a1]^T . dY */
+      osdp_oracle_matmul_dx(T, w, O, dY, O, Wj, ldw, part);    /* dY . Wj^T  -> dX[:, a0:a1] */
+      for (int64_t t = 0; t < T; ++t)
+        memcpy(dX + t * I + a0, part + t * w, (size_t)w * sizeof(double));
+    } else {
+      osdp_oracle_matmul_dw(T, I, w, X, I, dY + a0, O, dWj);   /* X^T . dY[:, a0:a1] */
+      osdp_oracle_matmul_dx(T, I, w, dY + a0, O, Wj, ldw, part);
+      for (int64_t e = 0; e < T * I; ++e) dX[e] += part[e];
+    }
+    for (int64_t r = 0; r < sr; ++r)
+      for (int64_t c = 0; c < sc; ++c) {
+        if (zdp) {
+          int64_t s, off;
+          osdp_oracle_locate(I, O, N, rows ? a0 + r : r, rows ? c : a0 + c, &s, &off);
+          dW_shards[s][off] = dWj[r * sc + c];
+        } else {
+          dw_dp[j][r * ld_dp + c] = dWj[r * sc + c];
+        }
+      }
+    free(part);
+    free(dWj);
+    if (zdp) staging_free(&m, Ws, bytes);
+  }
+  if (peak_staging) *peak_staging = m.peak;
+  return 0;
+}
+
 /* ---- single entries of the definition, for spot checks at full size ------ */
 
 /* out[n] = Y[rows[n], cols[n]] from the sharded W (no reassembly). */

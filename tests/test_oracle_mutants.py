@@ -20,7 +20,8 @@ MUTANTS = {
                           "osdp_oracle_bf16_to_f64(dY[t * lddy + (O - 1 - o)]) * osdp_oracle_bf16_to_f64(W[i * ldw + o]);"),
     "dw_dropped_term": ("    for (int64_t t = 0; t < T; ++t) {\n      double x = osdp_oracle_bf16_to_f64(X[t * ldx + i]);\n      const uint16_t *d = dY + t * lddy;",
                         "    for (int64_t t = 0; t < T - 1; ++t) {\n      double x = osdp_oracle_bf16_to_f64(X[t * ldx + i]);\n      const uint16_t *d = dY + t * lddy;"),
-    "dx_partial_sign": ("dX[e] += part[e];", "dX[e] -= part[e];"),
+    "dx_partial_sign": ("\n    for (int64_t e = 0; e < T * I; ++e) dX[e] += part[e];", "\n    for (int64_t e = 0; e < T * I; ++e) dX[e] -= part[e];"),
+    "mixed_dx_partial_sign": ("\n      for (int64_t e = 0; e < T * I; ++e) dX[e] += part[e];", "\n      for (int64_t e = 0; e < T * I; ++e) dX[e] -= part[e];"),
     "slice_bound_rounds_up": ("*c1 = ((j + 1) * O) / k;", "*c1 = ((j + 1) * O + k - 1) / k;"),
     "shard_length_off_by_one": ("return (I * O + N - 1) / N;", "return (I * O + N) / N;"),
     "gather_reversed_columns": ("Ws[r * w + c] = shards[s][off];", "Ws[r * w + (w - 1 - c)] = shards[s][off];"),
@@ -34,6 +35,10 @@ MUTANTS = {
                               "memcpy(dX + t * I + (I - r0 - w), dXj + t * w, (size_t)w * sizeof(double));"),
     "rows_dw_scatter_row": ("osdp_oracle_locate(I, O, N, r0 + r, c, &s, &off);\n        dW_shards[s][off] = dWj[r * O + c];",
                             "osdp_oracle_locate(I, O, N, r0 + r, c, &s, &off);\n        dW_shards[s][off] = dWj[((r + 1) % w) * O + c];"),
+    "mixed_dp_gradient_goes_to_shards": ("        if (zdp) {\n          int64_t s, off;", "        if (1) {\n          int64_t s, off;"),
+    "mixed_fwd_concat_offset": ("memcpy(Y + t * O + a0, Yj + t * w, (size_t)w * sizeof(double));",
+                                "memcpy(Y + t * O + (O - a0 - w), Yj + t * w, (size_t)w * sizeof(double));"),
+    "mixed_dp_gradient_reversed": ("dw_dp[j][r * ld_dp + c] = dWj[r * sc + c];", "dw_dp[j][r * ld_dp + c] = dWj[r * sc + (sc - 1 - c)];"),
     "widen_drops_sign": ("uint32_t u = ((uint32_t)b) << 16;", "uint32_t u = ((uint32_t)(b & 0x7fff)) << 16;"),
     "sample_dw_short_sum": ("    for (int64_t t = 0; t < T; ++t)\n      acc += osdp_oracle_bf16_to_f64(X[t * I + i]) * osdp_oracle_bf16_to_f64(dY[t * O + o]);",
                             "    for (int64_t t = 1; t < T; ++t)\n      acc += osdp_oracle_bf16_to_f64(X[t * I + i]) * osdp_oracle_bf16_to_f64(dY[t * O + o]);"),

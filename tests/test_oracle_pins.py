@@ -206,6 +206,107 @@ def test_reduction_split_route_reconstructs_the_unsplit_result(oracle, T, I, O, 
         assert peak_f * k == oracle.weight_bytes(I, O, 2)  # size / granularity
 
 
+def _mixed_case(oracle, seed, T, I, O, N, k, mask, rows, full_layout):
+    """Inputs for the per-slice DP/ZDP route in which the two weight sources disagree: the shards hold W with a
+    NaN pattern wherever a DP slice lies, the DP replicas hold other values.  Returns the inputs and the matrix
+    the operator really uses (float64)."""
+    d = wl.small_case(seed, T, I, O, N, w_std=1.0)
+    other = wl.small_case(seed + 100, T, I, O, N, w_std=1.0)
+    W = np.concatenate(d["W_shards"])[: I * O].reshape(I, O).copy()
+    W2 = np.concatenate(other["W_shards"])[: I * O].reshape(I, O)
+    keff = max(k, 1)
+    rng = [(oracle.row_slice_range(I, k, j) if rows else oracle.slice_range(O, k, j)) for j in range(keff)]
+    used = W.copy()
+    w_dp = [None] * keff
+    ld = O if (rows or full_layout) else max(b - a for a, b in rng)
+    for j, (a, b) in enumerate(rng):
+        if (mask >> j) & 1:
+            continue
+        sl = (slice(a, b), slice(None)) if rows else (slice(None), slice(a, b))
+        used[sl] = W2[sl]
+        W[sl] = 0x7FC0                       # what the shards hold there must never be read
+        if rows:
+            w_dp[j] = W2[a:b].copy()
+        elif full_layout:
+            w_dp[j] = np.ascontiguousarray(W2).reshape(-1)[a:]      # the slice where it lies in a full [I x O] copy
+        else:
+            buf = np.full((I, ld), 0x7FC0, dtype=np.uint16)   # compact replica, padded to the common ld
+            buf[:, : b - a] = W2[:, a:b]
+            w_dp[j] = buf
+    L = oracle.shard_len(I, O, N)
+    flat = np.full(N * L, 0x7FC0, dtype=np.uint16)
+    flat[: I * O] = W.reshape(-1)
+    shards = [flat[s * L:(s + 1) * L].copy() for s in range(N)]
+    return d["X"], d["dY"], shards, w_dp, ld, rng, widen(used)
+
+
+@pytest.mark.parametrize("rows", [False, True])
+@pytest.mark.parametrize("full_layout", [False, True])
+@pytest.mark.parametrize("T,I,O,N,k,mask", [
+    (9, 16, 24, 2, 4, 0b0001),   # the paper's example: one slice of four in ZDP mode, three in DP mode
+    (9, 16, 24, 4, 4, 0b1010), (5, 12, 20, 3, 6, 0b110011), (7, 10, 13, 4, 3, 0b000), (7, 10, 13, 4, 3, 0b111),
+    (6, 8, 8, 8, 1, 0b0), (6, 8, 8, 8, 0, 0b1)])
+def test_per_slice_modes_use_each_slice_from_its_own_place(oracle, T, I, O, N, k, mask, rows, full_layout):
+    """Section 3.3, last paragraph.  Expected values: numpy's float64 products with the matrix assembled by hand
+    from the two sources; gradients land in the shards (ZDP slices) or in the slice's own array (DP slices) and
+    nowhere else; only ZDP slices are ever staged."""
+    X, dY, shards, w_dp, ld, rng, Wf = _mixed_case(oracle, 9, T, I, O, N, k, mask, rows, full_layout)
+    Xf, dYf = widen(X), widen(dY)
+    Y, peak_f = oracle.split_fwd_mixed(X, shards, O, k, mask, w_dp, ld, rows=rows)
+    dX, dWs, dw_dp, peak_b = oracle.split_bwd_mixed(X, dY, shards, O, k, mask, w_dp, ld, rows=rows)
+    np.testing.assert_allclose(Y, Xf @ Wf, rtol=0, atol=1e-12 * np.abs(Xf @ Wf).max())
+    np.testing.assert_allclose(dX, dYf @ Wf.T, rtol=0, atol=1e-12 * np.abs(dYf @ Wf.T).max())
+    dW_ref = Xf.T @ dYf
+    dense = oracle.dense_from_f64_shards(dWs, I, O)
+    for j, (a, b) in enumerate(rng):
+        sl = (slice(a, b), slice(None)) if rows else (slice(None), slice(a, b))
+        if (mask >> j) & 1:
+            np.testing.assert_allclose(dense[sl], dW_ref[sl], rtol=0, atol=1e-12 * np.abs(dW_ref).max())
+            assert dw_dp[j] is None
+        else:
+            assert np.isnan(dense[sl]).all()          # a DP slice's gradient is not sharded
+            h, w = (b - a, O) if rows else (I, b - a)
+            np.testing.assert_allclose(dw_dp[j][:h, :w], dW_ref[sl], rtol=0, atol=1e-12 * np.abs(dW_ref).max())
+            if not full_layout:
+                assert np.isnan(dw_dp[j][:, w:]).all()    # nothing written outside the slice's columns
+    zdp = [(b - a) for j, (a, b) in enumerate(rng) if (mask >> j) & 1]
+    want_peak = (max(zdp) * (O if rows else I) * 2) if zdp else 0
+    assert peak_f == peak_b == want_peak
+
+
+@pytest.mark.parametrize("rows", [False, True])
+def test_all_zdp_mask_is_the_plain_split_route(oracle, rows):
+    T, I, O, N, k = 9, 16, 24, 4, 4
+    d = wl.small_case(10, T, I, O, N, w_std=1.0)
+    fwd, bwd = (oracle.split_fwd_rows, oracle.split_bwd_rows) if rows else (oracle.split_fwd, oracle.split_bwd)
+    Y, _ = oracle.split_fwd_mixed(d["X"], d["W_shards"], O, k, 0b1111, [None] * k, O, rows=rows)
+    dX, dWs, dw_dp, _ = oracle.split_bwd_mixed(d["X"], d["dY"], d["W_shards"], O, k, 0b1111, [None] * k, O, rows=rows)
+    assert np.array_equal(Y, fwd(d["X"], d["W_shards"], O, k)[0])
+    ref_dX, ref_dWs, _ = bwd(d["X"], d["dY"], d["W_shards"], O, k)
+    assert np.array_equal(dX, ref_dX) and dw_dp == [None] * k
+    assert np.array_equal(oracle.dense_from_f64_shards(dWs, I, O), oracle.dense_from_f64_shards(ref_dWs, I, O))
+
+
+def test_per_slice_modes_exact_on_small_integers(oracle):
+    """Integer-valued inputs: every product and sum is exact in float64, so the expected values are exact."""
+    T, I, O, N, k, mask = 5, 8, 12, 4, 3, 0b010
+    g = np.random.default_rng(11)
+    to_bits = lambda a: wl.f32_to_bf16_bits(a.astype(np.float32))
+    Xi, dYi = g.integers(-4, 5, (T, I)), g.integers(-4, 5, (T, O))
+    Wz, Wd = g.integers(-4, 5, (I, O)), g.integers(-4, 5, (I, O))
+    used = Wd.copy()
+    used[:, 4:8] = Wz[:, 4:8]                 # slice 1 is the ZDP one
+    shards = oracle.shard(to_bits(Wz), N)
+    w_dp = [to_bits(Wd[:, 0:4]), None, to_bits(Wd[:, 8:12])]
+    Y, _ = oracle.split_fwd_mixed(to_bits(Xi), shards, O, k, mask, w_dp, 4)
+    dX, dWs, dw_dp, _ = oracle.split_bwd_mixed(to_bits(Xi), to_bits(dYi), shards, O, k, mask, w_dp, 4)
+    assert np.array_equal(Y, (Xi @ used).astype(np.float64))
+    assert np.array_equal(dX, (dYi @ used.T).astype(np.float64))
+    dW = Xi.T @ dYi
+    assert np.array_equal(dw_dp[0], dW[:, 0:4]) and np.array_equal(dw_dp[2], dW[:, 8:12])
+    assert np.array_equal(oracle.dense_from_f64_shards(dWs, I, O)[:, 4:8], dW[:, 4:8])
+
+
 def test_split_route_ignores_shard_padding(oracle):
     T, I, O, N, k = 4, 5, 7, 4, 3
     d = wl.small_case(5, T, I, O, N)
