@@ -74,7 +74,7 @@ extern "C" {
 typedef enum {
   OSDP_OK = 0,
   OSDP_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, k > O, slice out of range, ld too small */
-  OSDP_ERR_UNSUPPORTED = -2, /* legal problem the kernels do not handle (alignment, N > 64, DP slices) */
+  OSDP_ERR_UNSUPPORTED = -2, /* legal problem the kernels or this entry point do not handle (alignment, N > 64) */
   OSDP_ERR_WORKSPACE = -3,   /* workspace_bytes smaller than osdp_split_linear_workspace_bytes says */
   OSDP_ERR_HIP = -4          /* a HIP runtime call failed; outputs are undefined */
 } osdp_status;
@@ -112,9 +112,10 @@ typedef enum {
 typedef struct {
   int32_t n_ops;            /* number of operators the arrays describe                         */
   const int32_t *k_per_op;  /* [n_ops] slice granularity; overrides shape->k for op_index      */
-  const uint64_t *zdp_mask; /* [n_ops] or NULL; bit j set: slice j is gathered (ZDP mode).     */
-                            /* Only NULL / all slices set is supported (Section 3.3 describes  */
-                            /* mixing DP and ZDP slices; not built here).                      */
+  const uint64_t *zdp_mask; /* [n_ops] or NULL (= every slice ZDP); bit j set: slice j is      */
+                            /* sharded and gathered (ZDP mode), clear: slice j is replicated   */
+                            /* (DP mode, Section 3.3: each slice may get its own mode) and is  */
+                            /* used from the caller's replica: the _mixed entry points only.   */
   int32_t staging;          /* an osdp_staging_mode                                            */
   const uint8_t *split_dim_per_op; /* [n_ops] or NULL (= all OSDP_SPLIT_OUT_FEATURES): an       */
                             /* osdp_split_dim per operator                                     */
@@ -191,6 +192,40 @@ OSDP_API osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_p
                                   const void *const *w_shards, void *dX, int64_t lddx,
                                   void *const *dw_shards, void *workspace, size_t workspace_bytes,
                                   void *stream_compute, void *stream_copy);
+
+/* ---- every slice in its own mode -------------------------------------------
+ * Section 3.3, last paragraph: once an operator is cut into slices each slice
+ * can be DP or ZDP on its own (the paper's example: 1 of 4 slices ZDP, 3 DP).
+ * A ZDP slice (plan->zdp_mask bit set) is handled as above: gathered from the
+ * shards into a staging slot before every use, its gradient written into
+ * dw_shards.  A DP slice is replicated on every worker: it is read where it
+ * lies in the caller's replica (no gather, no staging, so the gathered-weight
+ * peak counts ZDP slices only) and its gradient is a plain array of the same
+ * shape.
+ *   w_dp  : host array of k device pointers; w_dp[j] (DP slices only; others
+ *           ignored) is slice j, row-major bf16 with leading dimension ld_dp:
+ *           [I x w_j] for column slices, [h_j x O] for row slices.  A full
+ *           row-major copy of W serves with w_dp[j] = W + c0_j, ld_dp = O
+ *           (row slices: W + r0_j*O).  May be NULL when no slice is DP.
+ *   dw_dp : the same for the gradients (written, DP slices only).
+ *   ld_dp : multiple of 8, >= the widest DP slice's columns.
+ * The shard buffers keep the layout of the whole matrix, so a plan can change
+ * a slice's mode without re-sharding; their elements inside DP slices are
+ * never read, and dw_shards is not written there.  Everything else (shapes,
+ * workspace from osdp_split_linear_workspace_bytes, streams, errors) as for
+ * osdp_split_linear_fwd / _bwd, which these calls equal when every slice is
+ * ZDP.  Results are bit-identical to the all-ZDP plan on the same weights. */
+OSDP_API osdp_status osdp_split_linear_fwd_mixed(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index,
+                                                 const void *X, int64_t ldx, const void *const *w_shards,
+                                                 const void *const *w_dp, int64_t ld_dp, void *Y, int64_t ldy,
+                                                 void *workspace, size_t workspace_bytes, void *stream_compute,
+                                                 void *stream_copy);
+OSDP_API osdp_status osdp_split_linear_bwd_mixed(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index,
+                                                 const void *X, int64_t ldx, const void *dY, int64_t lddy,
+                                                 const void *const *w_shards, const void *const *w_dp, int64_t ld_dp,
+                                                 void *dX, int64_t lddx, void *const *dw_shards, void *const *dw_dp,
+                                                 void *workspace, size_t workspace_bytes, void *stream_compute,
+                                                 void *stream_copy);
 
 /* ---- automatic slice granularity ------------------------------------------
  * Section 4.3 (effectiveness of operator splitting) observes that the best

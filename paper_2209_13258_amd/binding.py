@@ -37,7 +37,8 @@ KERNEL_NAMES = ("gather", "gemm_fwd", "gemm_dw", "gemm_dx")
 EXPORTS = (
     "osdp_slice_range", "osdp_row_slice_range", "osdp_split_linear_gather_slice",
     "osdp_split_linear_gather_row_slice", "osdp_split_linear_workspace_bytes", "osdp_split_linear_fwd",
-    "osdp_split_linear_bwd", "osdp_granularity_candidates", "osdp_granularity_measure",
+    "osdp_split_linear_bwd", "osdp_split_linear_fwd_mixed", "osdp_split_linear_bwd_mixed",
+    "osdp_granularity_candidates", "osdp_granularity_measure",
     "osdp_granularity_select", "osdp_profile_begin", "osdp_profile_end",
     "osdp_strerror", "osdp_last_error", "osdp_version",
 )
@@ -90,6 +91,9 @@ def _load() -> ctypes.CDLL:
     lib.osdp_split_linear_fwd.argtypes = [shp, pln, i32, vp, i64, vp, vp, i64, vp, ctypes.c_size_t, vp, vp]
     lib.osdp_split_linear_bwd.argtypes = [shp, pln, i32, vp, i64, vp, i64, vp, vp, i64, vp, vp,
                                           ctypes.c_size_t, vp, vp]
+    lib.osdp_split_linear_fwd_mixed.argtypes = [shp, pln, i32, vp, i64, vp, vp, i64, vp, i64, vp, ctypes.c_size_t, vp, vp]
+    lib.osdp_split_linear_bwd_mixed.argtypes = [shp, pln, i32, vp, i64, vp, i64, vp, vp, i64, vp, i64, vp, vp, vp,
+                                                ctypes.c_size_t, vp, vp]
     cnd = ctypes.POINTER(osdp_granularity_candidate)
     lib.osdp_granularity_candidates.argtypes = [shp, ctypes.POINTER(i32), i32, cnd, i32, ctypes.POINTER(i32)]
     lib.osdp_granularity_measure.argtypes = [shp, vp, i64, vp, i64, vp, vp, i64, vp, i64, vp, vp, ctypes.c_size_t,
@@ -100,7 +104,8 @@ def _load() -> ctypes.CDLL:
     lib.osdp_profile_end.argtypes = [ctypes.POINTER(osdp_kernel_stats)]
     for name in ("osdp_slice_range", "osdp_row_slice_range", "osdp_split_linear_gather_slice",
                  "osdp_split_linear_gather_row_slice", "osdp_split_linear_workspace_bytes",
-                 "osdp_split_linear_fwd", "osdp_split_linear_bwd", "osdp_granularity_candidates",
+                 "osdp_split_linear_fwd", "osdp_split_linear_bwd", "osdp_split_linear_fwd_mixed",
+                 "osdp_split_linear_bwd_mixed", "osdp_granularity_candidates",
                  "osdp_granularity_measure", "osdp_granularity_select", "osdp_profile_begin", "osdp_profile_end"):
         getattr(lib, name).restype = ctypes.c_int
     lib.osdp_strerror.argtypes = [ctypes.c_int]
@@ -230,6 +235,40 @@ def osdp_split_linear_bwd(X, dY, w_shards, dX, dw_shards, k, workspace, *, plan:
                                      int(dX.data_ptr()), dX.stride(0), _ptrs(dw_shards),
                                      int(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                                      _stream(stream_compute), _stream(stream_copy)))
+
+
+def _opt_ptrs(tensors):
+    """Array of device pointers in which None stands for a slice that has no replica (ZDP mode)."""
+    if tensors is None:
+        return None
+    return (ctypes.c_void_p * len(tensors))(*[None if t is None else int(t.data_ptr()) for t in tensors])
+
+
+def osdp_split_linear_fwd_mixed(X, w_shards, w_dp, ld_dp, Y, k, workspace, *, plan: Optional[Plan] = None,
+                                op_index: int = 0, stream_compute=None, stream_copy=None):
+    """Forward with every slice in its own mode: ``w_dp[j]`` is the replica of DP slice j (None for ZDP slices)."""
+    T, I = X.shape
+    O = Y.shape[1]
+    shape = _shape(T, I, O, len(w_shards), k)
+    pref, _keep = _plan_ref(plan)
+    _check(lib.osdp_split_linear_fwd_mixed(ctypes.byref(shape), pref, op_index, int(X.data_ptr()), X.stride(0),
+                                           _ptrs(w_shards), _opt_ptrs(w_dp), int(ld_dp), int(Y.data_ptr()), Y.stride(0),
+                                           int(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                                           _stream(stream_compute), _stream(stream_copy)))
+
+
+def osdp_split_linear_bwd_mixed(X, dY, w_shards, w_dp, ld_dp, dX, dw_shards, dw_dp, k, workspace, *,
+                                plan: Optional[Plan] = None, op_index: int = 0, stream_compute=None, stream_copy=None):
+    """Backward with every slice in its own mode: DP slices' gradients go to ``dw_dp[j]``, ZDP ones to the shards."""
+    T, I = X.shape
+    O = dY.shape[1]
+    shape = _shape(T, I, O, len(w_shards), k)
+    pref, _keep = _plan_ref(plan)
+    _check(lib.osdp_split_linear_bwd_mixed(ctypes.byref(shape), pref, op_index, int(X.data_ptr()), X.stride(0),
+                                           int(dY.data_ptr()), dY.stride(0), _ptrs(w_shards), _opt_ptrs(w_dp), int(ld_dp),
+                                           int(dX.data_ptr()), dX.stride(0), _ptrs(dw_shards), _opt_ptrs(dw_dp),
+                                           int(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
+                                           _stream(stream_compute), _stream(stream_copy)))
 
 
 def osdp_granularity_candidates(T, I, O, N, k_list: Optional[Sequence[int]] = None):

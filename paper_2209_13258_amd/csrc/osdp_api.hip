@@ -62,6 +62,11 @@ struct Resolved {
   int32_t mode;              // resolved osdp_staging_mode (never AUTO)
   int32_t slots;             // staging slots in the workspace
   std::vector<Slice> sub;    // the ranges processed one after another
+  // slices in DP mode (zdp_mask bit clear) are read from, and their gradient written to, the caller's replica
+  bool any_dp;
+  std::vector<uint8_t> dp;      // per sub-slice: 1 = its slice is in DP mode (no gather, no staging)
+  std::vector<int32_t> owner;   // per sub-slice: index j of its slice
+  std::vector<int64_t> start;   // per sub-slice: where its slice starts along the split dimension
   ShardLayout layout;
   size_t slot_bytes;         // one staging slot, rounded up to kSlotAlign
   size_t peak_staging;       // gathered-weight bytes live at the peak (unrounded)
@@ -98,7 +103,7 @@ osdp_status check_shape(const osdp_shape *s) {
 // row slices it is the other way round (Y adds up over the slices, dX is written range by range).  Both cases
 // are planned as "concatenating" and "accumulating" launches over the sub-slices.
 osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, bool overlap_possible,
-                    bool is_bwd, Resolved *r) {
+                    bool is_bwd, Resolved *r, bool allow_dp = false) {
   osdp_status st = check_shape(shape);
   if (st != OSDP_OK) return st;
   int64_t k = shape->k;
@@ -126,10 +131,15 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
   const int64_t T = shape->T, I = shape->I, O = shape->O;
   const int64_t len = rows ? I : O;  // length of the split dimension
   if (k > len) return fail(OSDP_ERR_INVALID_ARG, "k = %lld exceeds %s = %lld", (long long)k, rows ? "I" : "O", (long long)len);
+  uint64_t zdp = ~0ull;  // bit j set: slice j is gathered
   if (mask) {
     const uint64_t want = k >= 64 ? ~0ull : ((1ull << k) - 1ull);
-    if (k > 64 || (*mask & want) != want)
-      return fail(OSDP_ERR_UNSUPPORTED, "slices in DP mode (zdp_mask with cleared bits) are not supported");
+    if ((*mask & want) != want) {
+      if (k > 64) return fail(OSDP_ERR_UNSUPPORTED, "a zdp_mask with cleared bits covers at most 64 slices (k = %lld)", (long long)k);
+      if (!allow_dp)
+        return fail(OSDP_ERR_UNSUPPORTED, "slices in DP mode (zdp_mask with cleared bits) need the replicas: use the _mixed entry points");
+      zdp = *mask & want;
+    }
   }
   const int32_t N = shape->N;
   if (T >= (1ll << 31) || I >= (1ll << 31) || O >= (1ll << 31))
@@ -148,31 +158,37 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
   r->layout.O = O; r->layout.L = L; r->layout.N = N;
   r->layout.rows_per_shard = (I % N == 0) ? static_cast<int32_t>(I / N) : 0;
   r->sub.clear();
-  int64_t wmax = 0;
+  r->dp.clear(); r->owner.clear(); r->start.clear();
+  r->any_dp = false;
+  int64_t wmax = 0;  // widest gathered sub-slice
   const char *what = rows ? "rows" : "columns";
   for (int64_t j = 0; j < k; ++j) {
     int64_t c0, c1;
     slice_bounds(len, k, j, &c0, &c1);
     if (c0 % 8 || c1 % 8)
       return fail(OSDP_ERR_UNSUPPORTED, "slice %lld = [%lld, %lld) is not aligned to 8 %s", (long long)j, (long long)c0, (long long)c1, what);
-    if (mode == OSDP_STAGING_HALF) {
-      if ((c1 - c0) % 16)
-        return fail(OSDP_ERR_UNSUPPORTED, "half-slice staging needs slice widths that are multiples of 16 (slice %lld has %lld)", (long long)j, (long long)(c1 - c0));
-      const int64_t mid = c0 + (c1 - c0) / 2;
-      r->sub.push_back({c0, mid});
-      r->sub.push_back({mid, c1});
-      wmax = std::max(wmax, (c1 - c0) / 2);
-    } else {
-      r->sub.push_back({c0, c1});
-      wmax = std::max(wmax, c1 - c0);
+    const bool is_dp = j < 64 && !((zdp >> j) & 1ull);
+    r->any_dp = r->any_dp || is_dp;
+    const int parts = mode == OSDP_STAGING_HALF ? 2 : 1;
+    if (parts == 2 && (c1 - c0) % 16)
+      return fail(OSDP_ERR_UNSUPPORTED, "half-slice staging needs slice widths that are multiples of 16 (slice %lld has %lld)", (long long)j, (long long)(c1 - c0));
+    for (int h = 0; h < parts; ++h) {
+      const int64_t a = c0 + h * (c1 - c0) / 2, b = parts == 2 && h == 0 ? c0 + (c1 - c0) / 2 : c1;
+      r->sub.push_back({a, b});
+      r->dp.push_back(is_dp ? 1 : 0);
+      r->owner.push_back(static_cast<int32_t>(j));
+      r->start.push_back(c0);
+      if (!is_dp) wmax = std::max(wmax, b - a);
     }
   }
   r->slots = (mode == OSDP_STAGING_SINGLE) ? 1 : 2;
+  int64_t n_gathered = 0;
+  for (uint8_t d : r->dp) n_gathered += d ? 0 : 1;
   if (static_cast<uint64_t>(D) * static_cast<uint64_t>(wmax) / 8 >= (1ull << 32))
     return fail(OSDP_ERR_UNSUPPORTED, "slice of %lld x %lld elements is too large for the gather kernel", (long long)D, (long long)wmax);
   const size_t slice_bytes = static_cast<size_t>(D) * static_cast<size_t>(wmax) * 2;
   r->slot_bytes = round_up(slice_bytes, kSlotAlign);
-  r->peak_staging = slice_bytes * r->slots;
+  r->peak_staging = slice_bytes * static_cast<size_t>(std::min<int64_t>(r->slots, n_gathered));
   const int64_t n = static_cast<int64_t>(r->sub.size());
   auto width = [&](int64_t j) { return r->sub[j].c1 - r->sub[j].c0; };
   auto span = [&](int64_t a, int64_t b) { return r->sub[b - 1].c1 - r->sub[a].c0; };
@@ -250,7 +266,22 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
     }
   }
   r->dw.clear();
-  for (int64_t a = 0; a < n; a += per) r->dw.push_back({a, std::min(n, a + per)});
+  if (!r->any_dp) {
+    for (int64_t a = 0; a < n; a += per) r->dw.push_back({a, std::min(n, a + per)});
+  } else {
+    // a launch stays within one destination: the sharded gradient (runs of gathered sub-slices, at most `per`)
+    // or one DP slice's own gradient array (the sub-slices of that slice)
+    for (int64_t a = 0; a < n;) {
+      int64_t b = a + 1;
+      if (r->dp[a]) {
+        while (b < n && r->dp[b] && r->owner[b] == r->owner[a]) ++b;
+      } else {
+        while (b < n && !r->dp[b] && b - a < per) ++b;
+      }
+      r->dw.push_back({a, b});
+      a = b;
+    }
+  }
   const size_t accumulating = is_bwd ? (bwd_concat ? 0 : r->pass.size()) : (fwd_concat ? 0 : r->fwd.size());
   r->acc_bytes = accumulating > 1 ? static_cast<size_t>(T) * static_cast<size_t>(D) * 4 : 0;
   return OSDP_OK;
@@ -396,13 +427,19 @@ hipError_t do_gemm(int kind, const GemmProblem &g, hipStream_t stream) {
 
 // The GEMM that consumes the staged sub-slices [j0, j1): one in B0, or two in B0 and B1.
 //   forward : act = X,  out = Y;   backward : act = dY, out = dX.
-// A staged column slice is [I x w] row-major, a staged row slice [w x O] row-major; the forward product reads
+// A column slice is [I x w] row-major, a row slice [w x O] row-major (staged: dense); the forward product reads
 // it as B[k][n] = Ws[k][n], the backward one as B[k][n] = Ws[n][k].
 // Concatenating launches (forward with column slices, dX with row slices) write columns [c0, c0 + span) of out.
 // Accumulating launches (dX with column slices, forward with row slices) add act[:, c0 : c0 + span] . B to the
 // running fp32 sum: launch `idx` of `count` reads the sum from `acc` unless it is the first and writes it back
 // unless it is the last, which rounds into out.
-GemmProblem weight_gemm(const Resolved &r, bool is_fwd, int j0, int j1, const void *B0, const void *B1, const void *act,
+// A slice's weights as the GEMM reads them: a staging slot, or (DP mode) the slice's place in the caller's replica.
+struct WeightView {
+  const void *p;
+  int64_t ld;
+};
+
+GemmProblem weight_gemm(const Resolved &r, bool is_fwd, int j0, int j1, WeightView B0, WeightView B1, const void *act,
                         int64_t ld_act, void *out, int64_t ld_out, float *acc, size_t idx, size_t count) {
   const Slice &s0 = r.sub[j0];
   const int64_t w0 = s0.c1 - s0.c0, span = r.sub[j1 - 1].c1 - s0.c0;
@@ -412,8 +449,8 @@ GemmProblem weight_gemm(const Resolved &r, bool is_fwd, int j0, int j1, const vo
   g.M = static_cast<int32_t>(r.T);
   g.a_kcontig = true;
   g.lda = ld_act;
-  g.B = B0; g.ldb = r.rows ? r.O : w0; g.b_kcontig = !is_fwd;
-  if (two) { g.B2 = B1; g.ldb2 = r.rows ? r.O : span - w0; }
+  g.B = B0.p; g.ldb = B0.ld; g.b_kcontig = !is_fwd;
+  if (two) { g.B2 = B1.p; g.ldb2 = B1.ld; }
   if (concat) {
     g.N = static_cast<int32_t>(span); g.K = static_cast<int32_t>(r.D);
     g.A = act;
@@ -436,8 +473,28 @@ GemmProblem weight_gemm(const Resolved &r, bool is_fwd, int j0, int j1, const vo
 
 // dW over the sub-slices [j0, j1), written into the shard-major gradient: column slices give
 // dW[:, c0:c1] = X^T . dY[:, c0:c1], row slices dW[c0:c1, :] = X[:, c0:c1]^T . dY.
+// Caller-owned replicas of the slices in DP mode: w[j] / dw[j] point at slice j's weights / gradient, row-major
+// with leading dimension ld ([I x w_j] for column slices, [h_j x O] for row slices).
+struct Replicas {
+  const void *const *w;
+  void *const *dw;
+  int64_t ld;
+};
+
+// element offset of sub-slice j inside its slice's replica
+int64_t replica_offset(const Resolved &r, const Replicas &rep, int j) {
+  const int64_t d = r.sub[j].c0 - r.start[j];
+  return r.rows ? d * rep.ld : d;
+}
+
+// where the GEMM finds sub-slice j: its staging slot, or its place in the replica
+WeightView weights_of(const Resolved &r, const Replicas &rep, int j, const void *slot) {
+  if (r.dp[j]) return {static_cast<const uint16_t *>(rep.w[r.owner[j]]) + replica_offset(r, rep, j), rep.ld};
+  return {slot, r.rows ? r.O : r.sub[j].c1 - r.sub[j].c0};
+}
+
 GemmProblem dw_gemm(const Resolved &r, int j0, int j1, const void *X, int64_t ldx, const void *dY, int64_t lddy,
-                    const ShardTable &gtab) {
+                    const ShardTable &gtab, const Replicas &rep) {
   const int64_t c0 = r.sub[j0].c0, c1 = r.sub[j1 - 1].c1;
   GemmProblem g{};
   g.K = static_cast<int32_t>(r.T);
@@ -452,9 +509,42 @@ GemmProblem dw_gemm(const Resolved &r, int j0, int j1, const void *X, int64_t ld
     g.A = X; g.B = static_cast<const uint16_t *>(dY) + c0;
     g.c0 = c0;
   }
-  g.epilogue = Epilogue::kBf16ShardMajor;
-  g.layout = r.layout; g.shards = gtab;
+  if (r.dp[j0]) {  // the gradient of a DP slice is a plain array of the slice's shape
+    g.C = static_cast<uint16_t *>(rep.dw[r.owner[j0]]) + replica_offset(r, rep, j0);
+    g.ldc = rep.ld;
+    g.epilogue = Epilogue::kBf16RowMajor;
+    g.c0 = g.r0 = 0;
+  } else {
+    g.epilogue = Epilogue::kBf16ShardMajor;
+    g.layout = r.layout; g.shards = gtab;
+  }
   return g;
+}
+
+osdp_status check_replicas(const Resolved &r, const Replicas &rep, bool need_dw) {
+  if (!r.any_dp) return OSDP_OK;
+  if (!rep.w) return fail(OSDP_ERR_INVALID_ARG, "w_dp is NULL but the plan has slices in DP mode");
+  if (need_dw && !rep.dw) return fail(OSDP_ERR_INVALID_ARG, "dw_dp is NULL but the plan has slices in DP mode");
+  if (rep.ld % 8) return fail(OSDP_ERR_UNSUPPORTED, "ld_dp (%lld) is not a multiple of 8", (long long)rep.ld);
+  for (size_t j = 0; j < r.sub.size(); ++j) {
+    if (!r.dp[j] || (j > 0 && r.owner[j] == r.owner[j - 1])) continue;
+    int64_t cols = r.O;
+    if (!r.rows) {
+      cols = 0;
+      for (size_t q = j; q < r.sub.size() && r.owner[q] == r.owner[j]; ++q) cols += r.sub[q].c1 - r.sub[q].c0;
+    }
+    if (rep.ld < cols)
+      return fail(OSDP_ERR_INVALID_ARG, "ld_dp (%lld) is below the %lld columns of slice %d", (long long)rep.ld, (long long)cols, r.owner[j]);
+    const void *w = rep.w[r.owner[j]];
+    if (!w) return fail(OSDP_ERR_INVALID_ARG, "w_dp[%d] is NULL", r.owner[j]);
+    if (!aligned16(w)) return fail(OSDP_ERR_UNSUPPORTED, "w_dp[%d] is not 16-byte aligned", r.owner[j]);
+    if (need_dw) {
+      const void *g = rep.dw[r.owner[j]];
+      if (!g) return fail(OSDP_ERR_INVALID_ARG, "dw_dp[%d] is NULL", r.owner[j]);
+      if (!aligned16(g)) return fail(OSDP_ERR_UNSUPPORTED, "dw_dp[%d] is not 16-byte aligned", r.owner[j]);
+    }
+  }
+  return OSDP_OK;
 }
 
 }  // namespace
@@ -502,9 +592,9 @@ osdp_status osdp_split_linear_workspace_bytes(const osdp_shape *shape, const osd
   // With OSDP_STAGING_AUTO the call decides between one and two slots by the streams it is given:
   // the answer covers both (peak staging is that of the two-slot case).
   Resolved two, one;
-  osdp_status st = resolve(shape, plan, op_index, /*overlap_possible=*/true, is_bwd != 0, &two);
+  osdp_status st = resolve(shape, plan, op_index, /*overlap_possible=*/true, is_bwd != 0, &two, /*allow_dp=*/true);
   if (st != OSDP_OK) return st;
-  st = resolve(shape, plan, op_index, /*overlap_possible=*/false, is_bwd != 0, &one);
+  st = resolve(shape, plan, op_index, /*overlap_possible=*/false, is_bwd != 0, &one, /*allow_dp=*/true);
   if (st != OSDP_OK) return st;
   if (total) *total = std::max(workspace_total(two), workspace_total(one));
   if (peak_weight_staging) *peak_weight_staging = two.peak_staging;
@@ -537,18 +627,19 @@ osdp_status osdp_split_linear_gather_row_slice(const osdp_shape *shape, int32_t 
   return gather_one(shape, OSDP_SPLIT_IN_FEATURES, slice_j, w_shards, staging, stream);
 }
 
-osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, const void *X,
-                                  int64_t ldx, const void *const *w_shards, void *Y, int64_t ldy, void *workspace,
-                                  size_t workspace_bytes, void *stream_compute, void *stream_copy) {
+static osdp_status forward(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, bool allow_dp, const void *X,
+                           int64_t ldx, const void *const *w_shards, const Replicas &rep, void *Y, int64_t ldy,
+                           void *workspace, size_t workspace_bytes, void *stream_compute, void *stream_copy) {
   hipStream_t sc = static_cast<hipStream_t>(stream_compute), sp = static_cast<hipStream_t>(stream_copy);
   const bool two_streams = sp != nullptr && sp != sc;
   Resolved r;
-  osdp_status st = resolve(shape, plan, op_index, two_streams, false, &r);
+  osdp_status st = resolve(shape, plan, op_index, two_streams, false, &r, allow_dp);
   if (st != OSDP_OK) return st;
   if ((st = check_matrix(X, ldx, r.I, "X")) != OSDP_OK) return st;
   if ((st = check_matrix(Y, ldy, r.O, "Y")) != OSDP_OK) return st;
   ShardTable tab;
   if ((st = fill_table(w_shards, r.N, "w_shards", &tab)) != OSDP_OK) return st;
+  if ((st = check_replicas(r, rep, false)) != OSDP_OK) return st;
   if ((st = check_workspace(r, workspace, workspace_bytes)) != OSDP_OK) return st;
 
   char *ws = static_cast<char *>(workspace);
@@ -562,35 +653,55 @@ osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_plan *plan
     const int j0 = static_cast<int>(r.fwd[li].c0), j1 = static_cast<int>(r.fwd[li].c1);
     void *slot_of[2] = {nullptr, nullptr};
     int slot_id[2] = {0, 0};
+    bool gathered = false;
     for (int j = j0; j < j1; ++j) {
       const int s = (j1 - j0 == 2) ? j - j0 : j % r.slots;
       slot_id[j - j0] = s;
       slot_of[j - j0] = ws + static_cast<size_t>(s) * r.slot_bytes;
+      if (r.dp[j]) continue;  // a DP slice is read where it lies
       if (overlap && slot_free[s]) OSDP_HIP(hipStreamWaitEvent(sp, slot_free[s], 0));  // slot released by its last reader
       OSDP_HIP(do_gather(r, tab, r.sub[j], slot_of[j - j0], sg));
+      gathered = true;
     }
-    if (overlap) OSDP_HIP(edge(sp, sc));
-    const GemmProblem g = weight_gemm(r, /*is_fwd=*/true, j0, j1, slot_of[0], slot_of[1], X, ldx, Y, ldy, acc, li, r.fwd.size());
+    if (overlap && gathered) OSDP_HIP(edge(sp, sc));
+    const GemmProblem g = weight_gemm(r, /*is_fwd=*/true, j0, j1, weights_of(r, rep, j0, slot_of[0]),
+                                      weights_of(r, rep, j1 - 1, slot_of[1]), X, ldx, Y, ldy, acc, li, r.fwd.size());
     OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_FWD, g, sc));
-    if (overlap && j1 < n) {
+    if (overlap && gathered && j1 < n) {
       hipEvent_t ev;
       OSDP_HIP(g_events.get(&ev));
       OSDP_HIP(hipEventRecord(ev, sc));
-      for (int j = j0; j < j1; ++j) slot_free[slot_id[j - j0]] = ev;
+      for (int j = j0; j < j1; ++j)
+        if (!r.dp[j]) slot_free[slot_id[j - j0]] = ev;
     }
   }
   if (overlap) OSDP_HIP(edge(sc, sp));  // later copy-stream work may reuse the workspace
   return OSDP_OK;
 }
 
-osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, const void *X,
-                                  int64_t ldx, const void *dY, int64_t lddy, const void *const *w_shards, void *dX,
-                                  int64_t lddx, void *const *dw_shards, void *workspace, size_t workspace_bytes,
-                                  void *stream_compute, void *stream_copy) {
+osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, const void *X,
+                                  int64_t ldx, const void *const *w_shards, void *Y, int64_t ldy, void *workspace,
+                                  size_t workspace_bytes, void *stream_compute, void *stream_copy) {
+  return forward(shape, plan, op_index, false, X, ldx, w_shards, Replicas{nullptr, nullptr, 0}, Y, ldy, workspace,
+                 workspace_bytes, stream_compute, stream_copy);
+}
+
+osdp_status osdp_split_linear_fwd_mixed(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, const void *X,
+                                        int64_t ldx, const void *const *w_shards, const void *const *w_dp, int64_t ld_dp,
+                                        void *Y, int64_t ldy, void *workspace, size_t workspace_bytes,
+                                        void *stream_compute, void *stream_copy) {
+  return forward(shape, plan, op_index, true, X, ldx, w_shards, Replicas{w_dp, nullptr, ld_dp}, Y, ldy, workspace,
+                 workspace_bytes, stream_compute, stream_copy);
+}
+
+static osdp_status backward(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, bool allow_dp, const void *X,
+                            int64_t ldx, const void *dY, int64_t lddy, const void *const *w_shards, const Replicas &rep,
+                            void *dX, int64_t lddx, void *const *dw_shards, void *workspace, size_t workspace_bytes,
+                            void *stream_compute, void *stream_copy) {
   hipStream_t sc = static_cast<hipStream_t>(stream_compute), sp = static_cast<hipStream_t>(stream_copy);
   const bool two_streams = sp != nullptr && sp != sc;
   Resolved r;
-  osdp_status st = resolve(shape, plan, op_index, two_streams, true, &r);
+  osdp_status st = resolve(shape, plan, op_index, two_streams, true, &r, allow_dp);
   if (st != OSDP_OK) return st;
   if ((st = check_matrix(X, ldx, r.I, "X")) != OSDP_OK) return st;
   if ((st = check_matrix(dY, lddy, r.O, "dY")) != OSDP_OK) return st;
@@ -598,6 +709,7 @@ osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan
   ShardTable tab, gtab;
   if ((st = fill_table(w_shards, r.N, "w_shards", &tab)) != OSDP_OK) return st;
   if ((st = fill_table(reinterpret_cast<const void *const *>(dw_shards), r.N, "dw_shards", &gtab)) != OSDP_OK) return st;
+  if ((st = check_replicas(r, rep, true)) != OSDP_OK) return st;
   if ((st = check_workspace(r, workspace, workspace_bytes)) != OSDP_OK) return st;
 
   char *ws = static_cast<char *>(workspace);
@@ -613,7 +725,7 @@ osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan
     // gather every slice of the group into its slot once the previous group has released the slots
     if (overlap && released) OSDP_HIP(hipStreamWaitEvent(sp, released, 0));
     for (int j = g0; j < g1; ++j)
-      OSDP_HIP(do_gather(r, tab, r.sub[j], ws + static_cast<size_t>(j - g0) * r.slot_bytes, sg));
+      if (!r.dp[j]) OSDP_HIP(do_gather(r, tab, r.sub[j], ws + static_cast<size_t>(j - g0) * r.slot_bytes, sg));
     hipEvent_t gathered = nullptr;
     if (overlap) {
       OSDP_HIP(g_events.get(&gathered));
@@ -621,16 +733,17 @@ osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan
     }
     // dW launches whose range starts in this group: they need no weights and run while the gathers are in flight
     for (; next_dw < r.dw.size() && r.dw[next_dw].c0 < g1; ++next_dw) {
-      const GemmProblem gw = dw_gemm(r, static_cast<int>(r.dw[next_dw].c0), static_cast<int>(r.dw[next_dw].c1), X, ldx, dY, lddy, gtab);
+      const GemmProblem gw = dw_gemm(r, static_cast<int>(r.dw[next_dw].c0), static_cast<int>(r.dw[next_dw].c1), X, ldx, dY, lddy, gtab, rep);
       OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DW, gw, sc));
     }
     if (overlap) OSDP_HIP(hipStreamWaitEvent(sc, gathered, 0));
     // the dX launches of the group (column slices: the fp32 partial sum is carried in the workspace between them)
     for (; next_pass < r.pass.size() && r.pass[next_pass].c1 <= g1; ++next_pass) {
       const int j0 = static_cast<int>(r.pass[next_pass].c0), j1 = static_cast<int>(r.pass[next_pass].c1);
-      const GemmProblem gx = weight_gemm(r, /*is_fwd=*/false, j0, j1, ws + static_cast<size_t>(j0 - g0) * r.slot_bytes,
-                                         ws + static_cast<size_t>(j0 + 1 - g0) * r.slot_bytes, dY, lddy, dX, lddx, acc,
-                                         next_pass, r.pass.size());
+      const GemmProblem gx = weight_gemm(r, /*is_fwd=*/false, j0, j1,
+                                         weights_of(r, rep, j0, ws + static_cast<size_t>(j0 - g0) * r.slot_bytes),
+                                         weights_of(r, rep, j1 - 1, ws + static_cast<size_t>(j1 - 1 - g0) * r.slot_bytes),
+                                         dY, lddy, dX, lddx, acc, next_pass, r.pass.size());
       OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DX, gx, sc));
     }
     if (overlap && g1 < n) {
@@ -640,6 +753,23 @@ osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan
   }
   if (overlap) OSDP_HIP(edge(sc, sp));
   return OSDP_OK;
+}
+
+osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, const void *X,
+                                  int64_t ldx, const void *dY, int64_t lddy, const void *const *w_shards, void *dX,
+                                  int64_t lddx, void *const *dw_shards, void *workspace, size_t workspace_bytes,
+                                  void *stream_compute, void *stream_copy) {
+  return backward(shape, plan, op_index, false, X, ldx, dY, lddy, w_shards, Replicas{nullptr, nullptr, 0}, dX, lddx,
+                  dw_shards, workspace, workspace_bytes, stream_compute, stream_copy);
+}
+
+osdp_status osdp_split_linear_bwd_mixed(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, const void *X,
+                                        int64_t ldx, const void *dY, int64_t lddy, const void *const *w_shards,
+                                        const void *const *w_dp, int64_t ld_dp, void *dX, int64_t lddx,
+                                        void *const *dw_shards, void *const *dw_dp, void *workspace,
+                                        size_t workspace_bytes, void *stream_compute, void *stream_copy) {
+  return backward(shape, plan, op_index, true, X, ldx, dY, lddy, w_shards, Replicas{w_dp, dw_dp, ld_dp}, dX, lddx,
+                  dw_shards, workspace, workspace_bytes, stream_compute, stream_copy);
 }
 
 osdp_status osdp_granularity_candidates(const osdp_shape *shape, const int32_t *k_list, int32_t n_k,

@@ -315,8 +315,10 @@ hipError_t launch_gemm(const GemmProblem &q, hipStream_t stream) {
     if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_best<true, false, kRow, true>(p, stream) : launch_best<true, false, kRow, false>(p, stream);
     if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_best<true, false, kF32, true>(p, stream) : launch_best<true, false, kF32, false>(p, stream);
   }
-  if (!q.a_kcontig && !q.b_kcontig && q.epilogue == Epilogue::kBf16ShardMajor && !acc)
-    return launch_best<false, false, kShard, false>(p, stream);                    // dW
+  if (!q.a_kcontig && !q.b_kcontig && !acc) {                                      // dW: into the shards, or (DP slice) a plain array
+    if (q.epilogue == Epilogue::kBf16ShardMajor) return launch_best<false, false, kShard, false>(p, stream);
+    if (q.epilogue == Epilogue::kBf16RowMajor) return launch_best<false, false, kRow, false>(p, stream);
+  }
   if (q.a_kcontig && q.b_kcontig) {                                                // dX
     if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_best<true, true, kRow, true>(p, stream) : launch_best<true, true, kRow, false>(p, stream);
     if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_best<true, true, kF32, true>(p, stream) : launch_best<true, true, kF32, false>(p, stream);

@@ -456,3 +456,219 @@ def test_config3_layer_with_row_split_plan(H, oracle):
     plan = osdp.Plan([op.k for op in w.ops], split_dim_per_op=[osdp.OSDP_SPLIT_IN_FEATURES] * len(w.ops))
     for n, op in enumerate(w.ops):
         _sampled_check_plan(H, oracle, 3, n, op, w, plan)
+
+
+# ---------------------------------------------- every slice in its own mode (DP or ZDP)
+POISON = 0x7FC0  # bf16 NaN
+
+
+def _mixed_host_case(oracle, seed, T, I, O, N, k, mask, rows, full_layout, cfg=None):
+    """Weights that differ between the two sources: the shards hold NaN wherever a DP slice lies, the replicas
+    hold the values that count there.  Returns host arrays and `used`, the matrix the operator really applies."""
+    d = wl.small_case(seed, T, I, O, N) if cfg is None else wl.operator_inputs(cfg[0], 0, cfg[1], T, I, O, N)
+    W = np.concatenate(d["W_shards"])[: I * O].reshape(I, O).copy()
+    other = np.random.default_rng(seed + 1000)
+    keff = max(k, 1)
+    rng = [(oracle.row_slice_range(I, k, j) if rows else oracle.slice_range(O, k, j)) for j in range(keff)]
+    used = W.copy()
+    ld = O if (rows or full_layout) else max(b - a for a, b in rng) + 8   # compact replicas padded by 8 columns
+    w_dp = [None] * keff
+    full = None
+    for j, (a, b) in enumerate(rng):
+        if (mask >> j) & 1:
+            continue
+        sl = (slice(a, b), slice(None)) if rows else (slice(None), slice(a, b))
+        vals = wl.f32_to_bf16_bits((other.standard_normal(W[sl].shape) * 0.02).astype(np.float32))
+        used[sl] = vals
+        W[sl] = POISON
+        if rows:
+            w_dp[j] = vals.copy()
+        elif full_layout:
+            if full is None:
+                full = np.full((I, O), POISON, dtype=np.uint16)
+            full[sl] = vals
+            w_dp[j] = (full, a)                  # a view into one full-layout copy, made on the device side
+        else:
+            buf = np.full((I, ld), POISON, dtype=np.uint16)
+            buf[:, : b - a] = vals
+            w_dp[j] = buf
+    L = oracle.shard_len(I, O, N)
+    flat = np.full(N * L, POISON, dtype=np.uint16)
+    flat[: I * O] = W.reshape(-1)
+    shards = [flat[s * L:(s + 1) * L].copy() for s in range(N)]
+    return d, shards, w_dp, ld, rng, used, full
+
+
+class _MixedDevice:
+    def __init__(self, H, d, shards, w_dp, ld, rng, I, O, rows, full):
+        self.op = H.Operator(d["X"], d["dY"], shards, O)
+        self.ld, self.rng, self.rows = ld, rng, rows
+        full_dev = H.to_dev(full.reshape(-1)) if full is not None else None
+        full_grad = torch.full((I * O,), float("nan"), dtype=torch.bfloat16, device="cuda") if full is not None else None
+        self.w_dp, self.dw_dp = [], []
+        for j, w in enumerate(w_dp):
+            if w is None:
+                self.w_dp.append(None)
+                self.dw_dp.append(None)
+            elif isinstance(w, tuple):
+                self.w_dp.append(full_dev[w[1]:])
+                self.dw_dp.append(full_grad[w[1]:])
+            else:
+                self.w_dp.append(H.to_dev(w.reshape(-1)))
+                self.dw_dp.append(torch.full((w.size,), float("nan"), dtype=torch.bfloat16, device="cuda"))
+        self.full_grad = full_grad
+
+    def run(self, k, plan, streams=(None, None)):
+        import paper_2209_13258_amd as osdp
+        op = self.op
+        ws, _ = op.workspace(k, True, plan)
+        ws2, _ = op.workspace(k, False, plan)
+        osdp.osdp_split_linear_fwd_mixed(op.X, op.W, self.w_dp, self.ld, op.Y, k, op.ws, plan=plan,
+                                         stream_compute=streams[0], stream_copy=streams[1])
+        osdp.osdp_split_linear_bwd_mixed(op.X, op.dY, op.W, self.w_dp, self.ld, op.dX, op.dW, self.dw_dp, k, op.ws,
+                                         plan=plan, stream_compute=streams[0], stream_copy=streams[1])
+
+    def gradient(self, H, I, O, mask):
+        """(dense dW assembled from both destinations, what the shards hold inside DP slices, what the replicas'
+        gradient arrays hold outside their slice)."""
+        got = self.op.results()
+        dW = got["dW"].copy()
+        in_dp, outside = [], []
+        for j, (a, b) in enumerate(self.rng):
+            if (mask >> j) & 1:
+                continue
+            sl = (slice(a, b), slice(None)) if self.rows else (slice(None), slice(a, b))
+            in_dp.append(dW[sl].copy().reshape(-1))
+            h, w = (b - a, O) if self.rows else (I, b - a)
+            buf = H.to_bits(self.dw_dp[j])
+            need = (h - 1) * self.ld + w
+            arr = np.full(h * self.ld, POISON, dtype=np.uint16)
+            arr[:need] = buf[:need]
+            arr = arr.reshape(h, self.ld)
+            dW[sl] = arr[:, :w]
+            if self.full_grad is None:
+                outside.append(arr[:, w:].reshape(-1))
+        return got, dW, in_dp, outside
+
+
+MIXED_SMALL = [
+    # T, I, O, N, k, zdp_mask
+    (128, 256, 1024, 2, 4, 0b0001),    # the paper's example on config 1: one slice ZDP, three DP
+    (300, 264, 528, 4, 3, 0b101),      # ragged everywhere
+    (513, 384, 640, 8, 5, 0b01010),
+    (200, 72, 1040, 5, 2, 0b00),       # every slice DP: nothing gathered at all
+    (256, 512, 512, 4, 4, 0b0110),     # unchecked kernel, fusable pairs of one DP and one ZDP slice
+    (77, 136, 200, 1, 1, 0b0),         # the whole operator in DP mode
+]
+
+
+@pytest.mark.parametrize("rows", [False, True])
+@pytest.mark.parametrize("T,I,O,N,k,mask", MIXED_SMALL)
+def test_per_slice_modes_match_oracle(H, oracle, T, I, O, N, k, mask, rows):
+    import paper_2209_13258_amd as osdp
+    if rows:
+        I, O = O, I   # cut the long dimension either way
+    _announce("mixed", T, I, O, N, k, bin(mask), "rows" if rows else "cols")
+    dim = osdp.OSDP_SPLIT_IN_FEATURES if rows else osdp.OSDP_SPLIT_OUT_FEATURES
+    for full_layout in (False, True):
+        d, shards, w_dp, ld, rng, used, full = _mixed_host_case(oracle, 61, T, I, O, N, k, mask, rows, full_layout)
+        host_dp = [None if w is None else (full.reshape(-1)[w[1]:] if isinstance(w, tuple) else w) for w in w_dp]
+        Y, peak = oracle.split_fwd_mixed(d["X"], shards, O, k, mask, host_dp, ld, rows=rows)
+        dX, dWs, dw_ref, _ = oracle.split_bwd_mixed(d["X"], d["dY"], shards, O, k, mask, host_dp, ld, rows=rows)
+        dW_ref = oracle.dense_from_f64_shards(dWs, I, O)
+        for j, (a, b) in enumerate(rng):
+            if not (mask >> j) & 1:
+                sl = (slice(a, b), slice(None)) if rows else (slice(None), slice(a, b))
+                h, w = (b - a, O) if rows else (I, b - a)
+                dW_ref[sl] = dw_ref[j][:h, :w]
+        for mode, two in ((osdp.OSDP_STAGING_SINGLE, False), (osdp.OSDP_STAGING_DOUBLE, True), (osdp.OSDP_STAGING_HALF, True)):
+            if mode == osdp.OSDP_STAGING_HALF and any((b - a) % 16 for a, b in rng):
+                continue
+            plan = osdp.Plan([k], staging=mode, zdp_mask=[mask], split_dim_per_op=[dim])
+            dev = _MixedDevice(H, d, shards, w_dp, ld, rng, I, O, rows, full)
+            sc, sp = H.streams()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(sc):
+                dev.run(k, plan, streams=(sc, sp if two else None))
+            sc.synchronize()
+            got, dW, in_dp, outside = dev.gradient(H, I, O, mask)
+            tag = f"mode {mode} full_layout {full_layout}"
+            H.assert_close(f"Y {tag}", got["Y"], Y)
+            H.assert_close(f"dX {tag}", got["dX"], dX)
+            H.assert_close(f"dW {tag}", dW, dW_ref)
+            for a in in_dp:
+                assert (a == POISON).all(), "the sharded gradient was written inside a DP slice"
+            for a in outside:
+                assert (a == POISON).all(), "a DP gradient array was written outside its slice"
+            # the gathered-weight peak counts ZDP slices only, and equals what the oracle's meter saw for one slot
+            _, lib_peak = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, True,
+                                                                 osdp.Plan([k], staging=osdp.OSDP_STAGING_SINGLE,
+                                                                           zdp_mask=[mask], split_dim_per_op=[dim]))
+            assert lib_peak == peak
+
+
+@pytest.mark.parametrize("rows", [False, True])
+def test_per_slice_modes_are_bit_identical_to_all_zdp(H, oracle, rows):
+    """With the replicas holding the same values as the shards, every mask gives the bits of the all-ZDP plan."""
+    import paper_2209_13258_amd as osdp
+    T, I, O, N, k = 256, 512, 1024, 4, 4
+    if rows:
+        I, O = O, I
+    dim = osdp.OSDP_SPLIT_IN_FEATURES if rows else osdp.OSDP_SPLIT_OUT_FEATURES
+    d = wl.small_case(62, T, I, O, N)
+    base = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+    plan0 = osdp.Plan([k], split_dim_per_op=[dim])
+    base.fwd(k, plan=plan0)
+    base.bwd(k, plan=plan0)
+    ref = base.results()
+    W = np.concatenate(d["W_shards"])[: I * O].reshape(I, O)
+    rng = [(oracle.row_slice_range(I, k, j) if rows else oracle.slice_range(O, k, j)) for j in range(k)]
+    for mask in (0b0000, 0b0001, 0b1010, 0b0111):
+        _announce("mixed bit-identity", bin(mask), "rows" if rows else "cols")
+        w_dp = [None if (mask >> j) & 1 else (W, a * O if rows else a) for j, (a, b) in enumerate(rng)]
+        for mode in (osdp.OSDP_STAGING_SINGLE, osdp.OSDP_STAGING_DOUBLE, osdp.OSDP_STAGING_HALF):
+            dev = _MixedDevice(H, d, d["W_shards"], w_dp, O, rng, I, O, rows, W)
+            sc, sp = H.streams()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(sc):
+                dev.run(k, osdp.Plan([k], staging=mode, zdp_mask=[mask], split_dim_per_op=[dim]), streams=(sc, sp))
+            sc.synchronize()
+            got, dW, _, _ = dev.gradient(H, I, O, mask)
+            assert np.array_equal(got["Y"], ref["Y"]), f"Y differs (mask {mask:04b}, mode {mode})"
+            assert np.array_equal(got["dX"], ref["dX"]), f"dX differs (mask {mask:04b}, mode {mode})"
+            assert np.array_equal(dW, ref["dW"]), f"dW differs (mask {mask:04b}, mode {mode})"
+
+
+@pytest.mark.parametrize("rows", [False, True])
+def test_config2_one_of_four_slices_zdp(H, oracle, rows):
+    """The paper's example at full size (config 2, k = 4): one slice ZDP, three DP; sampled entries."""
+    import paper_2209_13258_amd as osdp
+    w = wl.workload(2, 4)
+    k, mask = 4, 0b0100
+    dim = osdp.OSDP_SPLIT_IN_FEATURES if rows else osdp.OSDP_SPLIT_OUT_FEATURES
+    for n, o in enumerate(w.ops):
+        _announce("mixed config 2", o.name, "rows" if rows else "cols")
+        d, shards, w_dp, ld, rng, used, full = _mixed_host_case(oracle, 63 + n, w.T, o.I, o.O, w.N, k, mask, rows, True,
+                                                                cfg=(2, n))
+        dev = _MixedDevice(H, d, shards, w_dp, ld, rng, o.I, o.O, rows, full)
+        sc, sp = H.streams()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(sc):
+            dev.run(k, osdp.Plan([k], zdp_mask=[mask], split_dim_per_op=[dim]), streams=(sc, sp))
+        sc.synchronize()
+        got, dW, in_dp, _ = dev.gradient(H, o.I, o.O, mask)
+        for a in in_dp:
+            assert (a == POISON).all()
+        used_shards = oracle.shard(used, w.N)   # the matrix the operator applies, for the oracle's entry sampler
+        g = np.random.default_rng(64 + n)
+        ns = 50_000
+        r, c = g.integers(0, w.T, ns), g.integers(0, o.O, ns)
+        H.assert_close("Y", got["Y"][r, c], oracle.sample_y(d["X"], used_shards, o.O, r, c))
+        r, c = g.integers(0, w.T, ns), g.integers(0, o.I, ns)
+        H.assert_close("dX", got["dX"][r, c], oracle.sample_dx(d["dY"], used_shards, o.I, r, c))
+        r, c = g.integers(0, o.I, ns), g.integers(0, o.O, ns)
+        H.assert_close("dW", dW[r, c], oracle.sample_dw(d["X"], d["dY"], r, c))
+        _, peak = osdp.osdp_split_linear_workspace_bytes(w.T, o.I, o.O, w.N, k, True,
+                                                         osdp.Plan([k], zdp_mask=[mask], split_dim_per_op=[dim]))
+        law = oracle.peak_staging_bytes_rows if rows else oracle.peak_staging_bytes
+        assert peak == law(o.I, o.O, k, 1, 2)   # one gathered slice, however many slots the mode offers

@@ -145,12 +145,59 @@ def test_plan_vector_selects_staging_and_split_dimension_per_operator(oracle):
         osdp.osdp_split_linear_workspace_bytes(T, I, O, N, 0, True, osdp.Plan([4], staging_per_op=[9]))
 
 
-def test_dp_slices_are_rejected_as_unsupported():
-    plan = osdp.Plan([4], zdp_mask=[0b0111])
-    with pytest.raises(osdp.OsdpError) as e:
-        osdp.osdp_split_linear_workspace_bytes(128, 256, 1024, 2, 4, False, plan)
+def test_dp_slices_are_staged_nowhere(oracle):
+    """Section 3.3, last paragraph: a slice in DP mode is replicated, so only the ZDP slices count towards the
+    gathered-weight peak; with every slice in DP mode nothing is staged at all."""
+    T, I, O, N, k = 128, 256, 1024, 2, 4
+    one = oracle.peak_staging_bytes(I, O, k, 1, 2)
+    for mask, slots_used in ((0b1111, 2), (0b0111, 2), (0b0001, 1), (0b1000, 1), (0b0000, 0)):
+        for is_bwd in (False, True):
+            tot, peak = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, is_bwd, osdp.Plan([k], zdp_mask=[mask]))
+            assert peak == slots_used * one
+            assert tot >= peak
+    _, peak = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, False,
+                                                     osdp.Plan([k], staging=osdp.OSDP_STAGING_SINGLE, zdp_mask=[0b0101]))
+    assert peak == one
+    _, peak = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, False, osdp.Plan(
+        [k], zdp_mask=[0b0010], split_dim_per_op=[osdp.OSDP_SPLIT_IN_FEATURES]))
+    assert peak == oracle.peak_staging_bytes_rows(I, O, k, 1, 2)
+    # bits beyond the k slices are ignored
+    assert osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, False, osdp.Plan([k], zdp_mask=[0b1111]))[1] == \
+        osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, False, osdp.Plan([k], zdp_mask=[0xFFFF_FFFF_FFFF_FFFF]))[1]
+
+
+def test_dp_slices_need_the_mixed_entry_points_and_their_replicas():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("uses made-up device addresses: only run where nothing can be launched")
+    T, I, O, N, k = 128, 256, 1024, 2, 4
+    X, dY = _FakeTensor(0x10000, (T, I)), _FakeTensor(0x20000, (T, O))
+    Y, dX = _FakeTensor(0x30000, (T, O)), _FakeTensor(0x40000, (T, I))
+    sh = [_FakeTensor(0x50000, (I * O // N,)), _FakeTensor(0x60000, (I * O // N,))]
+    plan = osdp.Plan([k], staging=osdp.OSDP_STAGING_SINGLE, zdp_mask=[0b0110])
+    need = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, True, plan)[0]
+    ws = _FakeTensor(0x70000, (need,), elem=1)
+    with pytest.raises(osdp.OsdpError) as e:   # the plain entry point has no replicas to read DP slices from
+        osdp.osdp_split_linear_fwd(X, sh, Y, k, ws, plan=plan)
     assert e.value.status == osdp.binding.OSDP_ERR_UNSUPPORTED
-    osdp.osdp_split_linear_workspace_bytes(128, 256, 1024, 2, 4, False, osdp.Plan([4], zdp_mask=[0b1111]))
+    rep = _FakeTensor(0x80000, (I, O // k))
+    good = [rep, None, None, rep]
+    cases = [
+        (dict(w_dp=None), -1),                                             # DP slices but no replicas
+        (dict(w_dp=[None, None, None, rep]), -1),                          # slice 0 is DP and has none
+        (dict(w_dp=[_FakeTensor(0x80008, (I, O // k)), None, None, rep]), -2),   # misaligned replica
+        (dict(ld=O // k - 8), -1),                                         # leading dimension below the slice width
+        (dict(ld=O // k + 4), -2),                                         # not a multiple of 8
+    ]
+    for over, status in cases:
+        a = dict(w_dp=good, ld=O // k)
+        a.update(over)
+        with pytest.raises(osdp.OsdpError) as e:
+            osdp.osdp_split_linear_fwd_mixed(X, sh, a["w_dp"], a["ld"], Y, k, ws, plan=plan)
+        assert e.value.status == status, (over, str(e.value))
+    with pytest.raises(osdp.OsdpError) as e:   # backward also needs somewhere to put the DP gradients
+        osdp.osdp_split_linear_bwd_mixed(X, dY, sh, good, O // k, dX, sh, None, k, ws, plan=plan)
+    assert e.value.status == osdp.binding.OSDP_ERR_INVALID_ARG
 
 
 @pytest.mark.parametrize("args,status", [
