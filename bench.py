@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--staging", choices=["auto", "single", "double", "half"], default="auto")
     ap.add_argument("--split-dim", choices=["out", "in"], default="out",
                     help="cut W along its output features (columns) or its input features (rows, the reduction dimension)")
+    ap.add_argument("--zdp-slices", type=int, default=None,
+                    help="keep only the first Z slices of every operator sharded (ZDP); the others are DP slices "
+                         "read from a resident replica (default: every slice ZDP)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the k sweep and the extra workload")
     ap.add_argument("--no-auto", action="store_true", help="skip the automatic slice-granularity table")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -51,7 +54,7 @@ def parse():
 class Stack:
     """All operators of a workload resident on the GPU, with one shared workspace."""
 
-    def __init__(self, w, staging, torch, osdp, seed=0, rows=False, plan=None):
+    def __init__(self, w, staging, torch, osdp, seed=0, rows=False, plan=None, zdp_slices=None):
         self.w, self.torch, self.osdp = w, torch, osdp
         g = torch.Generator(device="cuda")
         g.manual_seed(220913258 + seed)
@@ -72,6 +75,18 @@ class Stack:
                 self.ops.append(d)
         dims = [osdp.OSDP_SPLIT_IN_FEATURES if rows else osdp.OSDP_SPLIT_OUT_FEATURES] * len(w.ops)
         self.plan = plan or osdp.Plan([op.k for op in w.ops], staging=staging, split_dim_per_op=dims)
+        # zdp_slices = z: the first z slices of every operator stay sharded (ZDP), the others are DP slices read from
+        # a resident full-layout replica, their gradients written to a full-layout array
+        self.mixed = zdp_slices is not None
+        if self.mixed:
+            self.plan.zdp_mask = [(1 << min(zdp_slices, max(op.k, 1))) - 1 for op in w.ops]
+            for d in self.ops:
+                op, k = d["op"], max(d["op"].k, 1)
+                d["Wfull"] = (torch.randn((op.I * op.O,), generator=g, device="cuda", dtype=torch.float32) * 0.02).to(bf)
+                d["dWfull"] = torch.empty((op.I * op.O,), device="cuda", dtype=bf)
+                starts = [(j * op.I // k) * op.O if rows else j * op.O // k for j in range(k)]
+                d["w_dp"] = [None if j < zdp_slices else d["Wfull"][s:] for j, s in enumerate(starts)]
+                d["dw_dp"] = [None if j < zdp_slices else d["dWfull"][s:] for j, s in enumerate(starts)]
         need, self.peak_staging = 0, 0
         for n, op in enumerate(w.ops):
             for is_bwd in (False, True):
@@ -83,6 +98,15 @@ class Stack:
 
     def step(self, serial=False):
         osdp, sp = self.osdp, (None if serial else self.sp)
+        if self.mixed:
+            for d in self.ops:
+                osdp.osdp_split_linear_fwd_mixed(d["X"], d["W"], d["w_dp"], d["op"].O, d["Y"], 0, self.ws, plan=self.plan,
+                                                 op_index=d["n"], stream_compute=self.sc, stream_copy=sp)
+            for d in reversed(self.ops):
+                osdp.osdp_split_linear_bwd_mixed(d["X"], d["dY"], d["W"], d["w_dp"], d["op"].O, d["dX"], d["dW"],
+                                                 d["dw_dp"], 0, self.ws, plan=self.plan, op_index=d["n"],
+                                                 stream_compute=self.sc, stream_copy=sp)
+            return
         for d in self.ops:
             osdp.osdp_split_linear_fwd(d["X"], d["W"], d["Y"], 0, self.ws, plan=self.plan, op_index=d["n"],
                                        stream_compute=self.sc, stream_copy=sp)
@@ -216,7 +240,7 @@ def main():
                "double": osdp.OSDP_STAGING_DOUBLE, "half": osdp.OSDP_STAGING_HALF}[a.staging]
     w = wl.workload(a.config, a.k)
     rows = a.split_dim == "in"
-    st = Stack(w, staging, torch, osdp, rows=rows)
+    st = Stack(w, staging, torch, osdp, rows=rows, zdp_slices=a.zdp_slices)
     flops = wl.flops(w)
 
     ms, _ = st.run(a.steps, a.warmup, serial=a.serial)
@@ -227,7 +251,8 @@ def main():
     roofline = {"bound": "mfma", "kernel": dom, "achieved": gemms[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(gemms[dom]["tflops"] / PEAK_BF16_TFLOPS, 4),
                 "traffic": (MEASURED_TRAFFIC.get(a.config, {}).get(dom)
-                            if (a.k is None and a.staging == "auto" and not a.serial and not rows) else None),
+                            if (a.k is None and a.staging == "auto" and not a.serial and not rows
+                                and a.zdp_slices is None) else None),
                 "algorithmic_bytes": round(stats[dom]["bytes"] / stats[dom]["launches"]),
                 "avg_launch_us": gemms[dom]["avg_us"], "launches": gemms[dom]["launches"]}
 
@@ -239,7 +264,8 @@ def main():
         "config": {"workload": w.name, "baseline_config": a.config, "T": w.T, "N_shards": w.N, "layers": w.layers,
                    "ops": {op.name: {"I": op.I, "O": op.O, "k": op.k} for op in w.ops},
                    "staging": a.staging, "overlap": not a.serial,
-                   "split_dim": "in_features" if rows else "out_features"},
+                   "split_dim": "in_features" if rows else "out_features",
+                   "zdp_slices": "all" if a.zdp_slices is None else a.zdp_slices},
         "frac_bf16_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3),
         "workspace_mb": round(st.workspace_bytes / 2 ** 20, 3),
@@ -248,6 +274,20 @@ def main():
         "kernels": kernels,
     }
 
+    if not a.no_sweep and a.zdp_slices is None:
+        # Section 3.3, last paragraph: the same granularity with fewer and fewer slices in ZDP mode
+        modes = {}
+        kmax = max(max(op.k, 1) for op in w.ops)
+        for z in sorted({kmax, kmax // 2, 1, 0}, reverse=True):
+            sm = Stack(w, staging, torch, osdp, rows=rows, zdp_slices=z)
+            msz = min(sm.run(max(5, a.steps // 2), max(2, a.warmup // 2), serial=a.serial)[0] for _ in range(2))
+            modes[str(z)] = {"tflops": round(flops / (msz * 1e-3) / 1e12, 2), "ms_per_step": round(msz, 4),
+                             "peak_staging_mb": round(sm.peak_staging / 2 ** 20, 3),
+                             "dp_replica_mb": round(sum((max(op.k, 1) - min(z, max(op.k, 1))) * op.I * op.O * 2 / max(op.k, 1)
+                                                        for op in w.ops) * w.layers / 2 ** 20, 3)}
+            del sm
+            torch.cuda.empty_cache()
+        out["zdp_slices_of_k"] = modes
     if not a.no_auto:
         out["auto_granularity"] = auto_granularity(st, osdp, torch, max(5, a.steps // 2), max(2, a.warmup // 2))
     if not a.no_sweep:

@@ -78,6 +78,14 @@ struct Resolved {
   std::vector<Slice> dw;     // backward: dW launches (dW needs no staged weights, so these may span groups)
 };
 
+// Caller-owned replicas of the slices in DP mode: w[j] / dw[j] point at slice j's weights / gradient, row-major
+// with leading dimension ld ([I x w_j] for column slices, [h_j x O] for row slices).
+struct Replicas {
+  const void *const *w;
+  void *const *dw;
+  int64_t ld;
+};
+
 // Rough duration of one gather launch in microseconds (read + write of the slice at about 3 TB/s).
 double gather_estimate_us(int64_t elems) { return 4.0 * static_cast<double>(elems) / 3.0e6 + 6.0; }
 
@@ -102,8 +110,13 @@ osdp_status check_shape(const osdp_shape *s) {
 // With column slices the forward launches write disjoint column ranges of Y and the dX launches add up; with
 // row slices it is the other way round (Y adds up over the slices, dX is written range by range).  Both cases
 // are planned as "concatenating" and "accumulating" launches over the sub-slices.
+//
+// `rep` (calls only, not the size query): where the DP slices lie.  DP sub-slices that follow one another in memory
+// (the halves of one slice; neighbouring slices inside one full-layout replica) need no staging and so no
+// separation: they are merged into one sub-slice, which only removes launches (the size query, which cannot
+// know, answers for the unmerged plan and is never below what the merged one needs).
 osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, bool overlap_possible,
-                    bool is_bwd, Resolved *r, bool allow_dp = false) {
+                    bool is_bwd, Resolved *r, bool allow_dp = false, const Replicas *rep = nullptr) {
   osdp_status st = check_shape(shape);
   if (st != OSDP_OK) return st;
   int64_t k = shape->k;
@@ -180,6 +193,31 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
       r->start.push_back(c0);
       if (!is_dp) wmax = std::max(wmax, b - a);
     }
+  }
+  if (rep && r->any_dp && rep->w && (!is_bwd || rep->dw)) {
+    size_t out = 0;
+    for (size_t j = 0; j < r->sub.size(); ++j) {
+      bool joins = false;
+      if (out > 0 && r->dp[j] && r->dp[out - 1]) {
+        const int32_t a = r->owner[out - 1], b = r->owner[j];
+        if (a == b) {
+          joins = true;
+        } else {
+          // slice b starts exactly where the merged run ends, in the weights and (backward) in the gradients
+          const int64_t len = r->sub[out - 1].c1 - r->start[out - 1];
+          const int64_t step = rows ? len * rep->ld : len;
+          joins = static_cast<const uint16_t *>(rep->w[b]) == static_cast<const uint16_t *>(rep->w[a]) + step &&
+                  (!is_bwd || static_cast<const uint16_t *>(rep->dw[b]) == static_cast<const uint16_t *>(rep->dw[a]) + step);
+        }
+      }
+      if (joins) {
+        r->sub[out - 1].c1 = r->sub[j].c1;
+      } else {
+        r->sub[out] = r->sub[j]; r->dp[out] = r->dp[j]; r->owner[out] = r->owner[j]; r->start[out] = r->start[j];
+        ++out;
+      }
+    }
+    r->sub.resize(out); r->dp.resize(out); r->owner.resize(out); r->start.resize(out);
   }
   r->slots = (mode == OSDP_STAGING_SINGLE) ? 1 : 2;
   int64_t n_gathered = 0;
@@ -473,14 +511,6 @@ GemmProblem weight_gemm(const Resolved &r, bool is_fwd, int j0, int j1, WeightVi
 
 // dW over the sub-slices [j0, j1), written into the shard-major gradient: column slices give
 // dW[:, c0:c1] = X^T . dY[:, c0:c1], row slices dW[c0:c1, :] = X[:, c0:c1]^T . dY.
-// Caller-owned replicas of the slices in DP mode: w[j] / dw[j] point at slice j's weights / gradient, row-major
-// with leading dimension ld ([I x w_j] for column slices, [h_j x O] for row slices).
-struct Replicas {
-  const void *const *w;
-  void *const *dw;
-  int64_t ld;
-};
-
 // element offset of sub-slice j inside its slice's replica
 int64_t replica_offset(const Resolved &r, const Replicas &rep, int j) {
   const int64_t d = r.sub[j].c0 - r.start[j];
@@ -633,7 +663,7 @@ static osdp_status forward(const osdp_shape *shape, const osdp_plan *plan, int32
   hipStream_t sc = static_cast<hipStream_t>(stream_compute), sp = static_cast<hipStream_t>(stream_copy);
   const bool two_streams = sp != nullptr && sp != sc;
   Resolved r;
-  osdp_status st = resolve(shape, plan, op_index, two_streams, false, &r, allow_dp);
+  osdp_status st = resolve(shape, plan, op_index, two_streams, false, &r, allow_dp, &rep);
   if (st != OSDP_OK) return st;
   if ((st = check_matrix(X, ldx, r.I, "X")) != OSDP_OK) return st;
   if ((st = check_matrix(Y, ldy, r.O, "Y")) != OSDP_OK) return st;
@@ -701,7 +731,7 @@ static osdp_status backward(const osdp_shape *shape, const osdp_plan *plan, int3
   hipStream_t sc = static_cast<hipStream_t>(stream_compute), sp = static_cast<hipStream_t>(stream_copy);
   const bool two_streams = sp != nullptr && sp != sc;
   Resolved r;
-  osdp_status st = resolve(shape, plan, op_index, two_streams, true, &r, allow_dp);
+  osdp_status st = resolve(shape, plan, op_index, two_streams, true, &r, allow_dp, &rep);
   if (st != OSDP_OK) return st;
   if ((st = check_matrix(X, ldx, r.I, "X")) != OSDP_OK) return st;
   if ((st = check_matrix(dY, lddy, r.O, "dY")) != OSDP_OK) return st;
