@@ -284,6 +284,64 @@ OSDP_API osdp_status osdp_granularity_select(const osdp_granularity_candidate *c
                                              size_t staging_budget, size_t workspace_budget,
                                              double max_slowdown, int32_t *chosen);
 
+/* ---- execution-plan search (host only) -------------------------------------
+ * Section 3.1 (problem formulation and cost model), Section 3.2 (Profiler,
+ * Search Engine, Scheduler) and Algorithm 1.  An "operator" here is whatever
+ * unit gets its own mode: a whole operator, or one slice of a split operator
+ * (Section 3.3), whose costs are the operator's divided by the granularity. */
+
+typedef struct {
+  double m_model; /* M_i^(model): bytes of model states (parameters and optimizer states)      */
+  double m_act;   /* M_i^(act): activation bytes per sample                                    */
+  double m_extra; /* M_i^(extra): other bytes (workspaces)                                     */
+  double s_bytes; /* S_i: size of the operator's parameters, as counted by the collectives     */
+  double gamma;   /* gamma_i: computation time per sample                                      */
+} osdp_operator_cost;
+
+typedef struct {
+  int32_t N;      /* parallelism degree                                                        */
+  int32_t b_max;  /* largest batch size to try; 0 = 65536                                      */
+  double alpha;   /* network latency per communication step                                    */
+  double beta;    /* transfer time per unit of s_bytes                                         */
+  double m_limit; /* device memory limit, same unit as the m_* fields                          */
+} osdp_device_info;
+
+typedef struct {
+  int32_t found;             /* 0: not even b = 1 has a plan within the memory limit           */
+  int32_t b;                 /* chosen batch size                                              */
+  double time_per_sample;    /* T(p, b) = (1/b) * sum_i T_i(p_i, b) of the chosen plan         */
+  double memory;             /* M(p, b) of the chosen plan                                     */
+  int32_t batch_sizes_tried; /* number of batch sizes that had a feasible plan                 */
+  int32_t exact;             /* 1: proven optimal; 0: a search ran out of its node budget and  */
+                             /* returned the best plan it had found                            */
+  int32_t reserved;
+  uint64_t plans_visited;    /* nodes of the search trees over all batch sizes                 */
+} osdp_search_result;
+
+/* The cost model of Section 3.1 for one plan: modes[i] = 0 (DP) or 1 (ZDP).
+ *   M(p, b) = sum_i [ M_model_i (DP) or M_model_i / N (ZDP) ] + b * M_act_i + M_extra_i
+ *   T(p, b) = (1/b) * sum_i [ 2 (DP) or 3 (ZDP) ] * (N-1) * (alpha + S_i/N * beta) + b * gamma_i
+ * Sums run over the operators in order.  Either output may be NULL. */
+OSDP_API osdp_status osdp_cost_model(const osdp_operator_cost *ops, int32_t n, const osdp_device_info *dev,
+                                     const uint8_t *modes, int32_t b, double *memory, double *time_per_sample);
+
+/* Algorithm 1.  For b = 1, 2, 3, ... a depth-first search over {DP, ZDP}^n,
+ * pruned when the memory limit can no longer be met or the best time so far
+ * can no longer be beaten, finds a fastest plan with M(p, b) <= m_limit; the
+ * loop ends at the first b with no such plan (or after b_max); the (plan, b)
+ * with the smallest time per sample is returned in modes[n] and *result (of
+ * equally fast batch sizes the smaller).  The search is exact: the time is the
+ * minimum over all 2^n plans up to the rounding of the sums (1e-12 relative);
+ * when several plans reach it, which of them is returned is unspecified.
+ * Operators with identical costs (repeated layers) are decided together, as
+ * a count, and classes are explored cheapest-memory-first (extra time per
+ * byte given back), which keeps models of hundreds of operators to
+ * milliseconds; the worst case (all operators different, costs strongly
+ * correlated) remains exponential, so each batch size's search stops after
+ * 2e7 nodes and result->exact then reads 0. */
+OSDP_API osdp_status osdp_plan_search(const osdp_operator_cost *ops, int32_t n, const osdp_device_info *dev,
+                                      uint8_t *modes, osdp_search_result *result);
+
 /* ---- per-kernel timing (for benchmarks) --------------------------------- */
 
 typedef enum {

@@ -449,6 +449,48 @@ def granularity_select(table, staging_budget: int = 0, workspace_budget: int = 0
     return keep[0]
 
 
+# --------------------------------------------- cost model and plan search (Section 3)
+def cost_model(ops, N: int, alpha: float, beta: float, modes, b: int):
+    """Memory and time of one execution plan (Section 3.1).  ops: (M_model, M_act, M_extra, S, gamma) per operator;
+    modes[i]: 0 = DP, 1 = ZDP.  Returns (M(p, b), T(p, b)) with T the time per sample, (1/b) * sum_i T_i."""
+    mem, time = 0.0, 0.0
+    for (m_model, m_act, m_extra, s, gamma), zdp in zip(ops, modes):
+        mem = mem + ((m_model / N if zdp else m_model) + (b * m_act + m_extra))
+        steps = (3.0 if zdp else 2.0) * (N - 1)
+        time = time + (steps * (alpha + s / N * beta) + b * gamma)
+    return mem, time / b
+
+
+def plan_search(ops, N: int, alpha: float, beta: float, m_limit: float, b_max: int = 0):
+    """Algorithm 1 by exhaustive enumeration: for b = 1, 2, ... every plan of {DP, ZDP}^n is costed, the fastest one
+    within the memory limit is kept (the first in enumeration order among equals: operator 0 varies slowest, DP before
+    ZDP), the loop ends at the first b with no feasible plan, and the best (plan, b) over all b by time per sample is
+    returned (the smaller b among equals) as dict(modes, b, time_per_sample, memory), or None."""
+    n = len(ops)
+    best = None
+    b = 1
+    while b <= (b_max if b_max > 0 else 65536):
+        # every plan at once, one operator after the other so that each plan's sums run left to right
+        bits = (np.arange(1 << n, dtype=np.int64)[:, None] >> np.arange(n - 1, -1, -1, dtype=np.int64)[None, :]) & 1
+        mem = np.zeros(1 << n)
+        time = np.zeros(1 << n)
+        for i, (m_model, m_act, m_extra, s, gamma) in enumerate(ops):
+            rest = b * m_act + m_extra
+            step = alpha + s / N * beta
+            mem = mem + np.where(bits[:, i] == 1, m_model / N + rest, m_model + rest)
+            time = time + np.where(bits[:, i] == 1, 3.0 * (N - 1) * step + b * gamma, 2.0 * (N - 1) * step + b * gamma)
+        ok = mem <= m_limit
+        if not ok.any():
+            break
+        time = np.where(ok, time, np.inf)
+        p = int(np.argmin(time))            # numpy returns the first of equal minima
+        per_sample = time[p] / b
+        if best is None or per_sample < best["time_per_sample"]:
+            best = dict(modes=[int(v) for v in bits[p]], b=b, time_per_sample=float(per_sample), memory=float(mem[p]))
+        b += 1
+    return best
+
+
 # ------------------------------------------------------------ sampled entries
 def _idx(a):
     return np.ascontiguousarray(a, dtype=np.int64)

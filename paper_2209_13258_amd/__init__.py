@@ -5,7 +5,8 @@ The product is ``libosdp.so`` (hand-written HIP for gfx950 behind a C ABI, see
 fails when the library has not been built: there is no fallback path.
 """
 from .binding import *  # noqa: F401,F403
-from .binding import (EXPORTS, KERNEL_NAMES, OsdpError, Plan, lib, osdp_granularity_candidates,
+from .binding import (EXPORTS, KERNEL_NAMES, OsdpError, Plan, lib, osdp_cost_model, osdp_granularity_candidates,
+                      osdp_plan_search,
                       osdp_granularity_measure, osdp_granularity_select, osdp_profile_begin, osdp_profile_end,
                       osdp_row_slice_range, osdp_slice_range, osdp_split_linear_bwd, osdp_split_linear_bwd_mixed,
                       osdp_split_linear_fwd, osdp_split_linear_fwd_mixed,

@@ -39,7 +39,7 @@ EXPORTS = (
     "osdp_split_linear_gather_row_slice", "osdp_split_linear_workspace_bytes", "osdp_split_linear_fwd",
     "osdp_split_linear_bwd", "osdp_split_linear_fwd_mixed", "osdp_split_linear_bwd_mixed",
     "osdp_granularity_candidates", "osdp_granularity_measure",
-    "osdp_granularity_select", "osdp_profile_begin", "osdp_profile_end",
+    "osdp_granularity_select", "osdp_cost_model", "osdp_plan_search", "osdp_profile_begin", "osdp_profile_end",
     "osdp_strerror", "osdp_last_error", "osdp_version",
 )
 
@@ -60,6 +60,22 @@ class osdp_granularity_candidate(ctypes.Structure):
     _fields_ = [("k", ctypes.c_int32), ("staging", ctypes.c_int32), ("split_dim", ctypes.c_int32),
                 ("reserved", ctypes.c_int32), ("peak_weight_staging", ctypes.c_size_t),
                 ("workspace", ctypes.c_size_t), ("ms", ctypes.c_double)]
+
+
+class osdp_operator_cost(ctypes.Structure):
+    _fields_ = [("m_model", ctypes.c_double), ("m_act", ctypes.c_double), ("m_extra", ctypes.c_double),
+                ("s_bytes", ctypes.c_double), ("gamma", ctypes.c_double)]
+
+
+class osdp_device_info(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int32), ("b_max", ctypes.c_int32), ("alpha", ctypes.c_double),
+                ("beta", ctypes.c_double), ("m_limit", ctypes.c_double)]
+
+
+class osdp_search_result(ctypes.Structure):
+    _fields_ = [("found", ctypes.c_int32), ("b", ctypes.c_int32), ("time_per_sample", ctypes.c_double),
+                ("memory", ctypes.c_double), ("batch_sizes_tried", ctypes.c_int32), ("exact", ctypes.c_int32),
+                ("reserved", ctypes.c_int32), ("plans_visited", ctypes.c_uint64)]
 
 
 class osdp_kernel_stats(ctypes.Structure):
@@ -100,13 +116,18 @@ def _load() -> ctypes.CDLL:
                                              vp, vp, cnd, i32, i32, i32]
     lib.osdp_granularity_select.argtypes = [cnd, i32, ctypes.c_size_t, ctypes.c_size_t, ctypes.c_double,
                                             ctypes.POINTER(i32)]
+    opc, dvi = ctypes.POINTER(osdp_operator_cost), ctypes.POINTER(osdp_device_info)
+    lib.osdp_cost_model.argtypes = [opc, i32, dvi, ctypes.POINTER(ctypes.c_uint8), i32,
+                                    ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
+    lib.osdp_plan_search.argtypes = [opc, i32, dvi, ctypes.POINTER(ctypes.c_uint8), ctypes.POINTER(osdp_search_result)]
     lib.osdp_profile_begin.argtypes = [i32]
     lib.osdp_profile_end.argtypes = [ctypes.POINTER(osdp_kernel_stats)]
     for name in ("osdp_slice_range", "osdp_row_slice_range", "osdp_split_linear_gather_slice",
                  "osdp_split_linear_gather_row_slice", "osdp_split_linear_workspace_bytes",
                  "osdp_split_linear_fwd", "osdp_split_linear_bwd", "osdp_split_linear_fwd_mixed",
                  "osdp_split_linear_bwd_mixed", "osdp_granularity_candidates",
-                 "osdp_granularity_measure", "osdp_granularity_select", "osdp_profile_begin", "osdp_profile_end"):
+                 "osdp_granularity_measure", "osdp_granularity_select", "osdp_cost_model", "osdp_plan_search",
+                 "osdp_profile_begin", "osdp_profile_end"):
         getattr(lib, name).restype = ctypes.c_int
     lib.osdp_strerror.argtypes = [ctypes.c_int]
     lib.osdp_strerror.restype = ctypes.c_char_p
@@ -304,6 +325,36 @@ def osdp_granularity_select(cands, staging_budget: int = 0, workspace_budget: in
     _check(lib.osdp_granularity_select(cands, len(cands), int(staging_budget), int(workspace_budget),
                                        float(max_slowdown), ctypes.byref(chosen)))
     return chosen.value
+
+
+def _costs(ops):
+    """ops: sequence of (m_model, m_act, m_extra, s_bytes, gamma)."""
+    return (osdp_operator_cost * len(ops))(*[osdp_operator_cost(*map(float, o)) for o in ops])
+
+
+def _device(N, alpha, beta, m_limit, b_max=0):
+    return osdp_device_info(int(N), int(b_max), float(alpha), float(beta), float(m_limit))
+
+
+def osdp_cost_model(ops, N, alpha, beta, m_limit, modes, b):
+    """(M(p, b), T(p, b)) of Section 3.1 for the plan ``modes`` (0 = DP, 1 = ZDP per operator)."""
+    mem, t = ctypes.c_double(), ctypes.c_double()
+    dev = _device(N, alpha, beta, m_limit)
+    m = (ctypes.c_uint8 * len(modes))(*modes)
+    _check(lib.osdp_cost_model(_costs(ops), len(ops), ctypes.byref(dev), m, int(b), ctypes.byref(mem), ctypes.byref(t)))
+    return mem.value, t.value
+
+
+def osdp_plan_search(ops, N, alpha, beta, m_limit, b_max=0):
+    """Algorithm 1.  Returns None when nothing fits, else dict(modes, b, time_per_sample, memory, ...)."""
+    dev = _device(N, alpha, beta, m_limit, b_max)
+    modes = (ctypes.c_uint8 * len(ops))()
+    res = osdp_search_result()
+    _check(lib.osdp_plan_search(_costs(ops), len(ops), ctypes.byref(dev), modes, ctypes.byref(res)))
+    if not res.found:
+        return None
+    return dict(modes=list(modes), b=res.b, time_per_sample=res.time_per_sample, memory=res.memory,
+                batch_sizes_tried=res.batch_sizes_tried, plans_visited=res.plans_visited, exact=bool(res.exact))
 
 
 def osdp_profile_begin(max_launches: int = 1 << 16) -> None:

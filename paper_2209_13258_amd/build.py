@@ -10,7 +10,7 @@ PKG = Path(__file__).resolve().parent
 ROOT = PKG.parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libosdp.so"
-SOURCES = ["osdp_api.hip", "osdp_gather.hip", "osdp_gemm.hip"]
+SOURCES = ["osdp_api.hip", "osdp_gather.hip", "osdp_gemm.hip", "osdp_search.hip"]
 HEADERS = [CSRC / "osdp_internal.h", CSRC / "gemm_common.h", CSRC / "gemm_dma.h", ROOT / "include" / "osdp.h"]
 
 HIPCC_FLAGS = [

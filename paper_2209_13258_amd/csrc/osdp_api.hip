@@ -579,6 +579,13 @@ osdp_status check_replicas(const Resolved &r, const Replicas &rep, bool need_dw)
 
 }  // namespace
 
+namespace osdp {
+osdp_status report_error(osdp_status status, const char *message) {
+  t_last_error = message;
+  return status;
+}
+}  // namespace osdp
+
 // =============================================================================
 extern "C" {
 

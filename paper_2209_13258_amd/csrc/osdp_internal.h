@@ -73,4 +73,7 @@ double gemm_estimate_us(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gather(const ShardTable &shards, const ShardLayout &layout, int64_t r0, int64_t rows, int64_t c0,
                          int64_t w, void *staging, hipStream_t stream);
 
+// Stores the message as the calling thread's last error (osdp_last_error) and returns `status`.
+osdp_status report_error(osdp_status status, const char *message);
+
 }  // namespace osdp
