@@ -54,7 +54,7 @@ def parse():
 class Stack:
     """All operators of a workload resident on the GPU, with one shared workspace."""
 
-    def __init__(self, w, staging, torch, osdp, seed=0, rows=False, plan=None, zdp_slices=None):
+    def __init__(self, w, staging, torch, osdp, seed=0, rows=False, plan=None, zdp_slices=None, zdp_masks=None):
         self.w, self.torch, self.osdp = w, torch, osdp
         g = torch.Generator(device="cuda")
         g.manual_seed(220913258 + seed)
@@ -77,16 +77,18 @@ class Stack:
         self.plan = plan or osdp.Plan([op.k for op in w.ops], staging=staging, split_dim_per_op=dims)
         # zdp_slices = z: the first z slices of every operator stay sharded (ZDP), the others are DP slices read from
         # a resident full-layout replica, their gradients written to a full-layout array
-        self.mixed = zdp_slices is not None
+        self.mixed = zdp_slices is not None or zdp_masks is not None
         if self.mixed:
-            self.plan.zdp_mask = [(1 << min(zdp_slices, max(op.k, 1))) - 1 for op in w.ops]
+            self.plan.zdp_mask = list(zdp_masks) if zdp_masks is not None else \
+                [(1 << min(zdp_slices, max(op.k, 1))) - 1 for op in w.ops]
             for d in self.ops:
                 op, k = d["op"], max(d["op"].k, 1)
                 d["Wfull"] = (torch.randn((op.I * op.O,), generator=g, device="cuda", dtype=torch.float32) * 0.02).to(bf)
                 d["dWfull"] = torch.empty((op.I * op.O,), device="cuda", dtype=bf)
                 starts = [(j * op.I // k) * op.O if rows else j * op.O // k for j in range(k)]
-                d["w_dp"] = [None if j < zdp_slices else d["Wfull"][s:] for j, s in enumerate(starts)]
-                d["dw_dp"] = [None if j < zdp_slices else d["dWfull"][s:] for j, s in enumerate(starts)]
+                mask = self.plan.zdp_mask[d["n"]]
+                d["w_dp"] = [None if (mask >> j) & 1 else d["Wfull"][s:] for j, s in enumerate(starts)]
+                d["dw_dp"] = [None if (mask >> j) & 1 else d["dWfull"][s:] for j, s in enumerate(starts)]
         need, self.peak_staging = 0, 0
         for n, op in enumerate(w.ops):
             for is_bwd in (False, True):
@@ -186,6 +188,48 @@ def auto_granularity(st, osdp, torch, steps, warmup):
                                      "peak_staging_mb": round(tuned.peak_staging / 2 ** 20, 3),
                                      "workspace_mb": round(tuned.workspace_bytes / 2 ** 20, 3)}
     return out
+
+
+def plan_search(w, kernels, staging, rows, torch, osdp, steps, warmup):
+    """Algorithm 1 on this workload with device information taken from this run: every slice of every operator is
+    an item (Section 3.3), gamma from the measured GEMM throughput, beta from the measured gather bandwidth, alpha
+    from the gather's launch-bound floor; the memory limit leaves room for half of the weights to be replicated.
+    The chosen per-slice modes are then run through the mixed entry points and timed."""
+    import workloads as wl
+    gemm_ms = sum(v["total_ms"] for k, v in kernels.items() if k.startswith("gemm"))
+    gemm_flops = sum(v["tflops"] * v["total_ms"] for k, v in kernels.items() if k.startswith("gemm")) * 1e9
+    flops_per_s = gemm_flops / (gemm_ms * 1e-3)
+    gather = kernels.get("gather")
+    beta = 1.0 / (gather["gbs_algorithmic"] * 1e9 / 2) if gather else 1.0 / 2e12   # seconds per byte gathered
+    alpha = 5e-6
+    items, owner = [], []
+    for layer in range(w.layers):
+        for n, op in enumerate(w.ops):
+            k = max(op.k, 1)
+            for j in range(k):
+                size = op.I * op.O * 2 / k
+                # model states = the bf16 weights and their gradient; no activations are kept by this path
+                items.append((2 * size, 0.0, 0.0, size, 6.0 * op.I * op.O / k / flops_per_s))
+                owner.append((layer, n, j))
+    limit = 0.5 * sum(i[0] for i in items) * (1 + 1 / w.N)
+    t0 = time.perf_counter()
+    r = osdp.osdp_plan_search(items, w.N, alpha, beta, limit, b_max=w.T)
+    search_ms = (time.perf_counter() - t0) * 1e3
+    if r is None:
+        return {"found": False, "search_ms": round(search_ms, 3)}
+    masks = [0] * len(w.ops)   # the stack shares one plan over its layers: take the first layer's modes
+    for (layer, n, j), m in zip(owner, r["modes"]):
+        if layer == 0 and m:
+            masks[n] |= 1 << j
+    st = Stack(w, staging, torch, osdp, rows=rows, zdp_masks=masks)
+    ms = min(st.run(steps, warmup)[0] for _ in range(2))
+    return {"found": True, "items": len(items), "memory_limit_mb": round(limit / 2 ** 20, 3),
+            "device_info": {"alpha_s": alpha, "beta_s_per_byte": beta, "gemm_flops_per_s": flops_per_s},
+            "zdp_mask_per_op": {op.name: bin(m) for op, m in zip(w.ops, masks)}, "zdp_items": int(sum(r["modes"])),
+            "model_memory_mb": round(r["memory"] / 2 ** 20, 3), "search_ms": round(search_ms, 3),
+            "plans_visited": r["plans_visited"], "exact": r["exact"], "batch_sizes_tried": r["batch_sizes_tried"],
+            "measured_ms_per_step": round(ms, 4), "measured_tflops": round(wl.flops(w) / (ms * 1e-3) / 1e12, 2),
+            "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3)}
 
 
 def cpu_baseline(w, target_s=15.0, rows=False):
@@ -288,6 +332,8 @@ def main():
             del sm
             torch.cuda.empty_cache()
         out["zdp_slices_of_k"] = modes
+    if not a.no_sweep and a.zdp_slices is None:
+        out["plan_search"] = plan_search(w, kernels, staging, rows, torch, osdp, max(5, a.steps // 2), max(2, a.warmup // 2))
     if not a.no_auto:
         out["auto_granularity"] = auto_granularity(st, osdp, torch, max(5, a.steps // 2), max(2, a.warmup // 2))
     if not a.no_sweep:

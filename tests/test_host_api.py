@@ -24,6 +24,9 @@ def test_struct_layouts_match_the_header():
     assert ctypes.sizeof(osdp.binding.osdp_shape) == 32
     assert ctypes.sizeof(osdp.binding.osdp_plan) == 48
     assert ctypes.sizeof(osdp.binding.osdp_granularity_candidate) == 40
+    assert ctypes.sizeof(osdp.binding.osdp_operator_cost) == 40
+    assert ctypes.sizeof(osdp.binding.osdp_device_info) == 32
+    assert ctypes.sizeof(osdp.binding.osdp_search_result) == 48
     assert ctypes.sizeof(osdp.binding.osdp_kernel_stats) == 32
 
 
