@@ -7,7 +7,16 @@ namespace osdp {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// One matrix-core step of every GEMM kernel here: a 16 x 16 block of C gains the product over 32 consecutive k.
+// Lane l supplies 8 consecutive k (8 * (l / 16) ..) of row / column l % 16 of each operand.  The operands are
+// passed swapped (the B fragment first), so that lane l ends up with C[m = l % 16][n = 4 * (l / 16) + 0..3]:
+// runs of 4 consecutive output columns.  All kernels use this one instruction with k ascending, which is what
+// makes their results bit-identical whatever the tile shape.
+__device__ __forceinline__ f32x4 mma_16x16x32(bf16x8 a_rows, bf16x8 b_cols, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(b_cols, a_rows, c, 0, 0, 0);
+}
 
 struct GemmParams {
   int32_t M, N, K;
@@ -62,67 +71,61 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int *tm,
 }
 
 // Accumulator layout of one wave: acc[bm][bn][i] is C[m][n] with
-//   m = m_base + 32*bm + l32,  n = n_base + 32*bn + 8*(i/4) + 4*g + i%4
-// (l32 = lane % 32, g = lane / 32): the MFMA is fed B as its first operand, so a lane holds
-// runs of 4 consecutive output columns.  No bounds checks: the caller's tile is full.
+//   m = m_base + 16*bm + l16,  n = n_base + 16*bn + 4*q + i        (l16 = lane % 16, q = lane / 16).
+// No bounds checks: the caller's tile is full.
 template <int MB, int NB>
-__device__ __forceinline__ void load_acc_tile(const GemmParams &p, f32x16 (&acc)[MB][NB], int m_base, int n_base,
-                                              int l32, int g) {
+__device__ __forceinline__ void load_acc_tile(const GemmParams &p, f32x4 (&acc)[MB][NB], int m_base, int n_base,
+                                              int l16, int q) {
 #pragma unroll
   for (int bm = 0; bm < MB; ++bm)
 #pragma unroll
     for (int bn = 0; bn < NB; ++bn) {
-      const float *src = p.acc_in + static_cast<int64_t>(m_base + bm * 32 + l32) * p.ld_acc + n_base + bn * 32 + 4 * g;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float4 c = *reinterpret_cast<const float4 *>(src + 8 * q);
-        acc[bm][bn][4 * q + 0] = c.x;
-        acc[bm][bn][4 * q + 1] = c.y;
-        acc[bm][bn][4 * q + 2] = c.z;
-        acc[bm][bn][4 * q + 3] = c.w;
-      }
+      const float *src = p.acc_in + static_cast<int64_t>(m_base + bm * 16 + l16) * p.ld_acc + n_base + bn * 16 + 4 * q;
+      const float4 c = *reinterpret_cast<const float4 *>(src);
+      acc[bm][bn][0] = c.x;
+      acc[bm][bn][1] = c.y;
+      acc[bm][bn][2] = c.z;
+      acc[bm][bn][3] = c.w;
     }
 }
 
+// Stores 4 consecutive columns of row m starting at column n according to the epilogue.
+template <int kEpi>
+__device__ __forceinline__ void store_acc4(const GemmParams &p, f32x4 c, int m, int n, uint16_t *const *s_tab) {
+  if (kEpi == static_cast<int>(Epilogue::kF32Workspace)) {
+    float4 o = {c[0], c[1], c[2], c[3]};
+    *reinterpret_cast<float4 *>(static_cast<float *>(p.C) + static_cast<int64_t>(m) * p.ldc + n) = o;
+    return;
+  }
+  uint2 o = {pack_bf16x2(c[0], c[1]), pack_bf16x2(c[2], c[3])};
+  uint16_t *dst;
+  if (kEpi == static_cast<int>(Epilogue::kBf16RowMajor)) {
+    dst = static_cast<uint16_t *>(p.C) + static_cast<int64_t>(m) * p.ldc + n;
+  } else {
+    int s;
+    int64_t off;
+    const int row = m + static_cast<int>(p.r0);
+    if (p.lay.rows_per_shard > 0) {
+      s = row / p.lay.rows_per_shard;
+      off = static_cast<int64_t>(row - s * p.lay.rows_per_shard) * p.lay.O + p.c0 + n;
+    } else {
+      const int64_t f = static_cast<int64_t>(row) * p.lay.O + p.c0 + n;
+      s = static_cast<int>(f / p.lay.L);
+      off = f - static_cast<int64_t>(s) * p.lay.L;
+    }
+    dst = s_tab[s] + off;
+  }
+  *reinterpret_cast<uint2 *>(dst) = o;
+}
+
 template <int MB, int NB, int kEpi>
-__device__ __forceinline__ void store_acc_tile(const GemmParams &p, const f32x16 (&acc)[MB][NB], int m_base, int n_base,
-                                               int l32, int g, uint16_t *const *s_tab) {
+__device__ __forceinline__ void store_acc_tile(const GemmParams &p, const f32x4 (&acc)[MB][NB], int m_base, int n_base,
+                                               int l16, int q, uint16_t *const *s_tab) {
 #pragma unroll
   for (int bm = 0; bm < MB; ++bm)
 #pragma unroll
-    for (int bn = 0; bn < NB; ++bn) {
-      const int m = m_base + bm * 32 + l32;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = n_base + bn * 32 + 8 * q + 4 * g;
-        const float c0 = acc[bm][bn][4 * q], c1 = acc[bm][bn][4 * q + 1], c2 = acc[bm][bn][4 * q + 2],
-                    c3 = acc[bm][bn][4 * q + 3];
-        if (kEpi == static_cast<int>(Epilogue::kF32Workspace)) {
-          float4 o = {c0, c1, c2, c3};
-          *reinterpret_cast<float4 *>(static_cast<float *>(p.C) + static_cast<int64_t>(m) * p.ldc + n) = o;
-        } else {
-          uint2 o = {pack_bf16x2(c0, c1), pack_bf16x2(c2, c3)};
-          uint16_t *dst;
-          if (kEpi == static_cast<int>(Epilogue::kBf16RowMajor)) {
-            dst = static_cast<uint16_t *>(p.C) + static_cast<int64_t>(m) * p.ldc + n;
-          } else {
-            int s;
-            int64_t off;
-            const int row = m + static_cast<int>(p.r0);
-            if (p.lay.rows_per_shard > 0) {
-              s = row / p.lay.rows_per_shard;
-              off = static_cast<int64_t>(row - s * p.lay.rows_per_shard) * p.lay.O + p.c0 + n;
-            } else {
-              const int64_t f = static_cast<int64_t>(row) * p.lay.O + p.c0 + n;
-              s = static_cast<int>(f / p.lay.L);
-              off = f - static_cast<int64_t>(s) * p.lay.L;
-            }
-            dst = s_tab[s] + off;
-          }
-          *reinterpret_cast<uint2 *>(dst) = o;
-        }
-      }
-    }
+    for (int bn = 0; bn < NB; ++bn)
+      store_acc4<kEpi>(p, acc[bm][bn], m_base + bm * 16 + l16, n_base + bn * 16 + 4 * q, s_tab);
 }
 
 }  // namespace

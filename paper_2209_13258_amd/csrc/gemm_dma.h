@@ -1,6 +1,7 @@
 // Main GEMM kernel of libosdp: tiles stream from global memory straight into LDS
 // (global_load_lds_dwordx4, no staging registers), a ring of LDS stages keeps one or more K
-// blocks in flight behind the MFMAs, and operand fragments are double-buffered in registers.
+// blocks in flight behind the MFMAs (v_mfma_f32_16x16x32_bf16), and operand fragments are
+// double-buffered in registers.
 //
 // Needs M % BM == 0, N % BN == 0, K % BK == 0; there are no bounds checks.
 //
@@ -11,7 +12,8 @@
 //       f(r) = (r >> 1) & 7 for BK = 64, (r >> 2) & 3 for BK = 32, so that the 16 rows a
 //       ds_read_b128 serves per cycle fall into 16 different 16-byte bank groups.
 //   MN-contiguous operand [BK][rows]   : 64-byte granule w of k-row k is stored at granule
-//       w ^ (k & 3), so that the 4 k-rows one ds_read_b64_tr_b16 group touches are 64 bytes apart.
+//       w ^ (k & 3) and its 32-byte halves are swapped when bit 3 of k is set, so that the k-rows the
+//       lane groups of one ds_read_b64_tr_b16 phase touch fall into different bank groups.
 #pragma once
 #include "gemm_common.h"
 
@@ -52,12 +54,18 @@ struct DmaOperand {
   static constexpr int VPR = kRows / 8, KPL = 64 / VPR;  // MN-contiguous: 16-byte vectors per k-row, k-rows per load
   static_assert(kBK == 64 || kBK == 32, "BK is 32 or 64");
   static_assert(kKC || (kRows >= 128 && kRows <= 512), "MN-contiguous tiles are 128..512 wide");
+  static_assert(kKC || (kWaves * KPL) % 16 == 0, "a wave's loads must be a multiple of 16 k-rows apart");
 
   static __device__ __forceinline__ int swz_k(int row) { return CPR == 8 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+  // MN-contiguous: element offset mn of k-row k is stored at mn ^ swz_mn(k): the 64-byte granule index is
+  // XORed with k & 3 and the 32-byte half inside the granule with bit 3 of k, so that the 8 k-rows the two
+  // lane groups of one transposing-read phase touch (k, k+1, k+2, k+3 and the same + 8) fall into 8 different
+  // 32-byte bank groups.
+  static __device__ __forceinline__ int swz_mn(int krow) { return ((krow & 3) << 5) | (((krow >> 3) & 1) << 4); }
 
   // Element offset, from the tile origin (mn = 0 of the tile, k = k0), of the 16 bytes this lane fetches in
   // its wave's load 0.  Load p of the wave adds p * load_stride(); the swizzle terms do not change with p
-  // because a wave's loads are a multiple of 16 rows (4 k-rows) apart.
+  // because a wave's loads are a multiple of 16 rows (16 k-rows) apart.
   static __device__ __forceinline__ int64_t lane_src(int wave, int lane, int64_t ld) {
     if (kKC) {
       const int row = wave * RPL + lane / CPR;
@@ -66,8 +74,7 @@ struct DmaOperand {
     } else {
       const int krow = wave * KPL + lane / VPR;
       const int pv = lane % VPR;
-      const int lv = (((pv >> 2) ^ (krow & 3)) << 2) | (pv & 3);
-      return static_cast<int64_t>(krow) * ld + lv * 8;
+      return static_cast<int64_t>(krow) * ld + ((pv * 8) ^ swz_mn(krow));
     }
   }
   static __device__ __forceinline__ int64_t load_stride(int64_t ld) {
@@ -75,23 +82,20 @@ struct DmaOperand {
   }
   static __device__ __forceinline__ int64_t block_stride(int64_t ld) { return kKC ? kBK : static_cast<int64_t>(kBK) * ld; }
 
-  // Issues this wave's loads of one K block into the stage at LDS byte address `stage` (the operand's area).
-  static __device__ __forceinline__ void issue(const uint16_t *src, int64_t lstride, uint32_t stage, int wave) {
-#pragma unroll
-    for (int p = 0; p < kLoads; ++p) dma16(src + p * lstride, stage + (wave + kWaves * p) * 1024);
-  }
-
-  // Fragment of the 32-row block at mn0 for K step kk: lane (l32, g) gets k = 16*kk + 8*g + 0..7 of row mn0 + l32.
+  // Fragment of the 16-row block at mn0 for K step kk (32 wide): lane (l16, q) gets k = 32*kk + 8*q + 0..7 of
+  // row mn0 + l16.
   static __device__ __forceinline__ bf16x8 frag(const uint16_t *s, int mn0, int kk, int lane) {
     if (kKC) {
-      const int r = mn0 + (lane & 31);
-      const int c = (kk * 2 + (lane >> 5)) ^ swz_k(r);
+      const int r = mn0 + (lane & 15);
+      const int c = (kk * 4 + (lane >> 4)) ^ swz_k(r);
       return *reinterpret_cast<const bf16x8 *>(s + r * kBK + c * 8);
     } else {
+      // ds_read_b64_tr_b16: within 16 lanes, lane s supplies 4 consecutive mn of k-row s / 4 and lane i
+      // receives the 4 k of mn i; two reads, 4 k-rows apart, give the lane its 8 consecutive k
       const int i = lane & 15;
-      const int krow = kk * 16 + (lane >> 5) * 8 + (i >> 2);
-      const int mn = mn0 + ((lane >> 4) & 1) * 16 + (i & 3) * 4;
-      const uint16_t *q = s + krow * kRows + (((mn >> 5) ^ (krow & 3)) << 5) + (mn & 31);
+      const int krow = kk * 32 + (lane >> 4) * 8 + (i >> 2);
+      const int mn = mn0 + (i & 3) * 4;
+      const uint16_t *q = s + krow * kRows + (mn ^ swz_mn(krow));
       typedef dma_s16x4 __attribute__((address_space(3))) * lds_s16x4;
       const dma_s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(q));
       const dma_s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4)(q + 4 * kRows));
@@ -101,16 +105,30 @@ struct DmaOperand {
   }
 };
 
+// Compile-time integers as lambda arguments.
+template <int v>
+struct Int {
+  static constexpr int value = v;
+};
+
+// Workgroups of one tile shape that fit a CU's 160 KB of LDS together (at most 2 are aimed for), and the waves
+// per SIMD that this takes: the register budget the compiler is held to.
+constexpr int dma_groups_per_cu(int BM, int BN, int BK, int kStages) {
+  return (2 * (kStages * (BM + BN) * BK * 2 + OSDP_MAX_SHARDS * 8) <= 160 * 1024) ? 2 : 1;
+}
+
 template <int BM, int BN, int WM, int WN, int BK, int kStages, bool kAK, bool kBK, int kEpi, bool kAccIn>
-__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(GemmParams p, int tiles_m, int tiles_n) {
+__global__ __launch_bounds__((BM / WM) * (BN / WN) * 64, dma_groups_per_cu(BM, BN, BK, kStages) * (BM / WM) * (BN / WN) / 4)
+void gemm_dma_kernel(GemmParams p, int tiles_m, int tiles_n) {
   constexpr int kWaves = (BM / WM) * (BN / WN);
-  constexpr int MB = WM / 32, NB = WN / 32, KS = BK / 16;
+  constexpr int MB = WM / 16, NB = WN / 16, NH = NB / 2;  // 16 x 16 blocks of the wave tile; B blocks per half
+  constexpr int KS = BK / 32;                              // K steps per block
+  constexpr int U = 2 * KS;                                // micro-steps per block: (K step, half of the B blocks)
+  static_assert(NB % 2 == 0, "the wave tile is split in two column halves");
   using OpA = DmaOperand<kAK, BM, BK, kWaves>;
   using OpB = DmaOperand<kBK, BN, BK, kWaves>;
   constexpr int kStageElems = OpA::kElems + OpB::kElems;
-  constexpr int kLoadsPerStage = OpA::kLoads + OpB::kLoads;
   static_assert(kStages >= 2 && kStages <= 4, "2 to 4 LDS stages");
-  static_assert((kStages - 2) * kLoadsPerStage < 64, "in-flight loads must fit the vmcnt counter");
   extern __shared__ __attribute__((aligned(1024))) uint16_t smem[];
   __shared__ uint16_t *s_tab[OSDP_MAX_SHARDS];
 
@@ -123,7 +141,7 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
   const int m0 = tm * BM, n0 = tn * BN;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave / (BN / WN)) * WM, wn = (wave % (BN / WN)) * WN;
-  const int l32 = lane & 31, g = lane >> 5;
+  const int l16 = lane & 15, q4 = lane >> 4;
 
   const uint16_t *gA = (kAK ? p.A + static_cast<int64_t>(m0) * p.lda : p.A + m0) + OpA::lane_src(wave, lane, p.lda);
   // B may come in two column segments (two staged slices): the tile lies in one of them
@@ -137,24 +155,26 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
   const int64_t bsA = OpA::block_stride(p.lda), bsB = OpB::block_stride(ldb);
   const int nk = p.K / BK;
 
-  f32x16 acc[MB][NB];
+  f32x4 acc[MB][NB];
   if (kAccIn) {
-    load_acc_tile<MB, NB>(p, acc, m0 + wm, n0 + wn, l32, g);
+    load_acc_tile<MB, NB>(p, acc, m0 + wm, n0 + wn, l16, q4);
   } else {
 #pragma unroll
     for (int bm = 0; bm < MB; ++bm)
 #pragma unroll
       for (int bn = 0; bn < NB; ++bn)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[bm][bn][i] = 0.f;
+        for (int i = 0; i < 4; ++i) acc[bm][bn][i] = 0.f;
   }
 
   // ---- global -> LDS: the LA + LB wave-level loads of one K block, issued in shares ------------------
   constexpr int LA = OpA::kLoads, LB = OpB::kLoads, L = LA + LB;
-  // With two stages block it+1 must be complete before the barrier that sits one K step before the end
-  // of block it, so its loads are spread over the K steps before that barrier; with more stages they
-  // are spread over all K steps.
-  constexpr int kIssueSteps = (kStages == 2 && KS > 1) ? KS - 1 : KS;
+  static_assert((kStages - 1) * L < 64, "in-flight loads must fit the vmcnt counter");
+  // The workgroup barrier of block it sits after the MFMAs of its micro-step U-2 and block it+1 must have
+  // landed there.  With two stages the loads of block it+1 can only start once the barrier of block it-1 has
+  // freed their stage, so they are spread over the micro-steps before the barrier; with more stages the loads
+  // of block it+kStages-1 are spread over all micro-steps.
+  constexpr int kIssueSteps = (kStages == 2 && U > 1) ? U - 1 : U;
   int first_seg = p.k_split ? p.k_split / BK : nk;  // K blocks left in the first B segment
   int64_t lsB_cur = lsB, bsB_cur = bsB;
   const uint32_t lds_base = lds_address(smem);
@@ -187,49 +207,68 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
   else wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
 
-  bf16x8 fa[2][MB], fb[2][NB];
-  auto frags = [&](int stage, int kk, int buf) {
+  // Fragments in registers: the A blocks of two K steps (alternating), the B blocks of two micro-steps.
+  bf16x8 fa[2][MB], fb[2][NH];
+  auto read_a = [&](int stage, int kk, auto buf) {
     const uint16_t *cA = smem + stage * kStageElems;
-    const uint16_t *cB = cA + OpA::kElems;
 #pragma unroll
-    for (int bm = 0; bm < MB; ++bm) fa[buf][bm] = OpA::frag(cA, wm + bm * 32, kk, lane);
-#pragma unroll
-    for (int bn = 0; bn < NB; ++bn) fb[buf][bn] = OpB::frag(cB, wn + bn * 32, kk, lane);
+    for (int bm = 0; bm < MB; ++bm) fa[decltype(buf)::value][bm] = OpA::frag(cA, wm + bm * 16, kk, lane);
   };
-  auto mfmas = [&](int buf) {
+  auto read_b = [&](int stage, int kk, int half, auto buf) {
+    const uint16_t *cB = smem + stage * kStageElems + OpA::kElems;
 #pragma unroll
-    for (int bm = 0; bm < MB; ++bm)
+    for (int bn = 0; bn < NH; ++bn) fb[decltype(buf)::value][bn] = OpB::frag(cB, wn + (half * NH + bn) * 16, kk, lane);
+  };
+  auto mfmas = [&](auto abuf, auto bbuf, auto half) {
 #pragma unroll
-      for (int bn = 0; bn < NB; ++bn) {
-        acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[buf][bn], fa[buf][bm], acc[bm][bn], 0, 0, 0);
-      }
+    for (int bn = 0; bn < NH; ++bn)
+#pragma unroll
+      for (int bm = 0; bm < MB; ++bm)
+        acc[bm][decltype(half)::value * NH + bn] =
+            mma_16x16x32(fa[decltype(abuf)::value][bm], fb[decltype(bbuf)::value][bn], acc[bm][decltype(half)::value * NH + bn]);
   };
 
-  // Steady state.  Per K block `it` (stage cur) and K step kk:
-  //   - the fragments of step kk+1 are read from LDS while the MFMAs of step kk run;
+  // Steady state, one K block `it` (stage cur) = U micro-steps.  In micro-step u = (K step kk, column half h):
+  //   - the fragments of micro-step u+1 are read from LDS (the other half of the B blocks; the A blocks too when
+  //     it starts a new K step) while the MB * NH MFMAs of micro-step u run;
   //   - a share of the loads of block it+kStages-1 goes out (stage nxt, freed by the previous barrier);
-  //   - after the MFMAs of the step before the last, every wave has all fragments of block it in
-  //     registers: block it+1 is awaited and the workgroup barrier is taken there, so that the last
-  //     step's MFMAs cover the first fragment reads of block it+1.
-  static_assert(KS == 2 || KS == 4, "K block of 32 or 64");
-  frags(0, 0, 0);
+  //   - after the MFMAs of micro-step U-2 every fragment read of block it has been issued: block it+1 is awaited
+  //     and the workgroup barrier taken there, so that the last micro-step's MFMAs cover the first fragment
+  //     reads of block it+1.
+  // `par` is the parity of the block's first K step: A fragments of K step kk sit in fa[(par + kk) & 1].
   int cur = 0, nxt = kStages - 1;
-  for (int it = 0; it < nk; ++it) {
+  auto block = [&](int it, auto par) {
+    constexpr int P = decltype(par)::value;
     const bool more = it + kStages - 1 < nk;
     const bool follows = it + 1 < nk;
     const int next_stage = (cur + 1 == kStages) ? 0 : cur + 1;
 #pragma unroll
-    for (int kk = 0; kk < KS; ++kk) {
-      if (kk + 1 < KS) frags(cur, kk + 1, (kk + 1) & 1);
-      else if (follows) frags(next_stage, 0, 0);
-      if (more && kk < kIssueSteps) issue_range(nxt, kk * L / kIssueSteps, (kk + 1) * L / kIssueSteps);
+    for (int u = 0; u < U; ++u) {
+      const int kk = u >> 1, h = u & 1;
+      // fragments of micro-step u+1 (its B half goes to fb[(u+1) & 1]; U is even, so the first micro-step of a
+      // block always uses fb[0])
+      if (u + 1 < U) {
+        const int kk2 = (u + 1) >> 1, h2 = (u + 1) & 1;
+        if (h2 == 0) {
+          if (((P + kk2) & 1) == 0) read_a(cur, kk2, Int<0>{}); else read_a(cur, kk2, Int<1>{});
+        }
+        if (((u + 1) & 1) == 0) read_b(cur, kk2, h2, Int<0>{}); else read_b(cur, kk2, h2, Int<1>{});
+      } else if (follows) {
+        if (((P + KS) & 1) == 0) read_a(next_stage, 0, Int<0>{}); else read_a(next_stage, 0, Int<1>{});
+        read_b(next_stage, 0, 0, Int<0>{});
+      }
+      if (more && u < kIssueSteps) issue_range(nxt, u * L / kIssueSteps, (u + 1) * L / kIssueSteps);
       __builtin_amdgcn_sched_barrier(0);
-      mfmas(kk & 1);
+      if (((P + kk) & 1) == 0) {
+        if (h == 0) mfmas(Int<0>{}, Int<0>{}, Int<0>{}); else mfmas(Int<0>{}, Int<1>{}, Int<1>{});
+      } else {
+        if (h == 0) mfmas(Int<1>{}, Int<0>{}, Int<0>{}); else mfmas(Int<1>{}, Int<1>{}, Int<1>{});
+      }
       __builtin_amdgcn_sched_barrier(0);
-      if (kk == KS - 2) {
+      if (u == U - 2) {
         // loads issued after the last load of block it+1: the full blocks it+2 .. it+kStages-2 and the
-        // shares of block it+kStages-1 issued so far in this iteration
-        constexpr int kYounger = (kStages >= 3) ? (kStages - 3) * L + (KS - 1) * L / kIssueSteps : 0;
+        // shares of block it+kStages-1 issued so far in this block
+        constexpr int kYounger = (kStages >= 3) ? (kStages - 3) * L + (U - 1) * L / kIssueSteps : 0;
         if (more) wait_vmcnt<kYounger>();
         else wait_vmcnt<0>();
         __builtin_amdgcn_s_waitcnt((15) | (7 << 4) | (0 << 8) | (3 << 14));  // lgkmcnt(0): this wave's LDS reads are done
@@ -239,9 +278,20 @@ __global__ __launch_bounds__((BM / WM) * (BN / WN) * 64) void gemm_dma_kernel(Ge
     }
     cur = next_stage;
     nxt = (nxt + 1 == kStages) ? 0 : nxt + 1;
+  };
+
+  read_a(0, 0, Int<0>{});
+  read_b(0, 0, 0, Int<0>{});
+  if (KS % 2 == 0) {
+    for (int it = 0; it < nk; ++it) block(it, Int<0>{});
+  } else {  // an odd number of K steps per block: the A fragment buffers swap roles from block to block
+    for (int it = 0; it < nk; it += 2) {
+      block(it, Int<0>{});
+      if (it + 1 < nk) block(it + 1, Int<1>{});
+    }
   }
 
-  store_acc_tile<MB, NB, kEpi>(p, acc, m0 + wm, n0 + wn, l32, g, s_tab);
+  store_acc_tile<MB, NB, kEpi>(p, acc, m0 + wm, n0 + wn, l16, q4, s_tab);
 }
 
 }  // namespace

@@ -3,11 +3,11 @@
 //   dW        dW[:, slice] = X^T . dY_slice  A M-contiguous, B N-contiguous
 //   dX        dX (+)= dY_slice . Ws^T        A K-contiguous, B K-contiguous
 // bf16 operands, fp32 accumulation on the gfx950 matrix cores
-// (v_mfma_f32_32x32x16_bf16), bf16 round-to-nearest-even outputs.
+// (v_mfma_f32_16x16x32_bf16), bf16 round-to-nearest-even outputs.
 //
 // Every kernel in this file feeds each output element the same sequence of
-// MFMA operations: K is walked in ascending blocks of 16, and inside a block
-// logical k = 8*g + e sits in lane group g, element e of both operands.  Tile
+// MFMA operations: K is walked in ascending blocks of 32, and inside a block
+// logical k = 8*q + e sits in lane group q, element e of both operands.  Tile
 // shape therefore never changes a result bit, which is what makes Y and dW of
 // a split operator bit-identical to the unsplit ones.
 #include <cstdlib>
@@ -85,27 +85,24 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
   const int m0 = tm * GBM, n0 = tn * GBN;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-  const int l32 = lane & 31, g = lane >> 5;
+  const int l16 = lane & 15, q = lane >> 4;
 
-  f32x16 acc[2][2];
+  // acc[bm][bn][i] is C[m0 + wm + 16*bm + l16][n0 + wn + 16*bn + 4*q + i]
+  f32x4 acc[4][4];
 #pragma unroll
-  for (int bm = 0; bm < 2; ++bm)
+  for (int bm = 0; bm < 4; ++bm)
 #pragma unroll
-    for (int bn = 0; bn < 2; ++bn) {
+    for (int bn = 0; bn < 4; ++bn) {
 #pragma unroll
-      for (int i = 0; i < 16; ++i) acc[bm][bn][i] = 0.f;
+      for (int i = 0; i < 4; ++i) acc[bm][bn][i] = 0.f;
       if (kAccIn) {
-        const int m = m0 + wm + bm * 32 + l32;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int n = n0 + wn + bn * 32 + 8 * q + 4 * g;
-          if (m < p.M && n < p.N) {
-            const float4 c = *reinterpret_cast<const float4 *>(p.acc_in + static_cast<int64_t>(m) * p.ld_acc + n);
-            acc[bm][bn][4 * q + 0] = c.x;
-            acc[bm][bn][4 * q + 1] = c.y;
-            acc[bm][bn][4 * q + 2] = c.z;
-            acc[bm][bn][4 * q + 3] = c.w;
-          }
+        const int m = m0 + wm + bm * 16 + l16, n = n0 + wn + bn * 16 + 4 * q;
+        if (m < p.M && n < p.N) {
+          const float4 c = *reinterpret_cast<const float4 *>(p.acc_in + static_cast<int64_t>(m) * p.ld_acc + n);
+          acc[bm][bn][0] = c.x;
+          acc[bm][bn][1] = c.y;
+          acc[bm][bn][2] = c.z;
+          acc[bm][bn][3] = c.w;
         }
       }
     }
@@ -118,62 +115,25 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
     generic_store_lds<kAK>(As, va);
     generic_store_lds<kBK>(Bs, vb);
     __syncthreads();
+    // one K step of 32 per block: lane (l16, q) holds k = k0 + 8*q + 0..7 of its row / column
+    bf16x8 a[4], b[4];
 #pragma unroll
-    for (int kk = 0; kk < GBK / 16; ++kk) {
-      bf16x8 a[2], b[2];
+    for (int bm = 0; bm < 4; ++bm) a[bm] = *reinterpret_cast<const bf16x8 *>(&As[wm + bm * 16 + l16][q * 8]);
 #pragma unroll
-      for (int bm = 0; bm < 2; ++bm)
-        a[bm] = *reinterpret_cast<const bf16x8 *>(&As[wm + bm * 32 + l32][kk * 16 + g * 8]);
+    for (int bn = 0; bn < 4; ++bn) b[bn] = *reinterpret_cast<const bf16x8 *>(&Bs[wn + bn * 16 + l16][q * 8]);
 #pragma unroll
-      for (int bn = 0; bn < 2; ++bn)
-        b[bn] = *reinterpret_cast<const bf16x8 *>(&Bs[wn + bn * 32 + l32][kk * 16 + g * 8]);
-      // Operands are passed swapped (B tile as the MFMA's first operand) so that a lane ends
-      // up with 4 consecutive output columns of one output row: acc[i] is
-      // C[m = l32][n = 8*(i/4) + 4*g + i%4] of the 32 x 32 block.
+    for (int bm = 0; bm < 4; ++bm)
 #pragma unroll
-      for (int bm = 0; bm < 2; ++bm)
-#pragma unroll
-        for (int bn = 0; bn < 2; ++bn)
-          acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[bn], a[bm], acc[bm][bn], 0, 0, 0);
-    }
+      for (int bn = 0; bn < 4; ++bn) acc[bm][bn] = mma_16x16x32(a[bm], b[bn], acc[bm][bn]);
   }
 
 #pragma unroll
-  for (int bm = 0; bm < 2; ++bm)
+  for (int bm = 0; bm < 4; ++bm)
 #pragma unroll
-    for (int bn = 0; bn < 2; ++bn) {
-      const int m = m0 + wm + bm * 32 + l32;
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int n = n0 + wn + bn * 32 + 8 * q + 4 * g;
-        if (m >= p.M || n >= p.N) continue;
-        const float c0 = acc[bm][bn][4 * q], c1 = acc[bm][bn][4 * q + 1], c2 = acc[bm][bn][4 * q + 2],
-                    c3 = acc[bm][bn][4 * q + 3];
-        if (kEpi == static_cast<int>(Epilogue::kF32Workspace)) {
-          float4 o = {c0, c1, c2, c3};
-          *reinterpret_cast<float4 *>(static_cast<float *>(p.C) + static_cast<int64_t>(m) * p.ldc + n) = o;
-        } else {
-          uint2 o = {pack_bf16x2(c0, c1), pack_bf16x2(c2, c3)};
-          uint16_t *dst;
-          if (kEpi == static_cast<int>(Epilogue::kBf16RowMajor)) {
-            dst = static_cast<uint16_t *>(p.C) + static_cast<int64_t>(m) * p.ldc + n;
-          } else {
-            int s;
-            int64_t off;
-            const int row = m + static_cast<int>(p.r0);
-            if (p.lay.rows_per_shard > 0) {
-              s = row / p.lay.rows_per_shard;
-              off = static_cast<int64_t>(row - s * p.lay.rows_per_shard) * p.lay.O + p.c0 + n;
-            } else {
-              const int64_t f = static_cast<int64_t>(row) * p.lay.O + p.c0 + n;
-              s = static_cast<int>(f / p.lay.L);
-              off = f - static_cast<int64_t>(s) * p.lay.L;
-            }
-            dst = s_tab[s] + off;
-          }
-          *reinterpret_cast<uint2 *>(dst) = o;
-        }
-      }
+    for (int bn = 0; bn < 4; ++bn) {
+      const int m = m0 + wm + bm * 16 + l16, n = n0 + wn + bn * 16 + 4 * q;
+      if (m >= p.M || n >= p.N) continue;  // N is a multiple of 8 and n of 4: the 4 columns are in or out together
+      store_acc4<kEpi>(p, acc[bm][bn], m, n, s_tab);
     }
 }
 
@@ -231,8 +191,9 @@ struct TileShape {
   int bm, bn;
   double penalty;
 };
-// (8192^3 on MI355X: 256x256 K64 1.15 PFLOP/s; 256x128 and 128x256 with K32, two workgroups per CU, 1.02; 128x128 K64 0.97)
-constexpr TileShape kTiles[4] = {{256, 256, 1.0}, {256, 128, 1.12}, {128, 256, 1.12}, {128, 128, 1.18}};
+// (8192^3 on MI355X, fwd / dW / dX in PFLOP/s: 256x256 K64 1.22 / 1.17 / 1.18; 256x128 K32, two workgroups per CU,
+// 1.01 / 0.91 / 1.09; 128x256 K32, two per CU, 1.12 / 1.02 / 1.06; 128x128 K64, two per CU, 1.01 / 0.96 / 1.02)
+constexpr TileShape kTiles[4] = {{256, 256, 1.0}, {256, 128, 1.20}, {128, 256, 1.11}, {128, 128, 1.20}};
 
 // Cheapest tile for M x N; a column split must fall on a tile boundary.  -1: none divides the problem.
 int best_tile(int M, int N, int n_split, double *cost) {
@@ -261,8 +222,8 @@ hipError_t launch_best(const GemmParams &p, hipStream_t stream) {
     }
     switch (best) {
       case 0: return launch_dma<256, 256, 64, 128, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
-      case 1: return launch_dma<256, 128, 64, 64, 32, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
-      case 2: return launch_dma<128, 256, 64, 64, 32, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
+      case 1: return launch_dma<256, 128, 64, 64, 32, 3, kAK, kBK, kEpi, kAccIn>(p, stream);
+      case 2: return launch_dma<128, 256, 64, 64, 32, 3, kAK, kBK, kEpi, kAccIn>(p, stream);
       case 3: return launch_dma<128, 128, 64, 64, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
     }
   }
