@@ -186,22 +186,30 @@ bool fast_path(int M, int N, int K, int k_split, int n_split) {
          n_split % 128 == 0;
 }
 
-// Tile shapes of the unchecked kernel and their measured cost per unit of tile area relative to 256 x 256.
+// Tile shapes of the unchecked kernel and their measured cost per unit of tile area relative to 256 x 256, for
+// the three operand layouts (forward, dW, dX).
 struct TileShape {
   int bm, bn;
-  double penalty;
+  double penalty[3];
 };
-// (8192^3 on MI355X, fwd / dW / dX in PFLOP/s: 256x256 K64 1.22 / 1.17 / 1.18; 256x128 K32, two workgroups per CU,
-// 1.01 / 0.91 / 1.09; 128x256 K32, two per CU, 1.12 / 1.02 / 1.06; 128x128 K64, two per CU, 1.01 / 0.96 / 1.02)
-constexpr TileShape kTiles[4] = {{256, 256, 1.0}, {256, 128, 1.20}, {128, 256, 1.11}, {128, 128, 1.20}};
+// 8192^3 on MI355X, forward / dW / dX in PFLOP/s: 256x256 1.26 / 1.24 / 1.25; 256x128 (two workgroups per CU)
+// 1.01 / 0.91 / 1.09; 128x256 (two per CU) 1.12 / 1.02 / 1.06; 128x128 (two per CU) 1.03 / 1.05 / 1.03.
+// K block and LDS stages per layout, also measured: forward (transposing reads of B) runs best with K blocks of
+// 64 in two stages, dW and dX on the 256x256 tile and dW on the 128x128 tile with K blocks of 32 in four stages.
+constexpr TileShape kTiles[4] = {{256, 256, {1.0, 1.0, 1.0}},
+                                 {256, 128, {1.25, 1.36, 1.15}},
+                                 {128, 256, {1.125, 1.21, 1.18}},
+                                 {128, 128, {1.22, 1.18, 1.21}}};
+
+constexpr int layout_kind(bool a_kcontig, bool b_kcontig) { return (a_kcontig && !b_kcontig) ? 0 : (!a_kcontig ? 1 : 2); }
 
 // Cheapest tile for M x N; a column split must fall on a tile boundary.  -1: none divides the problem.
-int best_tile(int M, int N, int n_split, double *cost) {
+int best_tile(int M, int N, int n_split, int kind, double *cost) {
   int best = -1;
   double best_cost = 0.0;
   for (int i = 0; i < 4; ++i) {
     if (n_split % kTiles[i].bn) continue;
-    const double c = tile_cost(M, N, kTiles[i].bm, kTiles[i].bn, kTiles[i].penalty);
+    const double c = tile_cost(M, N, kTiles[i].bm, kTiles[i].bn, kTiles[i].penalty[kind]);
     if (c > 0.0 && (best < 0 || c < best_cost)) {
       best = i;
       best_cost = c;
@@ -213,18 +221,23 @@ int best_tile(int M, int N, int n_split, double *cost) {
 
 template <bool kAK, bool kBK, int kEpi, bool kAccIn>
 hipError_t launch_best(const GemmParams &p, hipStream_t stream) {
+  constexpr int kind = layout_kind(kAK, kBK);
   if (fast_path(p.M, p.N, p.K, p.k_split, p.n_split)) {
-    int best = best_tile(p.M, p.N, p.n_split, nullptr);
+    int best = best_tile(p.M, p.N, p.n_split, kind, nullptr);
     const char *t = getenv("OSDP_TILE");  // testing: force tile 0..3 when it divides the problem
     if (t && t[0] >= '0' && t[0] <= '3') {
       const TileShape &f = kTiles[t[0] - '0'];
       if (p.M % f.bm == 0 && p.N % f.bn == 0 && p.n_split % f.bn == 0) best = t[0] - '0';
     }
     switch (best) {
-      case 0: return launch_dma<256, 256, 64, 128, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
+      case 0:
+        if (kind == 0) return launch_dma<256, 256, 64, 128, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
+        return launch_dma<256, 256, 64, 128, 32, 4, kAK, kBK, kEpi, kAccIn>(p, stream);
       case 1: return launch_dma<256, 128, 64, 64, 32, 3, kAK, kBK, kEpi, kAccIn>(p, stream);
       case 2: return launch_dma<128, 256, 64, 64, 32, 3, kAK, kBK, kEpi, kAccIn>(p, stream);
-      case 3: return launch_dma<128, 128, 64, 64, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
+      case 3:
+        if (kind == 1) return launch_dma<128, 128, 64, 64, 32, 4, kAK, kBK, kEpi, kAccIn>(p, stream);
+        return launch_dma<128, 128, 64, 64, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
     }
   }
   if (p.k_split || p.n_split) return hipErrorInvalidValue;  // the bounds-checked kernel takes one B segment only
@@ -241,14 +254,14 @@ bool gemm_takes_two_segments(int64_t M, int64_t N, int64_t k_first, int64_t k_se
 bool gemm_takes_two_column_segments(int64_t M, int64_t n_first, int64_t n_second, int64_t K) {
   return n_first > 0 && n_second > 0 &&
          fast_path(static_cast<int>(M), static_cast<int>(n_first + n_second), static_cast<int>(K), 0, static_cast<int>(n_first)) &&
-         best_tile(static_cast<int>(M), static_cast<int>(n_first + n_second), static_cast<int>(n_first), nullptr) >= 0;
+         best_tile(static_cast<int>(M), static_cast<int>(n_first + n_second), static_cast<int>(n_first), 0, nullptr) >= 0;
 }
 
 double gemm_estimate_us(int64_t M, int64_t N, int64_t K) {
   // one CU sustains about 4e6 flop per microsecond (1 PFLOP/s over 256 CUs) on 256 x 256 tiles
   double cost = 0.0;
   if (fast_path(static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), 0, 0) &&
-      best_tile(static_cast<int>(M), static_cast<int>(N), 0, &cost) >= 0)
+      best_tile(static_cast<int>(M), static_cast<int>(N), 0, 0, &cost) >= 0)
     return cost * 2.0 * static_cast<double>(K) / 4.0e6 + 6.0;
   const double tiles = static_cast<double>((M + GBM - 1) / GBM) * static_cast<double>((N + GBN - 1) / GBN);
   const double rounds = static_cast<double>(static_cast<long>((tiles + kCUs - 1) / kCUs));
