@@ -26,8 +26,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 # together).  Source: profiles/hbm_traffic_config2_config3.md.  Only valid for the default plan of the workload.
 KIB = 1024
 MEASURED_TRAFFIC = {
-    2: {"gemm_fwd": (26844 + 6844) * KIB, "gemm_dw": (96633 + 4096) * KIB, "gemm_dx": (48319 + 33999) * KIB},
-    3: {"gemm_fwd": (402017 + 53015) * KIB, "gemm_dw": (484364 + 13094) * KIB, "gemm_dx": (439043 + 116539) * KIB},
+    2: {"gemm_fwd": (26850 + 7168) * KIB, "gemm_dw": (96638 + 4096) * KIB, "gemm_dx": (49247 + 31723) * KIB},
+    3: {"gemm_fwd": (394270 + 53374) * KIB, "gemm_dw": (653485 + 12809) * KIB, "gemm_dx": (511824 + 117413) * KIB},
 }
 
 
