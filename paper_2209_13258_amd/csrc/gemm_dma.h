@@ -9,7 +9,7 @@
 // stage is a sequence of 1 KB chunks that cannot be padded; bank conflicts are avoided by
 // permuting which 16 bytes of global memory each lane fetches (an XOR swizzle on the source side):
 //   K-contiguous operand  [rows][BK]   : 16-byte chunk c of row r is stored at chunk c ^ f(r),
-//       f(r) = (r >> 1) & 7 for BK = 64, (r >> 2) & 3 for BK = 32, so that the 16 rows a
+//       f(r) = (r >> 1) & 7 for BK = 64, 2 * ((r >> 3) & 1) for BK = 32, so that the 16 lanes a
 //       ds_read_b128 serves per cycle fall into 16 different 16-byte bank groups.
 //   MN-contiguous operand [BK][rows]   : 64-byte granule w of k-row k is stored at granule
 //       w ^ (k & 3) and its 32-byte halves are swapped when bit 3 of k is set, so that the k-rows the
@@ -56,7 +56,11 @@ struct DmaOperand {
   static_assert(kKC || (kRows >= 128 && kRows <= 512), "MN-contiguous tiles are 128..512 wide");
   static_assert(kKC || (kWaves * KPL) % 16 == 0, "a wave's loads must be a multiple of 16 k-rows apart");
 
-  static __device__ __forceinline__ int swz_k(int row) { return CPR == 8 ? ((row >> 1) & 7) : ((row >> 2) & 3); }
+  // A ds_read_b128 is served 16 lanes at a time, and not 16 consecutive ones: measured on the box, lane 0 shares
+  // its cycle with lanes 1-3, 12-15 and 20-27 (within each half of the wave the two groups are the lanes with even
+  // and with odd parity of lane bits 2, 3 and 4).  With lane = 16 * q + row the swizzles below put the 16 reads
+  // of every such group into 16 different 16-byte bank groups.
+  static __device__ __forceinline__ int swz_k(int row) { return CPR == 8 ? ((row >> 1) & 7) : (((row >> 3) & 1) << 1); }
   // MN-contiguous: element offset mn of k-row k is stored at mn ^ swz_mn(k): the 64-byte granule index is
   // XORed with k & 3 and the 32-byte half inside the granule with bit 3 of k, so that the 8 k-rows the two
   // lane groups of one transposing-read phase touch (k, k+1, k+2, k+3 and the same + 8) fall into 8 different

@@ -192,14 +192,14 @@ struct TileShape {
   int bm, bn;
   double penalty[3];
 };
-// 8192^3 on MI355X, forward / dW / dX in PFLOP/s: 256x256 1.26 / 1.24 / 1.25; 256x128 (two workgroups per CU)
-// 1.01 / 0.91 / 1.09; 128x256 (two per CU) 1.12 / 1.02 / 1.06; 128x128 (two per CU) 1.03 / 1.05 / 1.03.
+// 8192^3 on MI355X, forward / dW / dX in PFLOP/s: 256x256 1.23 / 1.18-1.24 / 1.26; 256x128 (two workgroups per CU)
+// 1.04 / 0.90 / 1.09; 128x256 (two per CU) 1.19 / 1.02 / 1.06; 128x128 (two per CU) 1.03 / 1.05 / 1.03.
 // K block and LDS stages per layout, also measured: forward (transposing reads of B) runs best with K blocks of
 // 64 in two stages, dW and dX on the 256x256 tile and dW on the 128x128 tile with K blocks of 32 in four stages.
 constexpr TileShape kTiles[4] = {{256, 256, {1.0, 1.0, 1.0}},
-                                 {256, 128, {1.25, 1.36, 1.15}},
-                                 {128, 256, {1.125, 1.21, 1.18}},
-                                 {128, 128, {1.22, 1.18, 1.21}}};
+                                 {256, 128, {1.17, 1.32, 1.16}},
+                                 {128, 256, {1.03, 1.16, 1.19}},
+                                 {128, 128, {1.19, 1.13, 1.22}}};
 
 constexpr int layout_kind(bool a_kcontig, bool b_kcontig) { return (a_kcontig && !b_kcontig) ? 0 : (!a_kcontig ? 1 : 2); }
 
