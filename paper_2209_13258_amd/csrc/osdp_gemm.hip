@@ -171,13 +171,17 @@ hipError_t launch_dma(const GemmParams &p, hipStream_t stream) {
 
 constexpr int kCUs = 256;
 
-// Estimated cost of covering M x N with BM x BN tiles on 256 CUs: rounds of tiles times the tile's area,
-// with a penalty for the lower MFMA efficiency of smaller tiles.  0 when the tile does not divide the problem.
+// Estimated cost of covering M x N with BM x BN tiles on 256 CUs: tiles per CU times the tile's area, with a
+// penalty for the lower MFMA efficiency of smaller tiles.  Tiles that run two to a CU were measured in pairs; a
+// CU's odd last tile runs alone and slower, which is priced as one and a half tiles.  0 when the tile does not
+// divide the problem.
 double tile_cost(int M, int N, int BM, int BN, double penalty) {
   if (M % BM || N % BN) return 0.0;
   const long tiles = static_cast<long>(M / BM) * (N / BN);
-  const long rounds = (tiles + kCUs - 1) / kCUs;
-  return static_cast<double>(rounds) * BM * BN * penalty;
+  const long per_cu = (tiles + kCUs - 1) / kCUs;
+  const bool two_per_cu = BM * BN < 256 * 256;
+  const double units = (two_per_cu && per_cu % 2) ? static_cast<double>(per_cu) + 0.5 : static_cast<double>(per_cu);
+  return units * BM * BN * penalty;
 }
 
 bool fast_path(int M, int N, int K, int k_split, int n_split) {
