@@ -672,3 +672,38 @@ def test_config2_one_of_four_slices_zdp(H, oracle, rows):
                                                          osdp.Plan([k], zdp_mask=[mask], split_dim_per_op=[dim]))
         law = oracle.peak_staging_bytes_rows if rows else oracle.peak_staging_bytes
         assert peak == law(o.I, o.O, k, 1, 2)   # one gathered slice, however many slots the mode offers
+
+
+# ------------------------------------------------ every tile shape of the unchecked kernel
+@pytest.mark.parametrize("T,I,O,N", [(512, 512, 768, 4), (256, 1024, 256, 8)])
+def test_every_tile_shape_gives_the_bits_of_the_checked_kernel(H, oracle, T, I, O, N, monkeypatch):
+    """The host picks tile shapes by cost, so a test shape may never meet some of them: each of the four
+    (with its own K block, LDS stage count and launch bounds per operand layout) is forced in turn, for
+    the unsplit operator and for splits in both dimensions, and must reproduce the bounds-checked kernel
+    bit for bit (and, through it, the oracle)."""
+    import paper_2209_13258_amd as osdp
+    d = wl.small_case(71, T, I, O, N)
+    monkeypatch.setenv("OSDP_GEMM", "generic")
+    ref_op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+    ref_op.fwd(1)
+    ref_op.bwd(1)
+    ref = ref_op.results()
+    want = oracle.linear(d["X"], d["W_shards"], O, dY=d["dY"])
+    for name in ("Y", "dX", "dW"):
+        H.assert_close(name, ref[name], want[name])
+    monkeypatch.delenv("OSDP_GEMM")
+    sc, sp = H.streams()
+    for tile in "0123":
+        monkeypatch.setenv("OSDP_TILE", tile)
+        for k, dim in ((1, 0), (2, 0), (2, 1)):
+            _announce("tile", tile, T, I, O, N, "k", k, "dim", dim)
+            plan = osdp.Plan([k], staging=osdp.OSDP_STAGING_DOUBLE, split_dim_per_op=[dim])
+            op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+            torch.cuda.synchronize()
+            with torch.cuda.stream(sc):
+                op.fwd(k, plan=plan, streams=(sc, sp))
+                op.bwd(k, plan=plan, streams=(sc, sp))
+            sc.synchronize()
+            got = op.results()
+            for name in ("Y", "dX", "dW"):
+                assert np.array_equal(got[name], ref[name]), f"{name} differs (tile {tile}, k {k}, dim {dim})"
