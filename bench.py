@@ -26,8 +26,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 # together).  Source: profiles/hbm_traffic_config2_config3.md.  Only valid for the default plan of the workload.
 KIB = 1024
 MEASURED_TRAFFIC = {
-    2: {"gemm_fwd": (26850 + 7168) * KIB, "gemm_dw": (96638 + 4096) * KIB, "gemm_dx": (49247 + 31723) * KIB},
-    3: {"gemm_fwd": (394270 + 53374) * KIB, "gemm_dw": (653485 + 12809) * KIB, "gemm_dx": (511824 + 117413) * KIB},
+    2: {"gemm_fwd": (26849 + 6827) * KIB, "gemm_dw": (96624 + 4096) * KIB, "gemm_dx": (48918 + 31378) * KIB},
+    3: {"gemm_fwd": (391494 + 53376) * KIB, "gemm_dw": (645764 + 12806) * KIB, "gemm_dx": (416315 + 116430) * KIB},
 }
 
 
