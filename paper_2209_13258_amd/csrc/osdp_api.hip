@@ -233,7 +233,11 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
   // one launch over sub-slices [a, b): concatenating (T x span x D) or accumulating (T x D x span)
   auto concat_us = [&](int64_t a, int64_t b) { return gemm_estimate_us(T, span(a, b), D); };
   auto accum_us = [&](int64_t a, int64_t b) { return gemm_estimate_us(T, D, span(a, b)); };
+  // Two neighbouring gathered sub-slices can always share a launch: they are gathered by one copy into the two
+  // slots taken as one buffer and read as one slice.  When one of them is a DP slice (read in place) the launch
+  // needs a kernel that takes B in two segments.
   auto can_pair = [&](bool concat, int64_t j) {
+    if (!r->dp[j] && !r->dp[j + 1]) return true;
     return concat ? gemm_takes_two_column_segments(T, width(j), width(j + 1), D)
                   : gemm_takes_two_segments(T, D, width(j), width(j + 1));
   };
@@ -481,7 +485,7 @@ GemmProblem weight_gemm(const Resolved &r, bool is_fwd, int j0, int j1, WeightVi
                         int64_t ld_act, void *out, int64_t ld_out, float *acc, size_t idx, size_t count) {
   const Slice &s0 = r.sub[j0];
   const int64_t w0 = s0.c1 - s0.c0, span = r.sub[j1 - 1].c1 - s0.c0;
-  const bool two = j1 - j0 == 2;
+  const bool two = j1 - j0 == 2 && B1.p != nullptr;  // B1.p == nullptr: both sub-slices lie in B0 as one slice
   const bool concat = is_fwd != r.rows;
   GemmProblem g{};
   g.M = static_cast<int32_t>(r.T);
@@ -521,6 +525,13 @@ int64_t replica_offset(const Resolved &r, const Replicas &rep, int j) {
 WeightView weights_of(const Resolved &r, const Replicas &rep, int j, const void *slot) {
   if (r.dp[j]) return {static_cast<const uint16_t *>(rep.w[r.owner[j]]) + replica_offset(r, rep, j), rep.ld};
   return {slot, r.rows ? r.O : r.sub[j].c1 - r.sub[j].c0};
+}
+
+// Two neighbouring gathered sub-slices j, j+1 staged as one slice across both slots.
+bool staged_jointly(const Resolved &r, int j0, int j1) { return j1 - j0 == 2 && !r.dp[j0] && !r.dp[j0 + 1]; }
+Slice joint_range(const Resolved &r, int j0) { return {r.sub[j0].c0, r.sub[j0 + 1].c1}; }
+WeightView joint_view(const Resolved &r, int j0, const void *slots) {
+  return {slots, r.rows ? r.O : r.sub[j0 + 1].c1 - r.sub[j0].c0};
 }
 
 GemmProblem dw_gemm(const Resolved &r, int j0, int j1, const void *X, int64_t ldx, const void *dY, int64_t lddy,
@@ -691,18 +702,23 @@ static osdp_status forward(const osdp_shape *shape, const osdp_plan *plan, int32
     void *slot_of[2] = {nullptr, nullptr};
     int slot_id[2] = {0, 0};
     bool gathered = false;
+    const bool joint = staged_jointly(r, j0, j1);
     for (int j = j0; j < j1; ++j) {
       const int s = (j1 - j0 == 2) ? j - j0 : j % r.slots;
       slot_id[j - j0] = s;
       slot_of[j - j0] = ws + static_cast<size_t>(s) * r.slot_bytes;
       if (r.dp[j]) continue;  // a DP slice is read where it lies
       if (overlap && slot_free[s]) OSDP_HIP(hipStreamWaitEvent(sp, slot_free[s], 0));  // slot released by its last reader
-      OSDP_HIP(do_gather(r, tab, r.sub[j], slot_of[j - j0], sg));
+      if (!joint) OSDP_HIP(do_gather(r, tab, r.sub[j], slot_of[j - j0], sg));
       gathered = true;
     }
+    if (joint) OSDP_HIP(do_gather(r, tab, joint_range(r, j0), ws, sg));  // one copy for both, across the two slots
     if (overlap && gathered) OSDP_HIP(edge(sp, sc));
-    const GemmProblem g = weight_gemm(r, /*is_fwd=*/true, j0, j1, weights_of(r, rep, j0, slot_of[0]),
-                                      weights_of(r, rep, j1 - 1, slot_of[1]), X, ldx, Y, ldy, acc, li, r.fwd.size());
+    const GemmProblem g =
+        joint ? weight_gemm(r, /*is_fwd=*/true, j0, j1, joint_view(r, j0, ws), WeightView{nullptr, 0}, X, ldx, Y, ldy, acc,
+                            li, r.fwd.size())
+              : weight_gemm(r, /*is_fwd=*/true, j0, j1, weights_of(r, rep, j0, slot_of[0]),
+                            weights_of(r, rep, j1 - 1, slot_of[1]), X, ldx, Y, ldy, acc, li, r.fwd.size());
     OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_FWD, g, sc));
     if (overlap && gathered && j1 < n) {
       hipEvent_t ev;
@@ -761,7 +777,11 @@ static osdp_status backward(const osdp_shape *shape, const osdp_plan *plan, int3
     const int g0 = static_cast<int>(grp.c0), g1 = static_cast<int>(grp.c1);
     // gather every slice of the group into its slot once the previous group has released the slots
     if (overlap && released) OSDP_HIP(hipStreamWaitEvent(sp, released, 0));
-    for (int j = g0; j < g1; ++j)
+    // (a pair of gathered sub-slices that one dX launch will read: one copy, across the two slots)
+    const bool joint = staged_jointly(r, g0, g1) && next_pass < r.pass.size() && r.pass[next_pass].c0 == g0 &&
+                       r.pass[next_pass].c1 == g1;
+    if (joint) OSDP_HIP(do_gather(r, tab, joint_range(r, g0), ws, sg));
+    for (int j = g0; j < g1 && !joint; ++j)
       if (!r.dp[j]) OSDP_HIP(do_gather(r, tab, r.sub[j], ws + static_cast<size_t>(j - g0) * r.slot_bytes, sg));
     hipEvent_t gathered = nullptr;
     if (overlap) {
@@ -777,10 +797,13 @@ static osdp_status backward(const osdp_shape *shape, const osdp_plan *plan, int3
     // the dX launches of the group (column slices: the fp32 partial sum is carried in the workspace between them)
     for (; next_pass < r.pass.size() && r.pass[next_pass].c1 <= g1; ++next_pass) {
       const int j0 = static_cast<int>(r.pass[next_pass].c0), j1 = static_cast<int>(r.pass[next_pass].c1);
-      const GemmProblem gx = weight_gemm(r, /*is_fwd=*/false, j0, j1,
-                                         weights_of(r, rep, j0, ws + static_cast<size_t>(j0 - g0) * r.slot_bytes),
-                                         weights_of(r, rep, j1 - 1, ws + static_cast<size_t>(j1 - 1 - g0) * r.slot_bytes),
-                                         dY, lddy, dX, lddx, acc, next_pass, r.pass.size());
+      const GemmProblem gx =
+          joint ? weight_gemm(r, /*is_fwd=*/false, j0, j1, joint_view(r, j0, ws), WeightView{nullptr, 0}, dY, lddy, dX, lddx,
+                              acc, next_pass, r.pass.size())
+                : weight_gemm(r, /*is_fwd=*/false, j0, j1,
+                              weights_of(r, rep, j0, ws + static_cast<size_t>(j0 - g0) * r.slot_bytes),
+                              weights_of(r, rep, j1 - 1, ws + static_cast<size_t>(j1 - 1 - g0) * r.slot_bytes), dY, lddy, dX,
+                              lddx, acc, next_pass, r.pass.size());
       OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DX, gx, sc));
     }
     if (overlap && g1 < n) {

@@ -105,11 +105,9 @@ def test_workspace_and_peak_staging_follow_the_law(oracle, T, I, O, N, k):
     w = O // keff
 
     def passes(n_sub, width, slots):
-        """dX passes: sub-slices are staged in groups of `slots`; a full group of two runs as one pass
-        when both widths are multiples of 64 and T, I are multiples of 128 (the unchecked kernel's tiles)."""
-        groups = [min(slots, n_sub - g) for g in range(0, n_sub, slots)]
-        fusable = width % 64 == 0 and T % 128 == 0 and I % 128 == 0
-        return sum(1 if (g == 2 and fusable) else g for g in groups)
+        """dX passes: sub-slices are staged in groups of `slots`, and a group of two gathered sub-slices is
+        staged as one slice across both slots and read by one pass."""
+        return len(range(0, n_sub, slots))
 
     for is_bwd in (False, True):
         tot1, peak1 = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, is_bwd, single)
