@@ -693,7 +693,11 @@ static osdp_status forward(const osdp_shape *shape, const osdp_plan *plan, int32
   char *ws = static_cast<char *>(workspace);
   float *acc = reinterpret_cast<float *>(ws + r.slot_bytes * r.slots);  // row slices: Y's fp32 partial sum
   const int n = static_cast<int>(r.sub.size());
-  const bool overlap = two_streams && r.slots == 2 && n > 1;
+  // A launch over two staged sub-slices holds both slots, so the next gather has to wait for it whatever stream it
+  // is on: with such launches there is nothing to overlap, and everything goes on the compute stream, event-free.
+  bool pairs = false;
+  for (const Slice &l : r.fwd) pairs = pairs || l.c1 - l.c0 == 2;
+  const bool overlap = two_streams && r.slots == 2 && n > 1 && !pairs;
   hipStream_t sg = overlap ? sp : sc;
   hipEvent_t slot_free[2] = {nullptr, nullptr};  // recorded on the compute stream after the last GEMM that read the slot
   if (overlap) OSDP_HIP(edge(sc, sp));  // the staging area may still be in use by earlier compute-stream work
@@ -768,7 +772,12 @@ static osdp_status backward(const osdp_shape *shape, const osdp_plan *plan, int3
   char *ws = static_cast<char *>(workspace);
   float *acc = reinterpret_cast<float *>(ws + r.slot_bytes * r.slots);  // column slices: dX's fp32 partial sum
   const int n = static_cast<int>(r.sub.size());
-  const bool overlap = two_streams && r.slots == 2 && n > 1;
+  // The gathers of a group run on the copy stream behind dW.  Each group then costs four event operations, which
+  // is more than a small gather takes (measured: with 4 MB groups one stream is 5-12 % faster, with 25 MB groups
+  // two streams are 1 % faster), so small groups stay on the compute stream.
+  constexpr double kWorthOverlappingUs = 14.0;
+  const bool overlap = two_streams && r.slots == 2 && n > 1 &&
+                       gather_estimate_us(static_cast<int64_t>(r.slot_bytes)) >= kWorthOverlappingUs;  // two slots of slot_bytes / 2 elements
   hipStream_t sg = overlap ? sp : sc;
   hipEvent_t released = nullptr;  // recorded on the compute stream when a group's last GEMM has been enqueued
   if (overlap) OSDP_HIP(edge(sc, sp));
