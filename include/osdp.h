@@ -163,7 +163,10 @@ OSDP_API osdp_status osdp_split_linear_workspace_bytes(const osdp_shape *shape, 
  *   w_shards : host array of N device pointers
  *   workspace: device, 256-byte aligned, >= osdp_split_linear_workspace_bytes(.., 0, ..)
  *   stream_compute : hipStream_t the GEMMs run on
- *   stream_copy    : hipStream_t the gathers run on; NULL or == stream_compute = no overlap
+ *   stream_copy    : hipStream_t the gathers may run on; NULL or == stream_compute = no overlap.
+ *                    The library keeps a call on stream_compute alone when the copy stream could
+ *                    not hide anything (launches that hold both slots; gathers too small to be
+ *                    worth the cross-stream events).
  * With row slices (plan->split_dim_per_op): for j = 0..k-1 gather row slice j, then
  * Y += X[:, r0_j:r1_j] . Wr_j, the sum carried in fp32 (through the workspace between launches) in ascending
  * j and rounded to bf16 once.
