@@ -78,14 +78,14 @@ hipError_t launch_gather(const ShardTable &shards, const ShardLayout &layout, in
   const uint64_t vecs_per_row = static_cast<uint64_t>(w) / 8;
   const uint64_t total = static_cast<uint64_t>(rows) * vecs_per_row;
   if (total == 0) return hipSuccess;
-  // measured on MI355X: 8 vectors per thread are about twice as fast on slices up to ~32 MiB (few, long-lived
-  // blocks), 4 vectors per thread with a wide grid reach 5.2 TB/s (read + write) on larger ones
+  // measured on MI355X: one vector per thread and grid-stride step is fastest up to 128 MiB slices (2 MiB in 6 us,
+  // 12.5 MiB in 6.4 us, 50 and 128 MiB at 6.3 TB/s read + write, 80 % of the HBM peak); beyond that 4 vectors per
+  // thread with all loads ahead of the stores do slightly better (512 MiB: 5.3 against 5.1 TB/s)
   const unsigned max_blocks = 8192;
-  const int unroll = (total * 16 <= (32ull << 20)) ? 8 : 4;
   const bool rb = layout.rows_per_shard > 0;
-  if (unroll == 8) {
-    if (rb) launch_one<true, 8>(shards, layout, r0, c0, vecs_per_row, total, max_blocks, staging, stream);
-    else launch_one<false, 8>(shards, layout, r0, c0, vecs_per_row, total, max_blocks, staging, stream);
+  if (total * 16 <= (256ull << 20)) {
+    if (rb) launch_one<true, 1>(shards, layout, r0, c0, vecs_per_row, total, max_blocks, staging, stream);
+    else launch_one<false, 1>(shards, layout, r0, c0, vecs_per_row, total, max_blocks, staging, stream);
   } else {
     if (rb) launch_one<true, 4>(shards, layout, r0, c0, vecs_per_row, total, max_blocks, staging, stream);
     else launch_one<false, 4>(shards, layout, r0, c0, vecs_per_row, total, max_blocks, staging, stream);
