@@ -21,13 +21,14 @@ import time
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (vendor figure: 256 CUs x 2.4 GHz x 4096 flop/clk/CU)
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 
-# HBM-side traffic per launch (bytes, FETCH_SIZE + WRITE_SIZE of two rocprofv3 --pmc runs of this file, each scaled
-# by what the same counter read for the gather kernel, a plain copy of known size; all tile shapes of a kernel kind
-# together).  Source: profiles/hbm_traffic_config2_config3.md.  Only valid for the default plan of the workload.
+# L2-miss traffic per launch (bytes, FETCH_SIZE + WRITE_SIZE of two rocprofv3 --pmc runs of this file with
+# --traffic-calibration, each counter scaled by what it read for the three 1 GiB calibration copies: FETCH_SIZE
+# x 2.000, WRITE_SIZE x 1.000; all tile shapes of a kernel kind together).  Source:
+# profiles/hbm_traffic_config2_config3.md.  Only valid for the default plan of the workload.
 KIB = 1024
 MEASURED_TRAFFIC = {
-    2: {"gemm_fwd": (26849 + 6827) * KIB, "gemm_dw": (96624 + 4096) * KIB, "gemm_dx": (48918 + 31378) * KIB},
-    3: {"gemm_fwd": (391494 + 53376) * KIB, "gemm_dw": (645764 + 12806) * KIB, "gemm_dx": (416315 + 116430) * KIB},
+    2: {"gemm_fwd": (54732 + 13653) * KIB, "gemm_dw": (196964 + 8192) * KIB, "gemm_dx": (99632 + 63000) * KIB},
+    3: {"gemm_fwd": (790648 + 106778) * KIB, "gemm_dw": (1305492 + 25614) * KIB, "gemm_dx": (835047 + 232848) * KIB},
 }
 
 
@@ -46,6 +47,9 @@ def parse():
                          "read from a resident replica (default: every slice ZDP)")
     ap.add_argument("--no-sweep", action="store_true", help="skip the k sweep and the extra workload")
     ap.add_argument("--no-auto", action="store_true", help="skip the automatic slice-granularity table")
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="first run three plain copies of 1 GiB through the gather kernel (one shard, one slice, source "
+                         "far larger than every cache): the known traffic that HBM counters of a profiled run are scaled by")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--serial", action="store_true", help="one stream: no gather/GEMM overlap")
     return ap.parse_args()
@@ -282,6 +286,15 @@ def main():
 
     staging = {"auto": osdp.OSDP_STAGING_AUTO, "single": osdp.OSDP_STAGING_SINGLE,
                "double": osdp.OSDP_STAGING_DOUBLE, "half": osdp.OSDP_STAGING_HALF}[a.staging]
+    if a.traffic_calibration:
+        I, O = 16384, 32768   # 1 GiB of bf16
+        src = torch.zeros(I * O, dtype=torch.bfloat16, device="cuda")
+        dst = torch.empty(I * O, dtype=torch.bfloat16, device="cuda")
+        for _ in range(3):
+            osdp.osdp_split_linear_gather_slice(I, O, 1, 0, [src], dst)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     w = wl.workload(a.config, a.k)
     rows = a.split_dim == "in"
     st = Stack(w, staging, torch, osdp, rows=rows, zdp_slices=a.zdp_slices)
