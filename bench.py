@@ -40,8 +40,9 @@ def parse():
     ap.add_argument("--config", type=int, default=2, help="workload: index into BASELINE.json configs (1-based)")
     ap.add_argument("--k", type=int, default=None, help="slice granularity (default: the workload's own)")
     ap.add_argument("--staging", choices=["auto", "single", "double", "half"], default="auto")
-    ap.add_argument("--split-dim", choices=["out", "in"], default="out",
-                    help="cut W along its output features (columns) or its input features (rows, the reduction dimension)")
+    ap.add_argument("--split-dim", choices=["out", "in", "longer"], default="out",
+                    help="cut W along its output features (columns), its input features (rows, the reduction "
+                         "dimension), or per operator along the longer of the two")
     ap.add_argument("--zdp-slices", type=int, default=None,
                     help="keep only the first Z slices of every operator sharded (ZDP); the others are DP slices "
                          "read from a resident replica (default: every slice ZDP)")
@@ -58,7 +59,8 @@ def parse():
 class Stack:
     """All operators of a workload resident on the GPU, with one shared workspace."""
 
-    def __init__(self, w, staging, torch, osdp, seed=0, rows=False, plan=None, zdp_slices=None, zdp_masks=None):
+    def __init__(self, w, staging, torch, osdp, seed=0, rows=False, plan=None, zdp_slices=None, zdp_masks=None,
+                 longer=False):
         self.w, self.torch, self.osdp = w, torch, osdp
         g = torch.Generator(device="cuda")
         g.manual_seed(220913258 + seed)
@@ -78,6 +80,8 @@ class Stack:
                 )
                 self.ops.append(d)
         dims = [osdp.OSDP_SPLIT_IN_FEATURES if rows else osdp.OSDP_SPLIT_OUT_FEATURES] * len(w.ops)
+        if longer:
+            dims = [osdp.OSDP_SPLIT_LONGER] * len(w.ops)
         self.plan = plan or osdp.Plan([op.k for op in w.ops], staging=staging, split_dim_per_op=dims)
         # zdp_slices = z: the first z slices of every operator stay sharded (ZDP), the others are DP slices read from
         # a resident full-layout replica, their gradients written to a full-layout array
@@ -297,7 +301,8 @@ def main():
         torch.cuda.empty_cache()
     w = wl.workload(a.config, a.k)
     rows = a.split_dim == "in"
-    st = Stack(w, staging, torch, osdp, rows=rows, zdp_slices=a.zdp_slices)
+    longer = a.split_dim == "longer"
+    st = Stack(w, staging, torch, osdp, rows=rows, zdp_slices=a.zdp_slices, longer=longer)
     flops = wl.flops(w)
 
     ms, _ = st.run(a.steps, a.warmup, serial=a.serial)
@@ -321,7 +326,7 @@ def main():
         "config": {"workload": w.name, "baseline_config": a.config, "T": w.T, "N_shards": w.N, "layers": w.layers,
                    "ops": {op.name: {"I": op.I, "O": op.O, "k": op.k} for op in w.ops},
                    "staging": a.staging, "overlap": not a.serial,
-                   "split_dim": "in_features" if rows else "out_features",
+                   "split_dim": "longer" if longer else "in_features" if rows else "out_features",
                    "zdp_slices": "all" if a.zdp_slices is None else a.zdp_slices},
         "frac_bf16_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3),
@@ -375,6 +380,11 @@ def main():
                 mso = min(st.run(max(5, a.steps // 2), max(2, a.warmup // 2), serial=a.serial)[0] for _ in range(2))
                 sweep[str(k)]["tflops_other_split_dim"] = round(wl.flops(wk) / (mso * 1e-3) / 1e12, 2)
                 sweep[str(k)]["peak_staging_mb_other_split_dim"] = round(st.peak_staging / 2 ** 20, 3)
+                del st
+                torch.cuda.empty_cache()
+                st = Stack(wk, staging, torch, osdp, longer=True)   # every operator cut along its longer dimension
+                msl = min(st.run(max(5, a.steps // 2), max(2, a.warmup // 2), serial=a.serial)[0] for _ in range(2))
+                sweep[str(k)]["tflops_longer_split_dim"] = round(wl.flops(wk) / (msl * 1e-3) / 1e12, 2)
         out["k_sweep"] = sweep
         if a.config == 2:  # the h = 2560 layer under its plan vector, where the 70 % target applies
             del st

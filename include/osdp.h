@@ -101,8 +101,11 @@ typedef enum {
 /* Which dimension of W the k slices cut. */
 typedef enum {
   OSDP_SPLIT_OUT_FEATURES = 0, /* columns of W: Y and dW concatenate, dX is summed                   */
-  OSDP_SPLIT_IN_FEATURES = 1   /* rows of W, the forward product's reduction dimension (Section 3.3
+  OSDP_SPLIT_IN_FEATURES = 1,  /* rows of W, the forward product's reduction dimension (Section 3.3
                                   as printed): Y is summed, dW and dX concatenate                     */
+  OSDP_SPLIT_LONGER = 2        /* whichever of the two is longer (columns when I == O): the fp32 partial
+                                  sum is T x the other dimension, and measured on MI355X the longer cut
+                                  is the faster one at every granularity                              */
 } osdp_split_dim;
 
 /* The per-operator execution plan (the paper's plan vector p over the n

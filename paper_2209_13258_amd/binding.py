@@ -26,6 +26,7 @@ OSDP_STAGING_HALF = 3
 
 OSDP_SPLIT_OUT_FEATURES = 0
 OSDP_SPLIT_IN_FEATURES = 1
+OSDP_SPLIT_LONGER = 2
 
 OSDP_KERNEL_GATHER = 0
 OSDP_KERNEL_GEMM_FWD = 1

@@ -135,9 +135,9 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
     if (plan->zdp_mask) mask = plan->zdp_mask + op_index;
     if (plan->split_dim_per_op) {
       const uint8_t d = plan->split_dim_per_op[op_index];
-      if (d != OSDP_SPLIT_OUT_FEATURES && d != OSDP_SPLIT_IN_FEATURES)
+      if (d != OSDP_SPLIT_OUT_FEATURES && d != OSDP_SPLIT_IN_FEATURES && d != OSDP_SPLIT_LONGER)
         return fail(OSDP_ERR_INVALID_ARG, "unknown split dimension %d", static_cast<int>(d));
-      rows = d == OSDP_SPLIT_IN_FEATURES;
+      rows = d == OSDP_SPLIT_IN_FEATURES || (d == OSDP_SPLIT_LONGER && shape->I > shape->O);
     }
   }
   if (k == 0) k = 1;

@@ -413,7 +413,7 @@ def test_mixed_split_dimensions_share_one_workspace(H, oracle):
     """A plan vector that cuts some operators by columns and some by rows, run as a stack on two streams."""
     import paper_2209_13258_amd as osdp
     shapes = [(256, 128, 384, 4), (256, 384, 128, 4), (256, 128, 512, 4), (256, 512, 128, 4)]
-    plan = osdp.Plan([3, 2, 4, 4], split_dim_per_op=[0, 1, 1, 0])
+    plan = osdp.Plan([3, 2, 4, 4], split_dim_per_op=[0, osdp.OSDP_SPLIT_LONGER, 1, osdp.OSDP_SPLIT_LONGER])  # cols, rows (I > O), rows, rows
     ops, data = [], []
     for n, (T, I, O, N) in enumerate(shapes):
         d = wl.small_case(40 + n, T, I, O, N)

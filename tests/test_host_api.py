@@ -81,6 +81,18 @@ def test_row_split_workspace_and_peak_staging_follow_the_law(oracle, T, I, O, N,
         osdp.osdp_split_linear_workspace_bytes(T, I, O, N, 1, True, osdp.Plan([1]))
 
 
+def test_longer_dimension_split_resolves_by_shape():
+    for T, I, O, N, k in [(256, 512, 2048, 4, 4), (256, 2048, 512, 4, 4), (256, 512, 512, 4, 4)]:
+        longer = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, 0, False, osdp.Plan(
+            [k], staging=osdp.OSDP_STAGING_SINGLE, split_dim_per_op=[osdp.OSDP_SPLIT_LONGER]))
+        want_dim = osdp.OSDP_SPLIT_IN_FEATURES if I > O else osdp.OSDP_SPLIT_OUT_FEATURES
+        same = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, 0, False, osdp.Plan(
+            [k], staging=osdp.OSDP_STAGING_SINGLE, split_dim_per_op=[want_dim]))
+        assert longer == same
+        # the forward keeps an fp32 partial sum only when the rows are cut
+        assert (longer[0] > longer[1]) == (I > O)
+
+
 def test_row_split_rejects_what_the_kernels_cannot_take():
     rows = [osdp.OSDP_SPLIT_IN_FEATURES]
     for args, status in [((128, 8, 1024, 2, 16), -1),      # k > I
