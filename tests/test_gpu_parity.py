@@ -707,3 +707,46 @@ def test_every_tile_shape_gives_the_bits_of_the_checked_kernel(H, oracle, T, I, 
             got = op.results()
             for name in ("Y", "dX", "dW"):
                 assert np.array_equal(got[name], ref[name]), f"{name} differs (tile {tile}, k {k}, dim {dim})"
+
+
+# ------------------------------------------------ leading dimensions and many shards
+@pytest.mark.parametrize("T,I,O,N,k,dim", [(256, 256, 512, 4, 2, 0),     # unchecked kernels
+                                            (77, 136, 200, 1, 1, 0),     # checked kernel
+                                            (300, 264, 528, 4, 3, 1),    # row slices, ragged
+                                            (128, 64, 192, 64, 3, 0)])   # 64 shards of 192 elements: rows span shards
+def test_padded_leading_dimensions_and_many_shards(H, oracle, T, I, O, N, k, dim):
+    """X, dY, Y and dX live inside wider arrays (ld > row length); the columns beyond the row length hold NaN and
+    must neither be read (inputs) nor written (outputs)."""
+    import paper_2209_13258_amd as osdp
+    _announce("leading dimensions", T, I, O, N, k, dim)
+    d = wl.small_case(81, T, I, O, N)
+    pad_i, pad_o = 24, 40
+    nan = float("nan")
+
+    def widened(bits, pad):
+        t = torch.full((bits.shape[0], bits.shape[1] + pad), nan, dtype=torch.bfloat16, device="cuda")
+        t[:, : bits.shape[1]] = H.to_dev(bits)
+        return t
+
+    Xw, dYw = widened(d["X"], pad_i), widened(d["dY"], pad_o)
+    Yw = torch.full((T, O + pad_o), nan, dtype=torch.bfloat16, device="cuda")
+    dXw = torch.full((T, I + pad_i), nan, dtype=torch.bfloat16, device="cuda")
+    X, dY, Y, dX = Xw[:, :I], dYw[:, :O], Yw[:, :O], dXw[:, :I]
+    assert X.stride(0) == I + pad_i and Y.stride(0) == O + pad_o
+    W = [H.to_dev(s) for s in d["W_shards"]]
+    dW = [torch.full((d["W_shards"][0].size,), nan, dtype=torch.bfloat16, device="cuda") for _ in range(N)]
+    plan = osdp.Plan([k], split_dim_per_op=[dim])
+    need = max(osdp.osdp_split_linear_workspace_bytes(T, I, O, N, 0, b, plan)[0] for b in (False, True))
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda")
+    sc, sp = H.streams()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(sc):
+        osdp.osdp_split_linear_fwd(X, W, Y, 0, ws, plan=plan, stream_compute=sc, stream_copy=sp)
+        osdp.osdp_split_linear_bwd(X, dY, W, dX, dW, 0, ws, plan=plan, stream_compute=sc, stream_copy=sp)
+    sc.synchronize()
+    ref = oracle.linear(d["X"], d["W_shards"], O, dY=d["dY"])
+    H.assert_close("Y", H.to_bits(Yw)[:, :O], ref["Y"])
+    H.assert_close("dX", H.to_bits(dXw)[:, :I], ref["dX"])
+    got_dW = np.concatenate([H.to_bits(s) for s in dW])[: I * O].reshape(I, O)
+    H.assert_close("dW", got_dW, ref["dW"])
+    assert (H.to_bits(Yw)[:, O:] == POISON).all() and (H.to_bits(dXw)[:, I:] == POISON).all()
