@@ -362,7 +362,7 @@ typedef struct {
   int64_t launches; /* kernel launches seen since osdp_profile_begin          */
   double ms;        /* sum of their durations, HIP events on the launch stream */
   double flops;     /* 2*M*N*K summed over GEMM launches                       */
-  double bytes;     /* algorithmic bytes summed over launches (see DESIGN)     */
+  double bytes;     /* algorithmic bytes summed over launches: operands read once, output written once */
 } osdp_kernel_stats;
 
 /* Between begin and end every kernel launch of the calling thread is bracketed
