@@ -142,6 +142,22 @@ class Stack:
         return (t1 - t0) * 1e3 / steps, stats
 
 
+def per_step_times(st, iters, warmup, serial):
+    """Each step timed on its own by a pair of HIP events on the compute stream: (median ms, mean ms)."""
+    torch = st.torch
+    with torch.cuda.stream(st.sc):
+        for _ in range(warmup):
+            st.step(serial)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+        for e0, e1 in ev:
+            e0.record(st.sc)
+            st.step(serial)
+            e1.record(st.sc)
+        torch.cuda.synchronize()
+    ms = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+    return ms[len(ms) // 2], sum(ms) / len(ms)
+
+
 def kernel_table(stats):
     out = {}
     for name, s in stats.items():
@@ -305,7 +321,12 @@ def main():
     st = Stack(w, staging, torch, osdp, rows=rows, zdp_slices=a.zdp_slices, longer=longer)
     flops = wl.flops(w)
 
+    torch.cuda.synchronize()
+    alloc_before = torch.cuda.memory_allocated()
+    torch.cuda.reset_peak_memory_stats()
     ms, _ = st.run(a.steps, a.warmup, serial=a.serial)
+    alloc_delta = torch.cuda.max_memory_allocated() - alloc_before   # the library allocates nothing: the workspace is all
+    median_ms, mean_ms = per_step_times(st, 100, 10, a.serial)
     ms_prof, stats = st.run(a.steps, 2, serial=a.serial, profile=True)
     kernels = kernel_table(stats)
     gemms = {k: v for k, v in kernels.items() if k.startswith("gemm")}
@@ -332,6 +353,8 @@ def main():
         "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3),
         "workspace_mb": round(st.workspace_bytes / 2 ** 20, 3),
         "ms_per_step_with_kernel_timing": round(ms_prof, 4),
+        "per_step_events": {"iters": 100, "warmup": 10, "median_ms": round(median_ms, 4), "mean_ms": round(mean_ms, 4)},
+        "device_memory_allocated_during_steps_bytes": int(alloc_delta),
         "roofline": roofline,
         "kernels": kernels,
     }
