@@ -144,13 +144,20 @@ hipError_t launch_generic(const GemmParams &p, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// The kernels use more dynamic LDS than the default limit; the attribute is set once per kernel and device.
+constexpr int kMaxDevices = 16;
+
 template <class Kernel>
-hipError_t allow_lds(Kernel kernel, size_t lds, bool *configured) {
-  if (!*configured) {  // a benign race sets the same attribute twice
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       static_cast<int>(lds));
+hipError_t allow_lds(Kernel kernel, size_t lds, bool (&configured)[kMaxDevices]) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  if (!configured[dev]) {  // a benign race sets the same attribute twice
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            static_cast<int>(lds));
     if (e != hipSuccess) return e;
-    *configured = true;
+    configured[dev] = true;
   }
   return hipSuccess;
 }
@@ -161,8 +168,8 @@ hipError_t launch_dma(const GemmParams &p, hipStream_t stream) {
   constexpr size_t lds = static_cast<size_t>(kStages) * (BM + BN) * BK * sizeof(uint16_t);
   static_assert(lds + OSDP_MAX_SHARDS * 8 <= 160 * 1024, "tile does not fit the 160 KB of LDS");
   auto kernel = gemm_dma_kernel<BM, BN, WM, WN, BK, kStages, kAK, kBK, kEpi, kAccIn>;
-  static bool configured = false;
-  hipError_t e = allow_lds(kernel, lds, &configured);
+  static bool configured[kMaxDevices] = {};
+  hipError_t e = allow_lds(kernel, lds, configured);
   if (e != hipSuccess) return e;
   const int tiles_m = p.M / BM, tiles_n = p.N / BN;
   hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n), dim3(kWaves * 64), lds, stream, p, tiles_m, tiles_n);
