@@ -409,16 +409,26 @@ def main():
                 msl = min(st.run(max(5, a.steps // 2), max(2, a.warmup // 2), serial=a.serial)[0] for _ in range(2))
                 sweep[str(k)]["tflops_longer_split_dim"] = round(wl.flops(wk) / (msl * 1e-3) / 1e12, 2)
         out["k_sweep"] = sweep
-        if a.config == 2:  # the h = 2560 layer under its plan vector, where the 70 % target applies
-            del st
-            torch.cuda.empty_cache()
-            w3 = wl.workload(3)
-            st = Stack(w3, staging, torch, osdp, rows=rows)
-            ms3 = min(st.run(10, 3, serial=a.serial)[0] for _ in range(2))
-            tf3 = wl.flops(w3) / (ms3 * 1e-3) / 1e12
-            out["also"] = {"workload": w3.name, "plan": {op.name: op.k for op in w3.ops}, "ms_per_step": round(ms3, 4),
-                           "tflops": round(tf3, 2), "frac_bf16_mfma_peak": round(tf3 / PEAK_BF16_TFLOPS, 4),
-                           "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3)}
+        if a.config == 2:  # the larger workloads under their own plan vectors (config 3 is where the 70 % target applies)
+            also = []
+            for cfg in (3, 4, 5):
+                del st
+                torch.cuda.empty_cache()
+                wc = wl.workload(cfg)
+                entry = {"workload": wc.name, "baseline_config": cfg, "plan": {op.name: op.k for op in wc.ops}}
+                for label, kw in (("", dict(rows=rows)), ("_longer_split_dim", dict(longer=True))):
+                    st = Stack(wc, staging, torch, osdp, **kw)
+                    msc = min(st.run(5, 2, serial=a.serial)[0] for _ in range(2))
+                    tfc = wl.flops(wc) / (msc * 1e-3) / 1e12
+                    entry.update({"ms_per_step" + label: round(msc, 4), "tflops" + label: round(tfc, 2),
+                                  "frac_bf16_mfma_peak" + label: round(tfc / PEAK_BF16_TFLOPS, 4),
+                                  "peak_staging_mb" + label: round(st.peak_staging / 2 ** 20, 3),
+                                  "workspace_mb" + label: round(st.workspace_bytes / 2 ** 20, 3)})
+                    if label == "":
+                        del st
+                        torch.cuda.empty_cache()
+                also.append(entry)
+            out["also"] = also
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, rows=rows)
     print(json.dumps(out), flush=True)
