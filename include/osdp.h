@@ -49,6 +49,11 @@
  *     stream_compute alone makes every output valid, and stream_copy has been
  *     ordered after the last use of the workspace.  Inputs must be ready on
  *     stream_compute when the call is made.
+ *   - The forward, backward and gather calls can be captured into a HIP graph on
+ *     stream_compute (after one eager call, which sets kernel attributes): they enqueue
+ *     kernels and event records / waits only, and every use of stream_copy starts
+ *     from and returns to stream_compute.  Not capturable: the profiling calls
+ *     and osdp_granularity_measure, which synchronise.
  *   - Errors: arguments are validated before anything is enqueued, so every
  *     status except OSDP_ERR_HIP leaves the outputs untouched.
  *     osdp_last_error() gives a thread-local message for the last failure.

@@ -750,3 +750,52 @@ def test_padded_leading_dimensions_and_many_shards(H, oracle, T, I, O, N, k, dim
     got_dW = np.concatenate([H.to_bits(s) for s in dW])[: I * O].reshape(I, O)
     H.assert_close("dW", got_dW, ref["dW"])
     assert (H.to_bits(Yw)[:, O:] == POISON).all() and (H.to_bits(dXw)[:, I:] == POISON).all()
+
+
+# ------------------------------------------------ capture into a HIP graph
+@pytest.mark.parametrize("pair", ["0", "1"])
+def test_calls_can_be_captured_into_a_graph_and_replayed(H, pair, monkeypatch):
+    """A forward + backward captured on the compute stream (one-stream and two-stream pipelines, the latter with
+    its cross-stream events inside the capture) replays to the bits of the eager calls, every time, with eager work
+    and new inputs between the replays."""
+    import paper_2209_13258_amd as osdp
+    monkeypatch.setenv("OSDP_FWD_PAIR", pair)   # "0": the forward overlaps gathers on the copy stream; "1": one stream
+    T, I, O, N, k = 512, 2048, 4096, 8, 2       # 8 MB slices: the backward uses the copy stream too
+    d = wl.small_case(91, T, I, O, N)
+    op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+    plan = osdp.Plan([k], staging=osdp.OSDP_STAGING_DOUBLE)
+    sc, sp = H.streams()
+
+    def eager():
+        with torch.cuda.stream(sc):
+            op.fwd(k, plan=plan, streams=(sc, sp))
+            op.bwd(k, plan=plan, streams=(sc, sp))
+        sc.synchronize()
+        return [op.Y.clone(), op.dX.clone()] + [s.clone() for s in op.dW]
+
+    def poison():
+        for t in [op.Y, op.dX] + op.dW:
+            t.fill_(float("nan"))
+        torch.cuda.synchronize()
+
+    ref = eager()                                # also the warm-up that sets the kernels' attributes
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=sc):
+        op.fwd(k, plan=plan, streams=(sc, sp))
+        op.bwd(k, plan=plan, streams=(sc, sp))
+    g = torch.Generator(device="cuda")
+    g.manual_seed(92)
+    for rep in range(3):
+        _announce("graph replay", pair, rep)
+        poison()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [op.Y, op.dX] + op.dW
+        for a, b in zip(got, ref):
+            assert torch.equal(a.view(torch.int16), b.view(torch.int16)), f"replay {rep} differs from the eager result"
+        # new inputs, eager work and synchronisations before the next replay
+        op.X.copy_(torch.randn(op.X.shape, generator=g, device="cuda").to(torch.bfloat16))
+        op.dY.copy_(torch.randn(op.dY.shape, generator=g, device="cuda").to(torch.bfloat16))
+        torch.cuda.synchronize()
+        ref = eager()
