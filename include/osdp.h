@@ -78,7 +78,7 @@ extern "C" {
 
 typedef enum {
   OSDP_OK = 0,
-  OSDP_ERR_INVALID_ARG = -1, /* null pointer, non-positive size, k > O, slice out of range, ld too small */
+  OSDP_ERR_INVALID_ARG = -1, /* null pointer, non-positive size (T < 0), k > O, slice out of range, ld too small */
   OSDP_ERR_UNSUPPORTED = -2, /* legal problem the kernels or this entry point do not handle (alignment, N > 64) */
   OSDP_ERR_WORKSPACE = -3,   /* workspace_bytes smaller than osdp_split_linear_workspace_bytes says */
   OSDP_ERR_HIP = -4          /* a HIP runtime call failed; outputs are undefined */
@@ -87,7 +87,10 @@ typedef enum {
 /* One linear operator (the paper's operator i with its parallelism degree N,
  * Section 3) together with its slice granularity (Section 3.3). */
 typedef struct {
-  int64_t T; /* tokens: rows of X, Y, dY, dX                      */
+  int64_t T; /* tokens: rows of X, Y, dY, dX.  0 is allowed: the
+                forward call then does nothing, the backward call
+                stores dW = 0 (an empty sum); X, Y, dY, dX may be
+                NULL                                              */
   int64_t I; /* in-features: columns of X, rows of W               */
   int64_t O; /* out-features: columns of W, Y                      */
   int32_t N; /* shard count                                        */

@@ -96,9 +96,9 @@ void slice_bounds(int64_t len, int64_t k, int64_t j, int64_t *c0, int64_t *c1) {
 
 osdp_status check_shape(const osdp_shape *s) {
   if (!s) return fail(OSDP_ERR_INVALID_ARG, "shape is NULL");
-  if (s->T <= 0 || s->I <= 0 || s->O <= 0)
-    return fail(OSDP_ERR_INVALID_ARG, "T, I, O must be positive (got %lld, %lld, %lld)", (long long)s->T,
-                (long long)s->I, (long long)s->O);
+  if (s->T < 0 || s->I <= 0 || s->O <= 0)
+    return fail(OSDP_ERR_INVALID_ARG, "I, O must be positive and T non-negative (got T %lld, I %lld, O %lld)",
+                (long long)s->T, (long long)s->I, (long long)s->O);
   if (s->N < 1) return fail(OSDP_ERR_INVALID_ARG, "N must be >= 1 (got %d)", s->N);
   if (s->k < 0) return fail(OSDP_ERR_INVALID_ARG, "k must be >= 0 (got %d)", s->k);
   return OSDP_OK;
@@ -683,12 +683,14 @@ static osdp_status forward(const osdp_shape *shape, const osdp_plan *plan, int32
   Resolved r;
   osdp_status st = resolve(shape, plan, op_index, two_streams, false, &r, allow_dp, &rep);
   if (st != OSDP_OK) return st;
-  if ((st = check_matrix(X, ldx, r.I, "X")) != OSDP_OK) return st;
-  if ((st = check_matrix(Y, ldy, r.O, "Y")) != OSDP_OK) return st;
+  const bool no_tokens = r.T == 0;  // X and Y have no rows and may be NULL
+  if (!no_tokens && (st = check_matrix(X, ldx, r.I, "X")) != OSDP_OK) return st;
+  if (!no_tokens && (st = check_matrix(Y, ldy, r.O, "Y")) != OSDP_OK) return st;
   ShardTable tab;
   if ((st = fill_table(w_shards, r.N, "w_shards", &tab)) != OSDP_OK) return st;
   if ((st = check_replicas(r, rep, false)) != OSDP_OK) return st;
   if ((st = check_workspace(r, workspace, workspace_bytes)) != OSDP_OK) return st;
+  if (no_tokens) return OSDP_OK;  // Y is empty: nothing is gathered, nothing is launched
 
   char *ws = static_cast<char *>(workspace);
   float *acc = reinterpret_cast<float *>(ws + r.slot_bytes * r.slots);  // row slices: Y's fp32 partial sum
@@ -760,15 +762,25 @@ static osdp_status backward(const osdp_shape *shape, const osdp_plan *plan, int3
   Resolved r;
   osdp_status st = resolve(shape, plan, op_index, two_streams, true, &r, allow_dp, &rep);
   if (st != OSDP_OK) return st;
-  if ((st = check_matrix(X, ldx, r.I, "X")) != OSDP_OK) return st;
-  if ((st = check_matrix(dY, lddy, r.O, "dY")) != OSDP_OK) return st;
-  if ((st = check_matrix(dX, lddx, r.I, "dX")) != OSDP_OK) return st;
+  const bool no_tokens = r.T == 0;  // X, dY and dX have no rows and may be NULL
+  if (!no_tokens && (st = check_matrix(X, ldx, r.I, "X")) != OSDP_OK) return st;
+  if (!no_tokens && (st = check_matrix(dY, lddy, r.O, "dY")) != OSDP_OK) return st;
+  if (!no_tokens && (st = check_matrix(dX, lddx, r.I, "dX")) != OSDP_OK) return st;
   ShardTable tab, gtab;
   if ((st = fill_table(w_shards, r.N, "w_shards", &tab)) != OSDP_OK) return st;
   if ((st = fill_table(reinterpret_cast<const void *const *>(dw_shards), r.N, "dw_shards", &gtab)) != OSDP_OK) return st;
   if ((st = check_replicas(r, rep, true)) != OSDP_OK) return st;
   if ((st = check_workspace(r, workspace, workspace_bytes)) != OSDP_OK) return st;
 
+  if (no_tokens) {
+    // dW = X^T . dY summed over no tokens is zero: the dW launches run with an empty reduction and store the
+    // zeros where the gradient belongs; dX is empty, so no weight is gathered.
+    for (const Slice &l : r.dw) {
+      const GemmProblem gw = dw_gemm(r, static_cast<int>(l.c0), static_cast<int>(l.c1), X, ldx, dY, lddy, gtab, rep);
+      OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DW, gw, static_cast<hipStream_t>(stream_compute)));
+    }
+    return OSDP_OK;
+  }
   char *ws = static_cast<char *>(workspace);
   float *acc = reinterpret_cast<float *>(ws + r.slot_bytes * r.slots);  // column slices: dX's fp32 partial sum
   const int n = static_cast<int>(r.sub.size());

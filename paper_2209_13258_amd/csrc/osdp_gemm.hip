@@ -22,7 +22,8 @@ namespace {
 // ---------------------------------------------------------------------------
 // Generic kernel: 128 x 128 x 32 tile, 4 waves of 64 x 64, single LDS buffer,
 // every access bounds-checked.  Handles any M, N and any K that is a multiple
-// of 8 (the tail of the last K block is zero-filled, which adds exact zeros).
+// of 8 (the tail of the last K block is zero-filled, which adds exact zeros);
+// K = 0 is the empty sum: it stores zeros (or acc_in) and reads neither operand.
 // ---------------------------------------------------------------------------
 constexpr int GBM = 128, GBN = 128, GBK = 32, GLDK = GBK + 8;
 
@@ -79,6 +80,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
   const int tid = threadIdx.x;
   if (kEpi == static_cast<int>(Epilogue::kBf16ShardMajor)) {
     if (tid < OSDP_MAX_SHARDS) s_tab[tid] = static_cast<uint16_t *>(p.shards.p[tid]);
+    __syncthreads();  // with K = 0 the loop below, and its barriers, do not run
   }
   const int tiles_m = (p.M + GBM - 1) / GBM;
   const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
@@ -193,7 +195,7 @@ double tile_cost(int M, int N, int BM, int BN, double penalty) {
 
 bool fast_path(int M, int N, int K, int k_split, int n_split) {
   const char *force = getenv("OSDP_GEMM");  // testing: "generic" forces the bounds-checked kernel
-  return !(force && force[0] == 'g') && M % 128 == 0 && N % 128 == 0 && K % 64 == 0 && k_split % 64 == 0 &&
+  return !(force && force[0] == 'g') && M % 128 == 0 && N % 128 == 0 && K > 0 && K % 64 == 0 && k_split % 64 == 0 &&
          n_split % 128 == 0;
 }
 
@@ -280,7 +282,8 @@ double gemm_estimate_us(int64_t M, int64_t N, int64_t K) {
 }
 
 hipError_t launch_gemm(const GemmProblem &q, hipStream_t stream) {
-  if (q.M <= 0 || q.N <= 0 || q.K <= 0) return hipSuccess;
+  if (q.M < 0 || q.N < 0 || q.K < 0) return hipErrorInvalidValue;
+  if (q.M == 0 || q.N == 0) return hipSuccess;  // nothing to write; K == 0 still writes the empty sum
   GemmParams p;
   p.M = q.M; p.N = q.N; p.K = q.K;
   p.A = static_cast<const uint16_t *>(q.A); p.lda = q.lda;

@@ -799,3 +799,45 @@ def test_calls_can_be_captured_into_a_graph_and_replayed(H, pair, monkeypatch):
         op.dY.copy_(torch.randn(op.dY.shape, generator=g, device="cuda").to(torch.bfloat16))
         torch.cuda.synchronize()
         ref = eager()
+
+
+# ------------------------------------------------------------- no tokens at all
+@pytest.mark.parametrize("rows", [False, True])
+@pytest.mark.parametrize("I,O,N,k,mask", [(256, 512, 4, 4, 0b1111),   # shapes the unchecked kernels would take
+                                          (264, 528, 4, 3, 0b111),    # ragged
+                                          (256, 512, 4, 4, 0b0110),   # two of the four slices in DP mode
+                                          (40, 24, 11, 1, 0b1)])      # general shard map with padding
+def test_zero_tokens_leave_y_alone_and_zero_the_gradient(H, oracle, I, O, N, k, mask, rows):
+    """T = 0: Y, dX are empty, and dW = X^T . dY is a sum over no tokens, i.e. zero - which the backward call must
+    store (a gradient buffer is not assumed to be cleared), in the shards and in the DP slices' own arrays."""
+    import paper_2209_13258_amd as osdp
+    if rows:
+        I, O = O, I
+    _announce("zero tokens", I, O, N, k, bin(mask), "rows" if rows else "cols")
+    dim = osdp.OSDP_SPLIT_IN_FEATURES if rows else osdp.OSDP_SPLIT_OUT_FEATURES
+    d, shards, w_dp, ld, rng, used, full = _mixed_host_case(oracle, 71, 0, I, O, N, k, mask, rows, False)
+    ref = oracle.linear(d["X"], d["W_shards"], O, dY=d["dY"])
+    assert ref["Y"].shape == (0, O) and ref["dX"].shape == (0, I) and not ref["dW"].any()
+    for mode, two in ((osdp.OSDP_STAGING_SINGLE, False), (osdp.OSDP_STAGING_DOUBLE, True)):
+        plan = osdp.Plan([k], staging=mode, zdp_mask=[mask], split_dim_per_op=[dim])
+        dev = _MixedDevice(H, d, shards, w_dp, ld, rng, I, O, rows, full)
+        sc, sp = H.streams()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(sc):
+            dev.run(k, plan, streams=(sc, sp if two else None))
+        sc.synchronize()
+        got, dW, in_dp, outside = dev.gradient(H, I, O, mask)
+        assert got["Y"].shape == (0, O) and got["dX"].shape == (0, I)
+        assert dW.shape == (I, O) and (dW == 0).all()        # +0.0 everywhere: the bits of the oracle's zeros
+        for a in in_dp:
+            assert (a == POISON).all()
+        for a in outside:
+            assert (a == POISON).all()
+        L = dev.op.L
+        pad = H.to_bits(dev.op.dW[-1])[I * O - (N - 1) * L:]
+        assert (pad == POISON).all()                         # shard padding untouched
+    if mask == (1 << max(k, 1)) - 1:                         # the plain entry points take the same shape
+        op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+        op.fwd(k)
+        op.bwd(k)
+        assert not op.results()["dW"].any()

@@ -214,7 +214,7 @@ def test_dp_slices_need_the_mixed_entry_points_and_their_replicas():
 
 
 @pytest.mark.parametrize("args,status", [
-    ((0, 256, 1024, 2, 4), -1), ((128, 256, 1024, 0, 4), -1), ((128, 256, 1024, 2, -1), -1),
+    ((-1, 256, 1024, 2, 4), -1), ((128, 0, 1024, 2, 4), -1), ((128, 256, 1024, 0, 4), -1), ((128, 256, 1024, 2, -1), -1),
     ((128, 256, 8, 2, 16), -1),        # k > O
     ((128, 252, 1024, 2, 4), -2),      # I not a multiple of 8
     ((128, 256, 1024, 2, 3), -2),      # slice bounds not aligned to 8 columns
@@ -288,3 +288,13 @@ def test_argument_errors_are_raised_before_anything_is_enqueued():
 def test_profile_end_without_begin_is_an_error():
     with pytest.raises(osdp.OsdpError):
         osdp.osdp_profile_end()
+
+
+def test_zero_tokens_is_a_legal_shape_and_negative_is_not():
+    """No tokens: the operator still has its weight, so the staging law is unchanged and the fp32 partial sum is empty."""
+    total0, peak0 = osdp.osdp_split_linear_workspace_bytes(0, 1024, 4096, 8, 4, True)
+    total1, peak1 = osdp.osdp_split_linear_workspace_bytes(128, 1024, 4096, 8, 4, True)
+    assert peak0 == peak1 and total0 == total1 - 128 * 1024 * 4
+    with pytest.raises(osdp.OsdpError) as e:
+        osdp.osdp_split_linear_workspace_bytes(-1, 1024, 4096, 8, 4, True)
+    assert e.value.status == osdp.binding.OSDP_ERR_INVALID_ARG
