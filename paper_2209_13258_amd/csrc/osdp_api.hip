@@ -222,7 +222,8 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
   r->slots = (mode == OSDP_STAGING_SINGLE) ? 1 : 2;
   int64_t n_gathered = 0;
   for (uint8_t d : r->dp) n_gathered += d ? 0 : 1;
-  if (static_cast<uint64_t>(D) * static_cast<uint64_t>(wmax) / 8 >= (1ull << 32))
+  // the gather kernel counts 16-byte vectors in 32 bits, and one copy may fill both slots
+  if (static_cast<uint64_t>(D) * static_cast<uint64_t>(wmax) / 8 >= (1ull << 31))
     return fail(OSDP_ERR_UNSUPPORTED, "slice of %lld x %lld elements is too large for the gather kernel", (long long)D, (long long)wmax);
   const size_t slice_bytes = static_cast<size_t>(D) * static_cast<size_t>(wmax) * 2;
   r->slot_bytes = round_up(slice_bytes, kSlotAlign);

@@ -78,6 +78,7 @@ hipError_t launch_gather(const ShardTable &shards, const ShardLayout &layout, in
   const uint64_t vecs_per_row = static_cast<uint64_t>(w) / 8;
   const uint64_t total = static_cast<uint64_t>(rows) * vecs_per_row;
   if (total == 0) return hipSuccess;
+  if (total >> 32) return hipErrorInvalidValue;  // the kernel divides a 32-bit vector index
   // measured on MI355X: one vector per thread and grid-stride step is fastest up to 128 MiB slices (2 MiB in 6 us,
   // 12.5 MiB in 6.4 us, 50 and 128 MiB at 6.3 TB/s read + write, 80 % of the HBM peak); beyond that 4 vectors per
   // thread with all loads ahead of the stores do slightly better (512 MiB: 5.3 against 5.1 TB/s)

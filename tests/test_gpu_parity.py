@@ -841,3 +841,47 @@ def test_zero_tokens_leave_y_alone_and_zero_the_gradient(H, oracle, I, O, N, k, 
         op.fwd(k)
         op.bwd(k)
         assert not op.results()["dW"].any()
+
+
+# --------------------------------------- a weight whose flat index needs more than 32 bits
+@pytest.mark.parametrize("N,rows", [(8, False),   # shards are row blocks; column slices, the last one gathered alone too
+                                    (3, True)])   # N does not divide I: general flat map; row slices
+def test_weight_of_more_than_2_to_32_elements(H, oracle, N, rows):
+    """I x O = 32768 x 132096 = 4.33e9 weights (8.7 GB in bf16): every flat index past 2^31 and 2^32 must be formed
+    in 64 bits by the gather, by the slice GEMMs' reads of an up to 2.2 GB staging slot and by the shard-major dW
+    store.  The weights repeat with a period that divides neither power, so a wrapped index reads another value."""
+    import paper_2209_13258_amd as osdp
+    T, I, O, k = 256, 32768, 132096, 4
+    _announce("wide index", T, I, O, N, k, "rows" if rows else "cols")
+    d = wl.tiled_case(5, T, I, O, N, (1 << 24) + 8)
+    dev = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+    dim = osdp.OSDP_SPLIT_IN_FEATURES if rows else osdp.OSDP_SPLIT_OUT_FEATURES
+    plan = osdp.Plan([k], split_dim_per_op=[dim])
+    sc, sp = H.streams()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(sc):
+        dev.fwd(k, plan=plan, streams=(sc, sp))
+        dev.bwd(k, plan=plan, streams=(sc, sp))
+    sc.synchronize()
+    got = dev.results()
+    g = np.random.default_rng(4242 + N)
+    ns = 4000
+    # weight entries around flat index 2^31 and 2^32, the four corners, and random ones
+    near = np.array([f + e for f in (1 << 31, 1 << 32, I * O - 1) for e in (-8, -1, 0)] + [0, O - 1, (I - 1) * O])
+    wi = np.concatenate([g.integers(0, I, ns), near // O])
+    wo = np.concatenate([g.integers(0, O, ns), near % O])
+    H.assert_close("dW", got["dW"][wi, wo], oracle.sample_dw(d["X"], d["dY"], wi, wo))
+    r = np.concatenate([g.integers(0, T, ns), np.full(near.size, T - 1)])
+    c = np.concatenate([g.integers(0, O, ns), near % O])
+    H.assert_close("Y", got["Y"][r, c], oracle.sample_y(d["X"], d["W_shards"], O, r, c))
+    c = np.concatenate([g.integers(0, I, ns), near // O])
+    H.assert_close("dX", got["dX"][r, c], oracle.sample_dx(d["dY"], d["W_shards"], I, r, c))
+    for name in ("Y", "dX", "dW"):
+        assert not np.isnan(H.widen(got[name][:: max(1, got[name].shape[0] // 512)])).any(), f"{name} has unwritten entries"
+    if not rows:
+        j = k - 1
+        c0, c1 = oracle.slice_range(O, k, j)
+        stg = torch.empty((I * (c1 - c0),), dtype=torch.bfloat16, device="cuda")
+        osdp.osdp_split_linear_gather_slice(I, O, k, j, dev.W, stg)
+        torch.cuda.synchronize()
+        assert np.array_equal(H.to_bits(stg).reshape(I, c1 - c0), oracle.gather_slice(d["W_shards"], I, O, k, j))

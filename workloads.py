@@ -138,3 +138,17 @@ def small_case(seed: int, T: int, I: int, O: int, N: int, w_std: float = 0.02):
         "dY": normal_bf16(g, (T, O), 1.0),
         "W_shards": [normal_bf16(g, (L,), w_std) for _ in range(N)],
     }
+
+
+def tiled_case(seed: int, T: int, I: int, O: int, N: int, period: int, w_std: float = 0.02):
+    """Inputs for index-width tests on very large weights: ``period`` weights are drawn as in ``small_case``
+    and repeated to fill the N shards (drawing billions of values would take minutes and adds nothing to
+    such a test).  Choose a period that does not divide 2^31 or 2^32, so that an index that wraps at either
+    width lands on a different value."""
+    g = np.random.Generator(np.random.PCG64(np.random.SeedSequence([ROOT_SEED, 98, seed, T, I, O, N])))
+    L = shard_elems(I, O, N)
+    X = normal_bf16(g, (T, I), 1.0)
+    dY = normal_bf16(g, (T, O), 1.0)
+    block = normal_bf16(g, (period,), w_std)
+    flat = np.resize(block, N * L)
+    return {"X": X, "dY": dY, "W_shards": [flat[s * L:(s + 1) * L] for s in range(N)]}
