@@ -44,7 +44,11 @@
  *   - Slice bounds: c0_j = floor(j*O/k), c1_j = floor((j+1)*O/k).  k = 0 means
  *     "no splitting" (the paper's granularity 0, Section 4.3) and equals k = 1.
  *   - The library never allocates device memory.  The caller owns all buffers,
- *     including the workspace; the library owns only a few HIP events.
+ *     including the workspace; the library owns only a few HIP events
+ *     (a pool per calling host thread and device, kept until the process ends).
+ *   - Threads: any host thread may call; calls from different threads share no
+ *     state in the library.  Two calls that use the same workspace or outputs
+ *     must be ordered by the caller's streams like any other GPU work.
  *   - Calls enqueue work and return.  When a call returns, synchronising
  *     stream_compute alone makes every output valid, and stream_copy has been
  *     ordered after the last use of the workspace.  Inputs must be ready on

@@ -11,7 +11,6 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
-#include <mutex>
 #include <string>
 #include <vector>
 
@@ -360,13 +359,13 @@ osdp_status check_workspace(const Resolved &r, const void *ws, size_t bytes) {
 }
 
 // ---- events -----------------------------------------------------------------
-// A cyclic pool of untimed events for the cross-stream edges.  An event may be
-// re-recorded once the waits on its earlier record have been enqueued, which
-// always holds here: every wait is issued within a few pool steps of its record.
+// A cyclic pool of untimed events for the cross-stream edges, one pool per host thread and device.  An event
+// may be re-recorded once the waits on its earlier record have been enqueued, which always holds here: the
+// calling thread issues every wait within a few of its own pool steps of the record, and no other thread
+// takes events from its pool.  The events live until the process ends.
 class EventPool {
  public:
   hipError_t get(hipEvent_t *out) {
-    std::lock_guard<std::mutex> g(mu_);
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
@@ -392,11 +391,10 @@ class EventPool {
     std::vector<hipEvent_t> ev;
     size_t next = 0;
   };
-  std::mutex mu_;
   PerDevice dev_[kMaxDevices];
 };
 
-EventPool g_events;
+thread_local EventPool g_events;
 
 // after: everything enqueued on `from` so far; makes `to` wait for it
 hipError_t edge(hipStream_t from, hipStream_t to) {

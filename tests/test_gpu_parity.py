@@ -885,3 +885,53 @@ def test_weight_of_more_than_2_to_32_elements(H, oracle, N, rows):
         osdp.osdp_split_linear_gather_slice(I, O, k, j, dev.W, stg)
         torch.cuda.synchronize()
         assert np.array_equal(H.to_bits(stg).reshape(I, c1 - c0), oracle.gather_slice(d["W_shards"], I, O, k, j))
+
+
+# ------------------------------------------------------------- calls from several host threads
+def test_two_host_threads_call_concurrently(H, oracle):
+    """Each thread drives its own operator, workspace and pair of streams; the bits must be those of the same
+    calls made one after the other (the library keeps its cross-stream events per calling thread)."""
+    import threading
+    T, I, O, N, k = 512, 512, 2048, 4, 4
+    _announce("threads", T, I, O, N, k)
+    cases = [wl.small_case(80 + i, T, I, O, N) for i in range(2)]
+    want = []
+    for d in cases:
+        op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+        sc, sp = H.streams()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(sc):
+            op.fwd(k, streams=(sc, sp))
+            op.bwd(k, streams=(sc, sp))
+        sc.synchronize()
+        want.append(op.results())
+    ref0 = oracle.linear(cases[0]["X"], cases[0]["W_shards"], O, dY=cases[0]["dY"])
+    for name in ("Y", "dX", "dW"):
+        H.assert_close(name, want[0][name], ref0[name])
+    ops = [H.Operator(d["X"], d["dY"], d["W_shards"], O) for d in cases]
+    for op in ops:                       # workspaces allocated up front: the threads only enqueue
+        op.workspace(k, True)
+    streams = [H.streams() for _ in ops]
+    torch.cuda.synchronize()
+    errors = []
+
+    def drive(op, sc, sp):
+        try:
+            with torch.cuda.stream(sc):
+                for _ in range(20):
+                    op.fwd(k, streams=(sc, sp))
+                    op.bwd(k, streams=(sc, sp))
+            sc.synchronize()
+        except Exception as e:           # surfaced in the main thread below
+            errors.append(e)
+
+    threads = [threading.Thread(target=drive, args=(op, sc, sp)) for op, (sc, sp) in zip(ops, streams)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for op, ref in zip(ops, want):
+        got = op.results()
+        for name in ("Y", "dX", "dW"):
+            assert np.array_equal(got[name], ref[name]), name
