@@ -209,6 +209,10 @@ struct TileShape {
 // 1.04 / 0.90 / 1.09; 128x256 (two per CU) 1.19 / 1.02 / 1.06; 128x128 (two per CU) 1.03 / 1.05 / 1.03.
 // K block and LDS stages per layout, also measured: forward (transposing reads of B) runs best with K blocks of
 // 64 in two stages, dW and dX on the 256x256 tile and dW on the 128x128 tile with K blocks of 32 in four stages.
+// The smaller tiles are sized for two workgroups per CU.  A launch with no more tiles than CUs has one, and is
+// then bound by the latency of its loads (1024x4096x8192 for dW on 128x128 tiles: 41 GB/s per CU with 48 KB in
+// flight); it takes the CU's whole LDS for K blocks of 64 in three or four stages, 96 KB in flight: dW 100 -> 88 us,
+// the forward launch over two 256-column slices with K = 4096 64 -> 52 us.
 constexpr TileShape kTiles[4] = {{256, 256, {1.0, 1.0, 1.0}},
                                  {256, 128, {1.17, 1.32, 1.16}},
                                  {128, 256, {1.03, 1.16, 1.19}},
@@ -242,13 +246,23 @@ hipError_t launch_best(const GemmParams &p, hipStream_t stream) {
       const TileShape &f = kTiles[t[0] - '0'];
       if (p.M % f.bm == 0 && p.N % f.bn == 0 && p.n_split % f.bn == 0) best = t[0] - '0';
     }
+    // A launch of at most one tile per CU cannot hide the latency of its loads behind a second workgroup: it gets
+    // the whole LDS for a deeper pipeline instead (twice the bytes in flight).
+    const char *dp = getenv("OSDP_DEEP");  // testing: "0" keeps the shallow pipelines
+    const bool deep = best > 0 && static_cast<long>(p.M / kTiles[best].bm) * (p.N / kTiles[best].bn) <= kCUs &&
+                      !(dp && dp[0] == '0');
     switch (best) {
       case 0:
         if (kind == 0) return launch_dma<256, 256, 64, 128, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
         return launch_dma<256, 256, 64, 128, 32, 4, kAK, kBK, kEpi, kAccIn>(p, stream);
-      case 1: return launch_dma<256, 128, 64, 64, 32, 3, kAK, kBK, kEpi, kAccIn>(p, stream);
-      case 2: return launch_dma<128, 256, 64, 64, 32, 3, kAK, kBK, kEpi, kAccIn>(p, stream);
+      case 1:
+        if (deep) return launch_dma<256, 128, 64, 64, 64, 3, kAK, kBK, kEpi, kAccIn>(p, stream);
+        return launch_dma<256, 128, 64, 64, 32, 3, kAK, kBK, kEpi, kAccIn>(p, stream);
+      case 2:
+        if (deep) return launch_dma<128, 256, 64, 64, 64, 3, kAK, kBK, kEpi, kAccIn>(p, stream);
+        return launch_dma<128, 256, 64, 64, 32, 3, kAK, kBK, kEpi, kAccIn>(p, stream);
       case 3:
+        if (deep) return launch_dma<128, 128, 64, 64, 64, 4, kAK, kBK, kEpi, kAccIn>(p, stream);
         if (kind == 1) return launch_dma<128, 128, 64, 64, 32, 4, kAK, kBK, kEpi, kAccIn>(p, stream);
         return launch_dma<128, 128, 64, 64, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
     }

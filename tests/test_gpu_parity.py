@@ -678,7 +678,7 @@ def test_config2_one_of_four_slices_zdp(H, oracle, rows):
 @pytest.mark.parametrize("T,I,O,N", [(512, 512, 768, 4), (256, 1024, 256, 8)])
 def test_every_tile_shape_gives_the_bits_of_the_checked_kernel(H, oracle, T, I, O, N, monkeypatch):
     """The host picks tile shapes by cost, so a test shape may never meet some of them: each of the four
-    (with its own K block, LDS stage count and launch bounds per operand layout) is forced in turn, for
+    (with its own K block, LDS stage count and launch bounds per operand layout and pipeline depth) is forced in turn, for
     the unsplit operator and for splits in both dimensions, and must reproduce the bounds-checked kernel
     bit for bit (and, through it, the oracle)."""
     import paper_2209_13258_amd as osdp
@@ -693,10 +693,13 @@ def test_every_tile_shape_gives_the_bits_of_the_checked_kernel(H, oracle, T, I, 
         H.assert_close(name, ref[name], want[name])
     monkeypatch.delenv("OSDP_GEMM")
     sc, sp = H.streams()
-    for tile in "0123":
+    # these shapes give every launch at most one tile per CU, where the library would use its deep-pipeline
+    # variants of tiles 1..3 only: both pipelines of each tile are forced in turn
+    for tile, deep in (("0", "1"), ("1", "0"), ("1", "1"), ("2", "0"), ("2", "1"), ("3", "0"), ("3", "1")):
         monkeypatch.setenv("OSDP_TILE", tile)
+        monkeypatch.setenv("OSDP_DEEP", deep)
         for k, dim in ((1, 0), (2, 0), (2, 1)):
-            _announce("tile", tile, T, I, O, N, "k", k, "dim", dim)
+            _announce("tile", tile, "deep", deep, T, I, O, N, "k", k, "dim", dim)
             plan = osdp.Plan([k], staging=osdp.OSDP_STAGING_DOUBLE, split_dim_per_op=[dim])
             op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
             torch.cuda.synchronize()
