@@ -212,7 +212,9 @@ struct TileShape {
 // The smaller tiles are sized for two workgroups per CU.  A launch with no more tiles than CUs has one, and is
 // then bound by the latency of its loads (1024x4096x8192 for dW on 128x128 tiles: 41 GB/s per CU with 48 KB in
 // flight); it takes the CU's whole LDS for K blocks of 64 in three or four stages, 96 KB in flight: dW 100 -> 88 us,
-// the forward launch over two 256-column slices with K = 4096 64 -> 52 us.
+// the forward launch over two 256-column slices with K = 4096 64 -> 52 us.  The lone 128x128 workgroup also runs
+// as 8 waves of 32x64 rather than 4 of 64x64, two per SIMD (another 3-10 %; without the deep pipeline it made no
+// difference).
 constexpr TileShape kTiles[4] = {{256, 256, {1.0, 1.0, 1.0}},
                                  {256, 128, {1.17, 1.32, 1.16}},
                                  {128, 256, {1.03, 1.16, 1.19}},
@@ -262,7 +264,7 @@ hipError_t launch_best(const GemmParams &p, hipStream_t stream) {
         if (deep) return launch_dma<128, 256, 64, 64, 64, 3, kAK, kBK, kEpi, kAccIn>(p, stream);
         return launch_dma<128, 256, 64, 64, 32, 3, kAK, kBK, kEpi, kAccIn>(p, stream);
       case 3:
-        if (deep) return launch_dma<128, 128, 64, 64, 64, 4, kAK, kBK, kEpi, kAccIn>(p, stream);
+        if (deep) return launch_dma<128, 128, 32, 64, 64, 4, kAK, kBK, kEpi, kAccIn>(p, stream);  // 8 waves of 32 x 64
         if (kind == 1) return launch_dma<128, 128, 64, 64, 32, 4, kAK, kBK, kEpi, kAccIn>(p, stream);
         return launch_dma<128, 128, 64, 64, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
     }
