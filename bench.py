@@ -27,8 +27,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 # profiles/hbm_traffic_config2_config3.md.  Only valid for the default plan of the workload.
 KIB = 1024
 MEASURED_TRAFFIC = {
-    2: {"gemm_fwd": (54740 + 13653) * KIB, "gemm_dw": (197007 + 8192) * KIB, "gemm_dx": (99692 + 63007) * KIB},
-    3: {"gemm_fwd": (791352 + 106790) * KIB, "gemm_dw": (1309395 + 25621) * KIB, "gemm_dx": (835020 + 232834) * KIB},
+    2: {"gemm_fwd": (54717 + 13653) * KIB, "gemm_dw": (196809 + 8192) * KIB, "gemm_dx": (99715 + 62904) * KIB},
+    3: {"gemm_fwd": (787435 + 106743) * KIB, "gemm_dw": (1290087 + 25613) * KIB, "gemm_dx": (835048 + 232882) * KIB},
 }
 
 
