@@ -298,3 +298,14 @@ def test_zero_tokens_is_a_legal_shape_and_negative_is_not():
     with pytest.raises(osdp.OsdpError) as e:
         osdp.osdp_split_linear_workspace_bytes(-1, 1024, 4096, 8, 4, True)
     assert e.value.status == osdp.binding.OSDP_ERR_INVALID_ARG
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU's share of the step; asking for more must end with a message, not a run."""
+    import subprocess
+    import sys
+    from pathlib import Path
+    root = Path(__file__).resolve().parent.parent
+    r = subprocess.run([sys.executable, str(root / "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "--gpus must be 1" in (r.stderr + r.stdout)
