@@ -301,6 +301,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    import __graft_entry__
+    __graft_entry__.ensure_built()   # loads the library the tree holds; builds one only when there is none
     import paper_2209_13258_amd as osdp
     import workloads as wl
 

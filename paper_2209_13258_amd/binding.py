@@ -94,7 +94,7 @@ def _load() -> ctypes.CDLL:
     path = _build.LIB
     if not path.exists():
         raise ImportError(
-            f"{path} is missing: build it first (python -m paper_2209_13258_amd.build); "
+            f"{path} is missing: build it first (python paper_2209_13258_amd/build.py); "
             "there is no fallback path")
     lib = ctypes.CDLL(str(path))
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64

@@ -10,6 +10,8 @@ if str(ROOT) not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    import __graft_entry__
+    __graft_entry__.ensure_built()   # the tests load the library the tree holds and build one only when there is none
 
 
 @pytest.fixture(scope="session")
