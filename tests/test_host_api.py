@@ -309,3 +309,15 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, str(root / "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0
     assert "--gpus must be 1" in (r.stderr + r.stdout)
+
+
+def test_public_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: include/osdp.h must compile as C99 on its own, with no warnings."""
+    import subprocess
+    from pathlib import Path
+    root = Path(__file__).resolve().parent.parent
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "osdp.h"\nint main(void) { return (int)sizeof(osdp_plan) + (int)sizeof(osdp_shape); }\n')
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", f"-I{root / 'include'}",
+                        "-fsyntax-only", str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
