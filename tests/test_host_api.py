@@ -321,3 +321,37 @@ def test_public_header_is_plain_c(tmp_path):
     r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", f"-I{root / 'include'}",
                         "-fsyntax-only", str(src)], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
+
+
+def test_a_c_program_links_and_calls_the_library(tmp_path):
+    """No Python in between: a C99 program links libosdp.so and uses the host-side calls (slice law, errors)."""
+    import subprocess
+    from pathlib import Path
+    root = Path(__file__).resolve().parent.parent
+    pkg = root / "paper_2209_13258_amd"
+    src = tmp_path / "client.c"
+    src.write_text(r'''
+#include <stdio.h>
+#include <string.h>
+#include "osdp.h"
+int main(void) {
+  osdp_shape s = {8192, 1024, 4096, 8, 4};
+  int64_t c0 = -1, c1 = -1;
+  size_t total = 0, peak = 0;
+  if (osdp_slice_range(&s, 3, &c0, &c1) != OSDP_OK || c0 != 3072 || c1 != 4096) return 1;
+  if (osdp_split_linear_workspace_bytes(&s, NULL, 0, 1, &total, &peak) != OSDP_OK) return 2;
+  if (peak != (size_t)2 * 1024 * 1024 * 2 || total < peak) return 3;        /* automatic staging: two slots of size / k = 2 MiB */
+  if (osdp_slice_range(&s, 4, &c0, &c1) != OSDP_ERR_INVALID_ARG) return 4;  /* slice index out of range */
+  if (strlen(osdp_last_error()) == 0 || strlen(osdp_strerror(OSDP_ERR_INVALID_ARG)) == 0) return 5;
+  printf("%s\n", osdp_version());
+  return 0;
+}
+''')
+    exe = tmp_path / "client"
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", f"-I{root / 'include'}", str(src), "-o", str(exe),
+                        f"-L{pkg}", "-losdp", f"-Wl,-rpath,{pkg}", "-Wl,-rpath,/opt/rocm/lib", "-L/opt/rocm/lib"],
+                       capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+    assert r.stdout.strip()
