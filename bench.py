@@ -214,10 +214,28 @@ def auto_granularity(st, osdp, torch, steps, warmup):
     return out
 
 
+def measure_alpha(torch, osdp, reps=200):
+    """Fixed cost of one gather, in seconds: the smallest legal slice (8 x 8 elements from one shard) copied `reps`
+    times back to back on one stream, timed by a pair of events."""
+    shard = [torch.zeros(64, dtype=torch.bfloat16, device="cuda")]
+    stg = torch.empty(64, dtype=torch.bfloat16, device="cuda")
+    cur = torch.cuda.current_stream()
+    for _ in range(10):
+        osdp.osdp_split_linear_gather_slice(8, 8, 1, 0, shard, stg, stream=cur)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(cur)
+    for _ in range(reps):
+        osdp.osdp_split_linear_gather_slice(8, 8, 1, 0, shard, stg, stream=cur)
+    e1.record(cur)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / reps
+
+
 def plan_search(w, kernels, staging, rows, torch, osdp, steps, warmup):
     """Algorithm 1 on this workload with device information taken from this run: every slice of every operator is
     an item (Section 3.3), gamma from the measured GEMM throughput, beta from the measured gather bandwidth, alpha
-    from the gather's launch-bound floor; the memory limit leaves room for half of the weights to be replicated.
+    from the measured fixed cost of the smallest gather; the memory limit leaves room for half of the weights to be replicated.
     The chosen per-slice modes are then run through the mixed entry points and timed."""
     import workloads as wl
     gemm_ms = sum(v["total_ms"] for k, v in kernels.items() if k.startswith("gemm"))
@@ -225,7 +243,7 @@ def plan_search(w, kernels, staging, rows, torch, osdp, steps, warmup):
     flops_per_s = gemm_flops / (gemm_ms * 1e-3)
     gather = kernels.get("gather")
     beta = 1.0 / (gather["gbs_algorithmic"] * 1e9 / 2) if gather else 1.0 / 2e12   # seconds per byte gathered
-    alpha = 5e-6
+    alpha = measure_alpha(torch, osdp)
     items, owner = [], []
     for layer in range(w.layers):
         for n, op in enumerate(w.ops):
