@@ -273,6 +273,74 @@ hipError_t launch_best(const GemmParams &p, hipStream_t stream) {
   return launch_generic<kAK, kBK, kEpi, kAccIn>(p, stream);
 }
 
+// Columns [n0, n1) of a one-segment problem as a problem of its own.
+template <bool kBK, int kEpi>
+GemmParams column_range(const GemmParams &p, int n0, int n1) {
+  GemmParams s = p;
+  s.N = n1 - n0;
+  s.B = kBK ? p.B + static_cast<int64_t>(n0) * p.ldb : p.B + n0;
+  if (kEpi == static_cast<int>(Epilogue::kBf16ShardMajor)) s.c0 = p.c0 + n0;
+  else if (kEpi == static_cast<int>(Epilogue::kF32Workspace)) s.C = static_cast<float *>(p.C) + n0;
+  else s.C = static_cast<uint16_t *>(p.C) + n0;
+  if (p.acc_in) s.acc_in = p.acc_in + n0;
+  return s;
+}
+
+// Rows [m0, m1) likewise.
+template <bool kAK, int kEpi>
+GemmParams row_range(const GemmParams &p, int m0, int m1) {
+  GemmParams s = p;
+  s.M = m1 - m0;
+  s.A = kAK ? p.A + static_cast<int64_t>(m0) * p.lda : p.A + m0;
+  if (kEpi == static_cast<int>(Epilogue::kBf16ShardMajor)) s.r0 = p.r0 + m0;
+  else if (kEpi == static_cast<int>(Epilogue::kF32Workspace)) s.C = static_cast<float *>(p.C) + static_cast<int64_t>(m0) * p.ldc;
+  else s.C = static_cast<uint16_t *>(p.C) + static_cast<int64_t>(m0) * p.ldc;
+  if (p.acc_in) s.acc_in = p.acc_in + static_cast<int64_t>(m0) * p.ld_acc;
+  return s;
+}
+
+int gcd_int(int a, int b) { return b ? gcd_int(b, a % b) : a; }
+
+// A problem whose 256 x 256 tiles fill the CUs a whole number of times plus a little is run as two launches:
+// the part that makes whole rounds on the large tile, and the remainder on whatever tile suits it (usually a
+// small one that spreads it over all CUs).  Tile shape never changes a result bit, so neither does this.
+template <bool kAK, bool kBK, int kEpi, bool kAccIn>
+hipError_t launch_planned(const GemmParams &p, hipStream_t stream) {
+  constexpr int kind = layout_kind(kAK, kBK);
+  const char *off = getenv("OSDP_SPLIT_LAUNCH");  // testing: "0" keeps every problem in one launch
+  if (!(off && off[0] == '0') && !getenv("OSDP_TILE") && !p.k_split && !p.n_split && p.M % 256 == 0 && p.N % 256 == 0 &&
+      fast_path(p.M, p.N, p.K, 0, 0)) {
+    double whole = 0.0;
+    best_tile(p.M, p.N, 0, kind, &whole);
+    const int tm = p.M / 256, tn = p.N / 256;
+    const double between = 1.0e7 / p.K;  // about 5 us from one launch to the next, in the cost's units of tile area
+    double best = 0.95 * whole;          // only for a clear gain
+    int axis = -1, cut = 0;
+    const int step_n = kCUs / gcd_int(tm, kCUs), step_m = kCUs / gcd_int(tn, kCUs);  // tile columns (rows) per whole round
+    const int cn = (tn - 1) / step_n * step_n, cm = (tm - 1) / step_m * step_m;
+    double rest = 0.0;
+    if (cn > 0 && best_tile(p.M, p.N - cn * 256, 0, kind, &rest) >= 0) {
+      const double c = tile_cost(p.M, cn * 256, 256, 256, 1.0) + rest + between;
+      if (c < best) { best = c; axis = 1; cut = cn * 256; }
+    }
+    if (cm > 0 && best_tile(p.M - cm * 256, p.N, 0, kind, &rest) >= 0) {
+      const double c = tile_cost(cm * 256, p.N, 256, 256, 1.0) + rest + between;
+      if (c < best) { best = c; axis = 0; cut = cm * 256; }
+    }
+    if (axis == 1) {
+      hipError_t e = launch_best<kAK, kBK, kEpi, kAccIn>(column_range<kBK, kEpi>(p, 0, cut), stream);
+      if (e != hipSuccess) return e;
+      return launch_best<kAK, kBK, kEpi, kAccIn>(column_range<kBK, kEpi>(p, cut, p.N), stream);
+    }
+    if (axis == 0) {
+      hipError_t e = launch_best<kAK, kBK, kEpi, kAccIn>(row_range<kAK, kEpi>(p, 0, cut), stream);
+      if (e != hipSuccess) return e;
+      return launch_best<kAK, kBK, kEpi, kAccIn>(row_range<kAK, kEpi>(p, cut, p.M), stream);
+    }
+  }
+  return launch_best<kAK, kBK, kEpi, kAccIn>(p, stream);
+}
+
 }  // namespace
 
 bool gemm_takes_two_segments(int64_t M, int64_t N, int64_t k_first, int64_t k_second) {
@@ -316,16 +384,16 @@ hipError_t launch_gemm(const GemmProblem &q, hipStream_t stream) {
   const bool acc = q.acc_in != nullptr;
   // The three GEMMs of the split linear layer, with the four accumulate forms for forward and dX, are the only combinations built.
   if (q.a_kcontig && !q.b_kcontig) {                                               // forward (accumulating when the reduction dimension is split)
-    if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_best<true, false, kRow, true>(p, stream) : launch_best<true, false, kRow, false>(p, stream);
-    if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_best<true, false, kF32, true>(p, stream) : launch_best<true, false, kF32, false>(p, stream);
+    if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_planned<true, false, kRow, true>(p, stream) : launch_planned<true, false, kRow, false>(p, stream);
+    if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_planned<true, false, kF32, true>(p, stream) : launch_planned<true, false, kF32, false>(p, stream);
   }
   if (!q.a_kcontig && !q.b_kcontig && !acc) {                                      // dW: into the shards, or (DP slice) a plain array
-    if (q.epilogue == Epilogue::kBf16ShardMajor) return launch_best<false, false, kShard, false>(p, stream);
-    if (q.epilogue == Epilogue::kBf16RowMajor) return launch_best<false, false, kRow, false>(p, stream);
+    if (q.epilogue == Epilogue::kBf16ShardMajor) return launch_planned<false, false, kShard, false>(p, stream);
+    if (q.epilogue == Epilogue::kBf16RowMajor) return launch_planned<false, false, kRow, false>(p, stream);
   }
   if (q.a_kcontig && q.b_kcontig) {                                                // dX
-    if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_best<true, true, kRow, true>(p, stream) : launch_best<true, true, kRow, false>(p, stream);
-    if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_best<true, true, kF32, true>(p, stream) : launch_best<true, true, kF32, false>(p, stream);
+    if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_planned<true, true, kRow, true>(p, stream) : launch_planned<true, true, kRow, false>(p, stream);
+    if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_planned<true, true, kF32, true>(p, stream) : launch_planned<true, true, kF32, false>(p, stream);
   }
   return hipErrorInvalidValue;
 }

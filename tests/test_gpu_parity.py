@@ -938,3 +938,27 @@ def test_two_host_threads_call_concurrently(H, oracle):
         got = op.results()
         for name in ("Y", "dX", "dW"):
             assert np.array_equal(got[name], ref[name]), name
+
+
+# ------------------------------------------------ one problem run as two launches
+@pytest.mark.parametrize("T,I,O", [(4096, 256, 4352),    # forward: 16 x 17 large tiles, cut along the columns
+                                   (256, 4352, 4096)])   # dW: 17 x 16 large tiles, cut along the rows (shard-major store)
+def test_whole_rounds_plus_remainder_launches_keep_the_bits(H, oracle, T, I, O, monkeypatch):
+    """A GEMM whose large tiles fill the CUs once plus a little is run as two launches (whole rounds, remainder):
+    same bits as the single launch, and the oracle's values."""
+    N = 8
+    _announce("two launches", T, I, O, N)
+    d = wl.small_case(91, T, I, O, N)
+    ref = oracle.linear(d["X"], d["W_shards"], O, dY=d["dY"])
+    res = {}
+    for flag in ("0", "1"):
+        monkeypatch.setenv("OSDP_SPLIT_LAUNCH", flag)
+        for k in (1, 2):
+            op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+            op.fwd(k)
+            op.bwd(k)
+            res[flag, k] = op.results()
+    for name in ("Y", "dX", "dW"):
+        H.assert_close(name, res["1", 1][name], ref[name])
+        for k in (1, 2):
+            assert np.array_equal(res["0", k][name], res["1", k][name]), f"{name} differs with two launches (k {k})"
