@@ -299,11 +299,9 @@ GemmParams row_range(const GemmParams &p, int m0, int m1) {
   return s;
 }
 
-int gcd_int(int a, int b) { return b ? gcd_int(b, a % b) : a; }
-
 // A problem whose 256 x 256 tiles fill the CUs a whole number of times plus a little is run as two launches:
-// the part that makes whole rounds on the large tile, and the remainder on whatever tile suits it (usually a
-// small one that spreads it over all CUs).  Tile shape never changes a result bit, so neither does this.
+// the part that makes (nearly) whole rounds on the large tile, and the remainder on whatever tile suits it
+// (usually a small one that spreads it over all CUs).  Tile shape never changes a result bit, so neither does this.
 template <bool kAK, bool kBK, int kEpi, bool kAccIn>
 hipError_t launch_planned(const GemmParams &p, hipStream_t stream) {
   constexpr int kind = layout_kind(kAK, kBK);
@@ -316,14 +314,21 @@ hipError_t launch_planned(const GemmParams &p, hipStream_t stream) {
     const double between = 1.0e7 / p.K;  // about 5 us from one launch to the next, in the cost's units of tile area
     double best = 0.95 * whole;          // only for a clear gain
     int axis = -1, cut = 0;
-    const int step_n = kCUs / gcd_int(tm, kCUs), step_m = kCUs / gcd_int(tn, kCUs);  // tile columns (rows) per whole round
-    const int cn = (tn - 1) / step_n * step_n, cm = (tm - 1) / step_m * step_m;
+    // candidate cuts: for every number of rounds r, the most tile columns (rows) that r rounds of large tiles hold
     double rest = 0.0;
-    if (cn > 0 && best_tile(p.M, p.N - cn * 256, 0, kind, &rest) >= 0) {
+    for (int r = 1; r <= 16; ++r) {
+      const int cn = static_cast<int>(static_cast<long>(kCUs) * r / tm);
+      if (cn <= 0) continue;
+      if (cn >= tn) break;
+      if (best_tile(p.M, p.N - cn * 256, 0, kind, &rest) < 0) continue;
       const double c = tile_cost(p.M, cn * 256, 256, 256, 1.0) + rest + between;
       if (c < best) { best = c; axis = 1; cut = cn * 256; }
     }
-    if (cm > 0 && best_tile(p.M - cm * 256, p.N, 0, kind, &rest) >= 0) {
+    for (int r = 1; r <= 16; ++r) {
+      const int cm = static_cast<int>(static_cast<long>(kCUs) * r / tn);
+      if (cm <= 0) continue;
+      if (cm >= tm) break;
+      if (best_tile(p.M - cm * 256, p.N, 0, kind, &rest) < 0) continue;
       const double c = tile_cost(cm * 256, p.N, 256, 256, 1.0) + rest + between;
       if (c < best) { best = c; axis = 0; cut = cm * 256; }
     }
