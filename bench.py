@@ -23,12 +23,13 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 
 # L2-miss traffic per launch (bytes, FETCH_SIZE + WRITE_SIZE of two rocprofv3 --pmc runs of this file with
 # --traffic-calibration, each counter scaled by what it read for the three 1 GiB calibration copies: FETCH_SIZE
-# x 2.000, WRITE_SIZE x 1.000; all tile shapes of a kernel kind together).  Source:
+# x 2.000, WRITE_SIZE x 1.000; all tile shapes of a kernel kind together, and both dispatches of a launch that the
+# library runs as whole rounds + remainder).  Source:
 # profiles/hbm_traffic_config2_config3.md.  Only valid for the default plan of the workload.
 KIB = 1024
 MEASURED_TRAFFIC = {
-    2: {"gemm_fwd": (54717 + 13653) * KIB, "gemm_dw": (196809 + 8192) * KIB, "gemm_dx": (99715 + 62904) * KIB},
-    3: {"gemm_fwd": (787435 + 106743) * KIB, "gemm_dw": (1290087 + 25613) * KIB, "gemm_dx": (835048 + 232882) * KIB},
+    2: {"gemm_fwd": (54717 + 13653) * KIB, "gemm_dw": (196809 + 8192) * KIB, "gemm_dx": (99711 + 62948) * KIB},
+    3: {"gemm_fwd": (640374 + 106082) * KIB, "gemm_dw": (923378 + 25631) * KIB, "gemm_dx": (807668 + 232916) * KIB},
 }
 
 
