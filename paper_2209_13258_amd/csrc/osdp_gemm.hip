@@ -302,36 +302,44 @@ GemmParams row_range(const GemmParams &p, int m0, int m1) {
 // A problem whose 256 x 256 tiles fill the CUs a whole number of times plus a little is run as two launches:
 // the part that makes (nearly) whole rounds on the large tile, and the remainder on whatever tile suits it
 // (usually a small one that spreads it over all CUs).  Tile shape never changes a result bit, so neither does this.
+// Returns the modelled cost (tile-area units) of the best plan for a one-segment M x N x K problem of the given
+// layout; axis = 1: columns [0, cut) and [cut, N) are launched separately; axis = 0: rows; axis = -1: one launch.
+double plan_launches(int M, int N, int K, int kind, int *axis, int *cut) {
+  double whole = 0.0;
+  *axis = -1;
+  *cut = 0;
+  if (best_tile(M, N, 0, kind, &whole) < 0) return 0.0;
+  const char *off = getenv("OSDP_SPLIT_LAUNCH");  // testing: "0" keeps every problem in one launch
+  if ((off && off[0] == '0') || getenv("OSDP_TILE") || M % 256 || N % 256) return whole;
+  const int tm = M / 256, tn = N / 256;
+  const double between = 1.0e7 / K;  // about 5 us from one launch to the next, in the cost's units of tile area
+  double best = 0.95 * whole;        // only for a clear gain
+  double rest = 0.0;
+  // candidate cuts: for every number of rounds r, the most tile columns (rows) that r rounds of large tiles hold
+  for (int r = 1; r <= 16; ++r) {
+    const int cn = static_cast<int>(static_cast<long>(kCUs) * r / tm);
+    if (cn <= 0) continue;
+    if (cn >= tn) break;
+    if (best_tile(M, N - cn * 256, 0, kind, &rest) < 0) continue;
+    const double c = tile_cost(M, cn * 256, 256, 256, 1.0) + rest + between;
+    if (c < best) { best = c; *axis = 1; *cut = cn * 256; }
+  }
+  for (int r = 1; r <= 16; ++r) {
+    const int cm = static_cast<int>(static_cast<long>(kCUs) * r / tn);
+    if (cm <= 0) continue;
+    if (cm >= tm) break;
+    if (best_tile(M - cm * 256, N, 0, kind, &rest) < 0) continue;
+    const double c = tile_cost(cm * 256, N, 256, 256, 1.0) + rest + between;
+    if (c < best) { best = c; *axis = 0; *cut = cm * 256; }
+  }
+  return *axis >= 0 ? best : whole;
+}
+
 template <bool kAK, bool kBK, int kEpi, bool kAccIn>
 hipError_t launch_planned(const GemmParams &p, hipStream_t stream) {
-  constexpr int kind = layout_kind(kAK, kBK);
-  const char *off = getenv("OSDP_SPLIT_LAUNCH");  // testing: "0" keeps every problem in one launch
-  if (!(off && off[0] == '0') && !getenv("OSDP_TILE") && !p.k_split && !p.n_split && p.M % 256 == 0 && p.N % 256 == 0 &&
-      fast_path(p.M, p.N, p.K, 0, 0)) {
-    double whole = 0.0;
-    best_tile(p.M, p.N, 0, kind, &whole);
-    const int tm = p.M / 256, tn = p.N / 256;
-    const double between = 1.0e7 / p.K;  // about 5 us from one launch to the next, in the cost's units of tile area
-    double best = 0.95 * whole;          // only for a clear gain
-    int axis = -1, cut = 0;
-    // candidate cuts: for every number of rounds r, the most tile columns (rows) that r rounds of large tiles hold
-    double rest = 0.0;
-    for (int r = 1; r <= 16; ++r) {
-      const int cn = static_cast<int>(static_cast<long>(kCUs) * r / tm);
-      if (cn <= 0) continue;
-      if (cn >= tn) break;
-      if (best_tile(p.M, p.N - cn * 256, 0, kind, &rest) < 0) continue;
-      const double c = tile_cost(p.M, cn * 256, 256, 256, 1.0) + rest + between;
-      if (c < best) { best = c; axis = 1; cut = cn * 256; }
-    }
-    for (int r = 1; r <= 16; ++r) {
-      const int cm = static_cast<int>(static_cast<long>(kCUs) * r / tn);
-      if (cm <= 0) continue;
-      if (cm >= tm) break;
-      if (best_tile(p.M - cm * 256, p.N, 0, kind, &rest) < 0) continue;
-      const double c = tile_cost(cm * 256, p.N, 256, 256, 1.0) + rest + between;
-      if (c < best) { best = c; axis = 0; cut = cm * 256; }
-    }
+  if (!p.k_split && !p.n_split && fast_path(p.M, p.N, p.K, 0, 0)) {
+    int axis, cut;
+    plan_launches(p.M, p.N, p.K, layout_kind(kAK, kBK), &axis, &cut);
     if (axis == 1) {
       hipError_t e = launch_best<kAK, kBK, kEpi, kAccIn>(column_range<kBK, kEpi>(p, 0, cut), stream);
       if (e != hipSuccess) return e;
@@ -361,6 +369,8 @@ bool gemm_takes_two_column_segments(int64_t M, int64_t n_first, int64_t n_second
 
 double gemm_estimate_us(int64_t M, int64_t N, int64_t K) {
   // one CU sustains about 4e6 flop per microsecond (1 PFLOP/s over 256 CUs) on 256 x 256 tiles
+  // (one launch on its best tile: pricing the whole-rounds + remainder pair here instead was measured and made the
+  // forward launch grouping of config 3 slightly worse)
   double cost = 0.0;
   if (fast_path(static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), 0, 0) &&
       best_tile(static_cast<int>(M), static_cast<int>(N), 0, 0, &cost) >= 0)
