@@ -179,6 +179,7 @@ hipError_t launch_dma(const GemmParams &p, hipStream_t stream) {
 }
 
 constexpr int kCUs = 256;
+constexpr int kShortK = 1024;
 
 // Estimated cost of covering M x N with BM x BN tiles on 256 CUs: tiles per CU times the tile's area, with a
 // penalty for the lower MFMA efficiency of smaller tiles.  Tiles that run two to a CU were measured in pairs; a
@@ -247,6 +248,15 @@ hipError_t launch_best(const GemmParams &p, hipStream_t stream) {
     if (t && t[0] >= '0' && t[0] <= '3') {
       const TileShape &f = kTiles[t[0] - '0'];
       if (p.M % f.bm == 0 && p.N % f.bn == 0 && p.n_split % f.bn == 0) best = t[0] - '0';
+    }
+    // A dX launch with a short reduction whose fp32 partial sum comes from or goes to memory is bound by that
+    // traffic, and with only a round or two of large tiles every CU loads, computes and stores in step with the
+    // others: two smaller workgroups per CU overlap one's loads and stores with the other's MFMAs (8192 x 4096 with
+    // K = 256: 62 -> 54 us; with 8 rounds of large tiles, 4096 x 32768, the large tile stays 7 % ahead).
+    if (kind == 2 && (kAccIn || kEpi == static_cast<int>(Epilogue::kF32Workspace)) && p.K <= kShortK && best == 0 &&
+        static_cast<long>(p.M / 256) * (p.N / 256) <= 2 * kCUs && !(t && t[0] >= '0' && t[0] <= '3')) {
+      if (p.N % 256 == 0 && p.n_split % 256 == 0) best = 2;
+      else if (p.n_split % 128 == 0) best = 1;
     }
     // A launch of at most one tile per CU cannot hide the latency of its loads behind a second workgroup: it gets
     // the whole LDS for a deeper pipeline instead (twice the bytes in flight).
