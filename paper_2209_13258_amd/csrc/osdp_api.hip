@@ -254,7 +254,10 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
     for (int64_t j = 0; j + 1 < n; j += 2) {
       pair_fwd = pair_fwd && can_pair(fwd_concat, j);
       if (!pair_fwd) break;
-      const double exposed = gather_estimate_us(D * width(j)) + gather_estimate_us(D * width(j + 1));
+      // two gathered neighbours are staged by one copy; a DP slice is read in place and costs no copy
+      const double exposed = (!r->dp[j] && !r->dp[j + 1]) ? gather_estimate_us(D * (width(j) + width(j + 1)))
+                             : (r->dp[j] ? 0.0 : gather_estimate_us(D * width(j))) +
+                               (r->dp[j + 1] ? 0.0 : gather_estimate_us(D * width(j + 1)));
       if (fwd_concat) {
         t_single += concat_us(j, j + 1) + concat_us(j + 1, j + 2);
         t_pair += concat_us(j, j + 2) + exposed;
