@@ -28,8 +28,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 # profiles/hbm_traffic_config2_config3.md.  Only valid for the default plan of the workload.
 KIB = 1024
 MEASURED_TRAFFIC = {
-    2: {"gemm_fwd": (54717 + 13653) * KIB, "gemm_dw": (196809 + 8192) * KIB, "gemm_dx": (99711 + 62948) * KIB},
-    3: {"gemm_fwd": (640374 + 106082) * KIB, "gemm_dw": (923378 + 25631) * KIB, "gemm_dx": (807668 + 232916) * KIB},
+    2: {"gemm_fwd": (73863 + 21438) * KIB, "gemm_dw": (196810 + 8192) * KIB, "gemm_dx": (111427 + 62469) * KIB},
+    3: {"gemm_fwd": (880856 + 126405) * KIB, "gemm_dw": (925151 + 25629) * KIB, "gemm_dx": (807698 + 232924) * KIB},
 }
 
 
