@@ -44,8 +44,9 @@
  *   - Slice bounds: c0_j = floor(j*O/k), c1_j = floor((j+1)*O/k).  k = 0 means
  *     "no splitting" (the paper's granularity 0, Section 4.3) and equals k = 1.
  *   - The library never allocates device memory.  The caller owns all buffers,
- *     including the workspace; the library owns only a few HIP events
- *     (a pool per calling host thread and device, kept until the process ends).
+ *     including the workspace; the library owns only a few HIP events (at most 64
+ *     per calling host thread and device; a thread that ends hands its events to
+ *     the threads that start later).
  *   - Threads: any host thread may call; calls from different threads share no
  *     state in the library.  Two calls that use the same workspace or outputs
  *     must be ordered by the caller's streams like any other GPU work.
@@ -107,7 +108,8 @@ typedef enum {
   OSDP_STAGING_SINGLE = 1, /* one slot of one slice (size/k): gather and GEMM alternate, no overlap */
   OSDP_STAGING_DOUBLE = 2, /* two slots of one slice (2*size/k): gather j+1 overlaps GEMM j        */
   OSDP_STAGING_HALF = 3    /* two slots of half a slice (size/k in total): every slice is processed
-                              as two half-width sub-slices so that the gather still overlaps      */
+                              as two half-width sub-slices, each with a GEMM launch of its own, so
+                              that the gather of one half overlaps the GEMM of the other          */
 } osdp_staging_mode;
 
 /* Which dimension of W the k slices cut. */
@@ -295,8 +297,8 @@ OSDP_API osdp_status osdp_granularity_measure(const osdp_shape *shape, const voi
  * (0 = no limit, each), let t* be the smallest ms.  Of those with ms <= (1 + max_slowdown) * t*, the one
  * with the smallest peak_weight_staging is chosen; ties go to the smaller ms,
  * then to the lower index.  max_slowdown = 0 picks the fastest candidate that
- * fits; a large max_slowdown picks the smallest peak ("fully optimise the
- * memory footprint at an acceptable additional time cost").
+ * fits; a large max_slowdown picks the smallest peak whatever it costs in time
+ * (the trade-off Section 4.3 leaves open).
  * OSDP_ERR_UNSUPPORTED when no measured candidate fits the budgets. */
 OSDP_API osdp_status osdp_granularity_select(const osdp_granularity_candidate *cands, int32_t n,
                                              size_t staging_budget, size_t workspace_budget,
@@ -359,6 +361,24 @@ OSDP_API osdp_status osdp_cost_model(const osdp_operator_cost *ops, int32_t n, c
  * 2e7 nodes and result->exact then reads 0. */
 OSDP_API osdp_status osdp_plan_search(const osdp_operator_cost *ops, int32_t n, const osdp_device_info *dev,
                                       uint8_t *modes, osdp_search_result *result);
+
+/* ---- test and debug switches ------------------------------------------------
+ * Process-wide switches for tests and for hunting stream races; none of them
+ * changes a result bit.  Initial values come from the environment variables
+ * OSDP_DEBUG_<NAME IN CAPITALS>, read once when the library is first used.
+ *   "gemm_generic"   0 | 1   1: every GEMM runs on the bounds-checked kernel
+ *   "tile"          -1 .. 3  force tile shape 256x256, 256x128, 128x256, 128x128 where it divides the launch
+ *   "deep"          -1 | 0   0: launches of at most one tile per CU keep the shallow LDS pipelines
+ *   "split_launch"  -1 | 0   0: no launch is cut into whole rounds of large tiles + remainder
+ *   "fwd_pair"      -1 .. 1  0: the forward never runs two staged slices in one launch; 1: whenever it can
+ *   "poison_staging" 0 | 1   1: a staging slot is filled with bf16 NaN patterns when a call starts and again as
+ *                            soon as the last GEMM that reads its slice has been enqueued (on the compute
+ *                            stream, ahead of the event that hands the slot to the next gather): a GEMM that
+ *                            runs ahead of its gather, or a gather that lands on a slice still in use,
+ *                            then shows up as NaN or wrong outputs instead of going unnoticed because the
+ *                            stale bytes happened to be right.  Costs one fill per slot use.
+ * -1 restores the library's own choice.  OSDP_ERR_INVALID_ARG for unknown names or values. */
+OSDP_API osdp_status osdp_debug_option(const char *name, int32_t value);
 
 /* ---- per-kernel timing (for benchmarks) --------------------------------- */
 

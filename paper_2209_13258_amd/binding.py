@@ -41,7 +41,7 @@ EXPORTS = (
     "osdp_split_linear_bwd", "osdp_split_linear_fwd_mixed", "osdp_split_linear_bwd_mixed",
     "osdp_granularity_candidates", "osdp_granularity_measure",
     "osdp_granularity_select", "osdp_cost_model", "osdp_plan_search", "osdp_profile_begin", "osdp_profile_end",
-    "osdp_strerror", "osdp_last_error", "osdp_version",
+    "osdp_debug_option", "osdp_strerror", "osdp_last_error", "osdp_version",
 )
 
 
@@ -121,6 +121,8 @@ def _load() -> ctypes.CDLL:
     lib.osdp_cost_model.argtypes = [opc, i32, dvi, ctypes.POINTER(ctypes.c_uint8), i32,
                                     ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.osdp_plan_search.argtypes = [opc, i32, dvi, ctypes.POINTER(ctypes.c_uint8), ctypes.POINTER(osdp_search_result)]
+    lib.osdp_debug_option.argtypes = [ctypes.c_char_p, i32]
+    lib.osdp_debug_option.restype = ctypes.c_int
     lib.osdp_profile_begin.argtypes = [i32]
     lib.osdp_profile_end.argtypes = [ctypes.POINTER(osdp_kernel_stats)]
     for name in ("osdp_slice_range", "osdp_row_slice_range", "osdp_split_linear_gather_slice",
@@ -356,6 +358,11 @@ def osdp_plan_search(ops, N, alpha, beta, m_limit, b_max=0):
         return None
     return dict(modes=list(modes), b=res.b, time_per_sample=res.time_per_sample, memory=res.memory,
                 batch_sizes_tried=res.batch_sizes_tried, plans_visited=res.plans_visited, exact=bool(res.exact))
+
+
+def osdp_debug_option(name: str, value: int) -> None:
+    """Sets one of the library's process-wide test and debug switches (-1: back to the library's own choice)."""
+    _check(lib.osdp_debug_option(name.encode(), int(value)))
 
 
 def osdp_profile_begin(max_launches: int = 1 << 16) -> None:

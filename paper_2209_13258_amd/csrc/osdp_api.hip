@@ -7,10 +7,12 @@
 // stream into the staging slot that the GEMM of slice j-1 has released, while
 // the GEMM of slice j runs on the compute stream.
 #include <algorithm>
+#include <cctype>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -43,6 +45,7 @@ osdp_status fail_hip(hipError_t e, const char *what) {
   } while (0)
 
 constexpr size_t kSlotAlign = 256;
+constexpr uint16_t kPoison = 0x7FC0;  // bf16 quiet NaN
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -247,7 +250,9 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
   // fewer half-empty rounds of tiles; row slices: one trip of the fp32 partial sum through the workspace less)
   // at the price of exposing their gathers; taken when the estimate says it pays.
   r->fwd.clear();
-  bool pair_fwd = r->slots == 2 && n >= 2;
+  // (never with half-slice staging: a launch over both halves would hold the whole staging area, and the
+  // mode would degenerate to SINGLE with nothing left for the next gather to overlap)
+  bool pair_fwd = r->slots == 2 && n >= 2 && mode != OSDP_STAGING_HALF;
   if (pair_fwd) {
     double t_single = 0.0, t_pair = 0.0;
     const double acc_trip_us = 8.0 * static_cast<double>(T) * static_cast<double>(D) / 3.0e6;  // fp32 out and back in
@@ -270,12 +275,11 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
     // than the estimate predicted (two streams cost events and contend for memory), so it only loses when the
     // estimate puts it clearly behind, as it does when the gathers dwarf the GEMMs (few tokens)
     pair_fwd = pair_fwd && t_pair < 1.10 * t_single;
-    if (const char *f = getenv("OSDP_FWD_PAIR")) {  // testing: "0" never pairs, "1" pairs whenever the kernel can
-      if (f[0] == '0') pair_fwd = false;
-      if (f[0] == '1') {
-        pair_fwd = true;
-        for (int64_t j = 0; j + 1 < n; j += 2) pair_fwd = pair_fwd && can_pair(fwd_concat, j);
-      }
+    const int forced = debug_options().fwd_pair.load(std::memory_order_relaxed);  // testing: 0 never pairs, 1 pairs whenever the kernel can
+    if (forced == 0) pair_fwd = false;
+    if (forced == 1) {
+      pair_fwd = true;
+      for (int64_t j = 0; j + 1 < n; j += 2) pair_fwd = pair_fwd && can_pair(fwd_concat, j);
     }
   }
   for (int64_t j = 0; j < n;) {
@@ -356,6 +360,14 @@ osdp_status check_matrix(const void *p, int64_t ld, int64_t cols, const char *na
   return OSDP_OK;
 }
 
+osdp_status device_ok() {
+  const hipError_t e = check_device();
+  if (e == hipErrorInvalidDevice)
+    return fail(OSDP_ERR_UNSUPPORTED, "the current device is not an MI355X (256 compute units in 8 XCDs), which the kernels are written for");
+  if (e != hipSuccess) return fail_hip(e, "querying the device");
+  return OSDP_OK;
+}
+
 osdp_status check_workspace(const Resolved &r, const void *ws, size_t bytes) {
   if (!ws) return fail(OSDP_ERR_INVALID_ARG, "workspace is NULL");
   if (reinterpret_cast<uintptr_t>(ws) % kSlotAlign) return fail(OSDP_ERR_UNSUPPORTED, "workspace is not 256-byte aligned");
@@ -367,20 +379,49 @@ osdp_status check_workspace(const Resolved &r, const void *ws, size_t bytes) {
 // ---- events -----------------------------------------------------------------
 // A cyclic pool of untimed events for the cross-stream edges, one pool per host thread and device.  An event
 // may be re-recorded once the waits on its earlier record have been enqueued, which always holds here: the
-// calling thread issues every wait within a few of its own pool steps of the record, and no other thread
-// takes events from its pool.  The events live until the process ends.
+// calling thread issues every wait within two pipeline steps (at most six pool steps) of the record, and no
+// other thread takes events from its pool.  When a thread ends its events go to a process-wide free list, from
+// which new threads draw before creating any, so that threads which come and go do not pile events up; the
+// events themselves live until the process ends (destroying them from a thread-exit or process-exit handler
+// would race with the runtime's own teardown).
+constexpr int kEventDevices = 16;
+
+struct EventFreeList {
+  std::mutex mu;
+  std::vector<hipEvent_t> ev[kEventDevices];
+};
+EventFreeList &event_free_list() {
+  static EventFreeList *list = new EventFreeList;  // never destroyed: thread-exit handlers may run late
+  return *list;
+}
+
 class EventPool {
  public:
+  ~EventPool() {
+    EventFreeList &fl = event_free_list();
+    std::lock_guard<std::mutex> lock(fl.mu);
+    for (int d = 0; d < kEventDevices; ++d) fl.ev[d].insert(fl.ev[d].end(), dev_[d].ev.begin(), dev_[d].ev.end());
+  }
   hipError_t get(hipEvent_t *out) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    if (dev < 0 || dev >= kEventDevices) return hipErrorInvalidDevice;
     PerDevice &d = dev_[dev];
     if (d.ev.size() < kPool) {
-      hipEvent_t ev;
-      e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
-      if (e != hipSuccess) return e;
+      hipEvent_t ev = nullptr;
+      {
+        EventFreeList &fl = event_free_list();
+        std::lock_guard<std::mutex> lock(fl.mu);
+        if (!fl.ev[dev].empty()) {
+          ev = fl.ev[dev].back();
+          fl.ev[dev].pop_back();
+        }
+      }
+      if (!ev) {
+        e = hipEventCreateWithFlags(&ev, hipEventDisableTiming);
+        if (e != hipSuccess) return e;
+      }
       d.ev.push_back(ev);
       *out = ev;
       return hipSuccess;
@@ -391,13 +432,12 @@ class EventPool {
   }
 
  private:
-  static constexpr size_t kPool = 512;
-  static constexpr int kMaxDevices = 16;
+  static constexpr size_t kPool = 64;
   struct PerDevice {
     std::vector<hipEvent_t> ev;
     size_t next = 0;
   };
-  PerDevice dev_[kMaxDevices];
+  PerDevice dev_[kEventDevices];
 };
 
 thread_local EventPool g_events;
@@ -600,6 +640,37 @@ osdp_status report_error(osdp_status status, const char *message) {
   t_last_error = message;
   return status;
 }
+
+namespace {
+struct DebugSwitch {
+  const char *name;
+  std::atomic<int32_t> DebugOptions::*field;
+  int32_t lo, hi;  // accepted values; the default of the field stands for "not set"
+};
+const DebugSwitch kSwitches[] = {
+    {"gemm_generic", &DebugOptions::gemm_generic, 0, 1}, {"tile", &DebugOptions::tile, -1, 3},
+    {"deep", &DebugOptions::deep, -1, 1},                {"split_launch", &DebugOptions::split_launch, -1, 1},
+    {"fwd_pair", &DebugOptions::fwd_pair, -1, 1},        {"poison_staging", &DebugOptions::poison_staging, 0, 1},
+};
+}  // namespace
+
+DebugOptions &debug_options() {
+  // initial values: OSDP_DEBUG_<NAME IN CAPITALS>=<integer> in the environment, read once
+  static DebugOptions *opt = [] {
+    DebugOptions *o = new DebugOptions;
+    for (const DebugSwitch &sw : kSwitches) {
+      std::string var = "OSDP_DEBUG_";
+      for (const char *c = sw.name; *c; ++c) var += static_cast<char>(std::toupper(static_cast<unsigned char>(*c)));
+      if (const char *v = std::getenv(var.c_str())) {
+        char *end = nullptr;
+        const long val = std::strtol(v, &end, 10);
+        if (end != v && *end == 0 && val >= sw.lo && val <= sw.hi) (o->*sw.field).store(static_cast<int32_t>(val));
+      }
+    }
+    return o;
+  }();
+  return *opt;
+}
 }  // namespace osdp
 
 // =============================================================================
@@ -695,11 +766,16 @@ static osdp_status forward(const osdp_shape *shape, const osdp_plan *plan, int32
   if ((st = fill_table(w_shards, r.N, "w_shards", &tab)) != OSDP_OK) return st;
   if ((st = check_replicas(r, rep, false)) != OSDP_OK) return st;
   if ((st = check_workspace(r, workspace, workspace_bytes)) != OSDP_OK) return st;
+  if ((st = device_ok()) != OSDP_OK) return st;
   if (no_tokens) return OSDP_OK;  // Y is empty: nothing is gathered, nothing is launched
 
   char *ws = static_cast<char *>(workspace);
   float *acc = reinterpret_cast<float *>(ws + r.slot_bytes * r.slots);  // row slices: Y's fp32 partial sum
   const int n = static_cast<int>(r.sub.size());
+  // Debug mode: a slot holds NaN patterns whenever no gathered slice is live in it, so that a GEMM that ran ahead
+  // of its gather, or a gather that overwrote a slice still being read, shows up as NaN (or wrong) outputs.
+  const bool poison = debug_options().poison_staging.load(std::memory_order_relaxed) != 0;
+  if (poison) OSDP_HIP(launch_fill16(ws, r.slot_bytes * r.slots, kPoison, sc));
   // A launch over two staged sub-slices holds both slots, so the next gather has to wait for it whatever stream it
   // is on: with such launches there is nothing to overlap, and everything goes on the compute stream, event-free.
   bool pairs = false;
@@ -731,6 +807,11 @@ static osdp_status forward(const osdp_shape *shape, const osdp_plan *plan, int32
               : weight_gemm(r, /*is_fwd=*/true, j0, j1, weights_of(r, rep, j0, slot_of[0]),
                             weights_of(r, rep, j1 - 1, slot_of[1]), X, ldx, Y, ldy, acc, li, r.fwd.size());
     OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_FWD, g, sc));
+    if (poison && gathered) {  // the slices this launch read are dead: poison their slots before they are handed back
+      if (joint) OSDP_HIP(launch_fill16(ws, r.slot_bytes * 2, kPoison, sc));
+      for (int j = j0; j < j1 && !joint; ++j)
+        if (!r.dp[j]) OSDP_HIP(launch_fill16(slot_of[j - j0], r.slot_bytes, kPoison, sc));
+    }
     if (overlap && gathered && j1 < n) {
       hipEvent_t ev;
       OSDP_HIP(g_events.get(&ev));
@@ -776,6 +857,7 @@ static osdp_status backward(const osdp_shape *shape, const osdp_plan *plan, int3
   if ((st = fill_table(reinterpret_cast<const void *const *>(dw_shards), r.N, "dw_shards", &gtab)) != OSDP_OK) return st;
   if ((st = check_replicas(r, rep, true)) != OSDP_OK) return st;
   if ((st = check_workspace(r, workspace, workspace_bytes)) != OSDP_OK) return st;
+  if ((st = device_ok()) != OSDP_OK) return st;
 
   if (no_tokens) {
     // dW = X^T . dY summed over no tokens is zero: the dW launches run with an empty reduction and store the
@@ -797,6 +879,8 @@ static osdp_status backward(const osdp_shape *shape, const osdp_plan *plan, int3
                        gather_estimate_us(static_cast<int64_t>(r.slot_bytes)) >= kWorthOverlappingUs;  // two slots of slot_bytes / 2 elements
   hipStream_t sg = overlap ? sp : sc;
   hipEvent_t released = nullptr;  // recorded on the compute stream when a group's last GEMM has been enqueued
+  const bool poison = debug_options().poison_staging.load(std::memory_order_relaxed) != 0;  // see forward()
+  if (poison) OSDP_HIP(launch_fill16(ws, r.slot_bytes * r.slots, kPoison, sc));
   if (overlap) OSDP_HIP(edge(sc, sp));
   size_t next_pass = 0, next_dw = 0;
   for (const Slice &grp : r.group) {
@@ -832,6 +916,7 @@ static osdp_status backward(const osdp_shape *shape, const osdp_plan *plan, int3
                               lddx, acc, next_pass, r.pass.size());
       OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DX, gx, sc));
     }
+    if (poison) OSDP_HIP(launch_fill16(ws, r.slot_bytes * r.slots, kPoison, sc));
     if (overlap && g1 < n) {
       OSDP_HIP(g_events.get(&released));
       OSDP_HIP(hipEventRecord(released, sc));
@@ -980,6 +1065,18 @@ osdp_status osdp_granularity_measure(const osdp_shape *shape, const void *X, int
   (void)hipEventDestroy(t0);
   (void)hipEventDestroy(t1);
   return st;
+}
+
+osdp_status osdp_debug_option(const char *name, int32_t value) {
+  if (!name) return fail(OSDP_ERR_INVALID_ARG, "option name is NULL");
+  for (const DebugSwitch &sw : kSwitches) {
+    if (std::strcmp(name, sw.name) != 0) continue;
+    if (value < sw.lo || value > sw.hi)
+      return fail(OSDP_ERR_INVALID_ARG, "debug option %s takes values %d to %d (got %d)", name, sw.lo, sw.hi, value);
+    (debug_options().*sw.field).store(value, std::memory_order_relaxed);
+    return OSDP_OK;
+  }
+  return fail(OSDP_ERR_INVALID_ARG, "unknown debug option %s", name);
 }
 
 osdp_status osdp_profile_begin(int32_t max_launches) {

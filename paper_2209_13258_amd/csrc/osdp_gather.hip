@@ -7,6 +7,8 @@
 // split, is the same copy with c0 = 0, w = O and a row offset).  The kernel is a
 // pure 16-byte-vector copy and is bound by HBM bandwidth: it reads I*w*2
 // bytes and writes I*w*2 bytes.
+#include <algorithm>
+
 #include "osdp_internal.h"
 
 namespace osdp {
@@ -61,7 +63,24 @@ __global__ __launch_bounds__(kThreads) void gather_slice_kernel(
   }
 }
 
+__global__ __launch_bounds__(kThreads) void fill16_kernel(uint4 *__restrict__ dst, uint64_t vecs, uint32_t pattern2) {
+  const uint4 v = {pattern2, pattern2, pattern2, pattern2};
+  const uint64_t step = static_cast<uint64_t>(gridDim.x) * kThreads;
+  for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * kThreads + threadIdx.x; i < vecs; i += step) dst[i] = v;
+}
+
 }  // namespace
+
+hipError_t launch_fill16(void *dst, size_t bytes, uint16_t pattern, hipStream_t stream) {
+  if (bytes == 0) return hipSuccess;
+  if (bytes % 16 || reinterpret_cast<uintptr_t>(dst) % 16) return hipErrorInvalidValue;
+  const uint64_t vecs = bytes / 16;
+  const uint64_t blocks = std::min<uint64_t>((vecs + kThreads - 1) / kThreads, 4096);
+  const uint32_t p2 = static_cast<uint32_t>(pattern) | (static_cast<uint32_t>(pattern) << 16);
+  hipLaunchKernelGGL(fill16_kernel, dim3(static_cast<unsigned>(blocks)), dim3(kThreads), 0, stream,
+                     static_cast<uint4 *>(dst), vecs, p2);
+  return hipGetLastError();
+}
 
 template <bool kRowBlock, int kUnroll>
 void launch_one(const ShardTable &shards, const ShardLayout &layout, int64_t r0, int64_t c0, uint64_t vecs_per_row, uint64_t total,

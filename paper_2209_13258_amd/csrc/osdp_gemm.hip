@@ -10,8 +10,6 @@
 // logical k = 8*q + e sits in lane group q, element e of both operands.  Tile
 // shape therefore never changes a result bit, which is what makes Y and dW of
 // a split operator bit-identical to the unsplit ones.
-#include <cstdlib>
-
 #include "gemm_common.h"
 #include "gemm_dma.h"
 
@@ -195,8 +193,8 @@ double tile_cost(int M, int N, int BM, int BN, double penalty) {
 }
 
 bool fast_path(int M, int N, int K, int k_split, int n_split) {
-  const char *force = getenv("OSDP_GEMM");  // testing: "generic" forces the bounds-checked kernel
-  return !(force && force[0] == 'g') && M % 128 == 0 && N % 128 == 0 && K > 0 && K % 64 == 0 && k_split % 64 == 0 &&
+  const bool generic = debug_options().gemm_generic.load(std::memory_order_relaxed) != 0;  // testing: the bounds-checked kernel
+  return !generic && M % 128 == 0 && N % 128 == 0 && K > 0 && K % 64 == 0 && k_split % 64 == 0 &&
          n_split % 128 == 0;
 }
 
@@ -244,25 +242,25 @@ hipError_t launch_best(const GemmParams &p, hipStream_t stream) {
   constexpr int kind = layout_kind(kAK, kBK);
   if (fast_path(p.M, p.N, p.K, p.k_split, p.n_split)) {
     int best = best_tile(p.M, p.N, p.n_split, kind, nullptr);
-    const char *t = getenv("OSDP_TILE");  // testing: force tile 0..3 when it divides the problem
-    if (t && t[0] >= '0' && t[0] <= '3') {
-      const TileShape &f = kTiles[t[0] - '0'];
-      if (p.M % f.bm == 0 && p.N % f.bn == 0 && p.n_split % f.bn == 0) best = t[0] - '0';
+    const int forced = debug_options().tile.load(std::memory_order_relaxed);  // testing: tile 0..3 when it divides the problem
+    const bool force = forced >= 0 && forced <= 3;
+    if (force) {
+      const TileShape &f = kTiles[forced];
+      if (p.M % f.bm == 0 && p.N % f.bn == 0 && p.n_split % f.bn == 0) best = forced;
     }
     // A dX launch with a short reduction whose fp32 partial sum comes from or goes to memory is bound by that
     // traffic, and with only a round or two of large tiles every CU loads, computes and stores in step with the
     // others: two smaller workgroups per CU overlap one's loads and stores with the other's MFMAs (8192 x 4096 with
     // K = 256: 62 -> 54 us; with 8 rounds of large tiles, 4096 x 32768, the large tile stays 7 % ahead).
     if (kind == 2 && (kAccIn || kEpi == static_cast<int>(Epilogue::kF32Workspace)) && p.K <= kShortK && best == 0 &&
-        static_cast<long>(p.M / 256) * (p.N / 256) <= 2 * kCUs && !(t && t[0] >= '0' && t[0] <= '3')) {
+        static_cast<long>(p.M / 256) * (p.N / 256) <= 2 * kCUs && !force) {
       if (p.N % 256 == 0 && p.n_split % 256 == 0) best = 2;
       else if (p.n_split % 128 == 0) best = 1;
     }
     // A launch of at most one tile per CU cannot hide the latency of its loads behind a second workgroup: it gets
     // the whole LDS for a deeper pipeline instead (twice the bytes in flight).
-    const char *dp = getenv("OSDP_DEEP");  // testing: "0" keeps the shallow pipelines
     const bool deep = best > 0 && static_cast<long>(p.M / kTiles[best].bm) * (p.N / kTiles[best].bn) <= kCUs &&
-                      !(dp && dp[0] == '0');
+                      debug_options().deep.load(std::memory_order_relaxed) != 0;  // testing: 0 keeps the shallow pipelines
     switch (best) {
       case 0:
         if (kind == 0) return launch_dma<256, 256, 64, 128, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
@@ -319,8 +317,10 @@ double plan_launches(int M, int N, int K, int kind, int *axis, int *cut) {
   *axis = -1;
   *cut = 0;
   if (best_tile(M, N, 0, kind, &whole) < 0) return 0.0;
-  const char *off = getenv("OSDP_SPLIT_LAUNCH");  // testing: "0" keeps every problem in one launch
-  if ((off && off[0] == '0') || getenv("OSDP_TILE") || M % 256 || N % 256) return whole;
+  // testing: split_launch = 0 keeps every problem in one launch, as does a forced tile shape
+  if (debug_options().split_launch.load(std::memory_order_relaxed) == 0 ||
+      debug_options().tile.load(std::memory_order_relaxed) >= 0 || M % 256 || N % 256)
+    return whole;
   const int tm = M / 256, tn = N / 256;
   const double between = 1.0e7 / K;  // about 5 us from one launch to the next, in the cost's units of tile area
   double best = 0.95 * whole;        // only for a clear gain
@@ -388,6 +388,23 @@ double gemm_estimate_us(int64_t M, int64_t N, int64_t K) {
   const double tiles = static_cast<double>((M + GBM - 1) / GBM) * static_cast<double>((N + GBN - 1) / GBN);
   const double rounds = static_cast<double>(static_cast<long>((tiles + kCUs - 1) / kCUs));
   return rounds * GBM * GBN * 4.0 * 2.0 * static_cast<double>(K) / 4.0e6 + 6.0;  // the checked kernel is about 4x slower per tile
+}
+
+hipError_t check_device() {
+  static std::atomic<int8_t> verdict[kMaxDevices] = {};  // 0: not looked at, 1: fits, -1: does not
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  int8_t v = verdict[dev].load(std::memory_order_relaxed);
+  if (v == 0) {
+    int cus = 0, xcds = 0;
+    if ((e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+    if ((e = hipDeviceGetAttribute(&xcds, hipDeviceAttributeNumberOfXccs, dev)) != hipSuccess) return e;
+    v = (cus == kCUs && xcds == kXcds) ? 1 : -1;
+    verdict[dev].store(v, std::memory_order_relaxed);
+  }
+  return v > 0 ? hipSuccess : hipErrorInvalidDevice;
 }
 
 hipError_t launch_gemm(const GemmProblem &q, hipStream_t stream) {

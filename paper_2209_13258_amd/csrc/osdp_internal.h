@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "osdp.h"
 
 namespace osdp {
@@ -72,6 +74,26 @@ double gemm_estimate_us(int64_t M, int64_t N, int64_t K);
 // Ws[r, c] = W[r0 + r, c0 + c] for r < rows, c < w; Ws dense row-major [rows x w].
 hipError_t launch_gather(const ShardTable &shards, const ShardLayout &layout, int64_t r0, int64_t rows, int64_t c0,
                          int64_t w, void *staging, hipStream_t stream);
+
+// Fills `bytes` (a multiple of 16) at dst (16-byte aligned) with the 16-bit pattern: the debug mode that poisons
+// released staging slots.  A kernel, not a memset node, so that a captured graph replays it correctly.
+hipError_t launch_fill16(void *dst, size_t bytes, uint16_t pattern, hipStream_t stream);
+
+// Test and debug switches (osdp_debug_option), process-wide.  Each is read with one relaxed atomic load where it
+// applies; the environment is consulted once, when the library is loaded, for their initial values.
+struct DebugOptions {
+  std::atomic<int32_t> gemm_generic{0};    // 1: every GEMM runs on the bounds-checked kernel
+  std::atomic<int32_t> tile{-1};           // 0..3: force that tile shape where it divides the problem
+  std::atomic<int32_t> deep{-1};           // 0: launches of at most one tile per CU keep the shallow pipelines
+  std::atomic<int32_t> split_launch{-1};   // 0: no whole-rounds + remainder launches
+  std::atomic<int32_t> fwd_pair{-1};       // 0: the forward never pairs staged slices; 1: whenever the kernel can
+  std::atomic<int32_t> poison_staging{0};  // 1: staging slots hold NaN patterns whenever no gathered slice is live in them
+};
+DebugOptions &debug_options();
+
+// The kernels' tile maps and cost estimates are written for the MI355X's 256 CUs in 8 XCDs; hipErrorInvalidDevice
+// when the current device is something else.  Checked once per device.
+hipError_t check_device();
 
 // Stores the message as the calling thread's last error (osdp_last_error) and returns `status`.
 osdp_status report_error(osdp_status status, const char *message);

@@ -16,6 +16,24 @@ def H():
     return gpu_harness
 
 
+DEBUG_DEFAULTS = {"gemm_generic": 0, "tile": -1, "deep": -1, "split_launch": -1, "fwd_pair": -1, "poison_staging": 0}
+
+
+@pytest.fixture
+def debug():
+    """Sets the library's process-wide debug switches for one test and puts them back afterwards."""
+    import paper_2209_13258_amd as osdp
+    touched = set()
+
+    def set_option(name, value):
+        touched.add(name)
+        osdp.osdp_debug_option(name, int(value))
+
+    yield set_option
+    for name in touched:
+        osdp.osdp_debug_option(name, DEBUG_DEFAULTS[name])
+
+
 def _announce(*what):
     print("CASE", *what, flush=True)
 
@@ -97,11 +115,11 @@ def test_shard_padding_is_never_touched(H, oracle):
 @pytest.mark.parametrize("pair", ["0", "1"])
 @pytest.mark.parametrize("T,I,O,N", [(300, 264, 640, 4), (128, 256, 1024, 2), (1024, 512, 2048, 8),
                                      (256, 256, 640, 4)])  # last: k=1 takes the unchecked kernel, k=2 (320 columns) the checked one
-def test_split_is_bit_identical_to_unsplit(H, T, I, O, N, pair, monkeypatch):
+def test_split_is_bit_identical_to_unsplit(H, T, I, O, N, pair, debug):
     """Every k, staging mode and stream choice; forward both with one launch per slice and with
     two staged slices per launch (the library's own choice is an estimate, so both are forced here)."""
     _announce("bit-identity", T, I, O, N, "pair", pair)
-    monkeypatch.setenv("OSDP_FWD_PAIR", pair)
+    debug("fwd_pair", pair)
     import paper_2209_13258_amd as osdp
     d = wl.small_case(14, T, I, O, N)
     op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
@@ -165,6 +183,33 @@ def test_repeated_calls_reuse_workspace_safely(H, oracle):
 
 
 # ------------------------------------------------ full-size configs, sampled
+def _edge_entries(n, cuts):
+    """Indices just below, at and just above every cut of [0, n), plus the corners of the first 256 x 256 tile
+    and the last two entries."""
+    e = [c + d for c in cuts for d in (-1, 0, 1)] + [0, 1, 127, 128, 255, 256, n - 2, n - 1]
+    return np.unique(np.clip(np.array(e), 0, n - 1))
+
+
+def _check_samples(H, oracle, label, d, got, T, I, O, N, k, rows, g, n_samples):
+    """Random entries of Y, dX and dW plus every entry whose row / column lies at a slice, shard or tile edge
+    paired with every such column / row (whole edge-by-edge blocks), each against the oracle's own dot product."""
+    cuts_o = [] if rows else [j * O // k for j in range(k + 1)]
+    cuts_i = [s * I // N for s in range(N + 1)] + ([j * I // k for j in range(k + 1)] if rows else [])
+    edges_o, edges_i, edges_t = _edge_entries(O, cuts_o), _edge_entries(I, cuts_i), _edge_entries(T, [])
+
+    def pairs(n0, n1, e0, e1):
+        r = np.concatenate([g.integers(0, n0, n_samples), np.repeat(e0, e1.size)])
+        c = np.concatenate([g.integers(0, n1, n_samples), np.tile(e1, e0.size)])
+        return r, c
+
+    r, c = pairs(T, O, edges_t, edges_o)
+    H.assert_close(f"{label} Y", got["Y"][r, c], oracle.sample_y(d["X"], d["W_shards"], O, r, c))
+    r, c = pairs(T, I, edges_t, edges_i)
+    H.assert_close(f"{label} dX", got["dX"][r, c], oracle.sample_dx(d["dY"], d["W_shards"], I, r, c))
+    r, c = pairs(I, O, edges_i, edges_o)
+    H.assert_close(f"{label} dW", got["dW"][r, c], oracle.sample_dw(d["X"], d["dY"], r, c))
+
+
 def _sampled_check(H, oracle, cfg, op_index, op, T, N, k, plan=None, n_samples=100_000, layer=0):
     I, O = op.I, op.O
     _announce("config", cfg, op.name, T, I, O, N, k)
@@ -178,26 +223,8 @@ def _sampled_check(H, oracle, cfg, op_index, op, T, N, k, plan=None, n_samples=1
     sc.synchronize()
     got = dev.results()
     g = np.random.default_rng(cfg * 1000 + op_index)
-    keff = max(k, 1)
-    # random entries plus entries that straddle slice and shard boundaries
-    edges_o = np.unique(np.clip(np.concatenate([[j * O // keff + e for e in (-1, 0, 1)] for j in range(keff + 1)]), 0, O - 1))
-    edges_i = np.unique(np.clip(np.concatenate([[s * I // N + e for e in (-1, 0, 1)] for s in range(N + 1)]), 0, I - 1))
-    edges_t = np.unique(np.clip(np.array([0, 1, 127, 128, 255, 256, T - 2, T - 1]), 0, T - 1))
-
-    def pairs(n0, n1, e0, e1):
-        r = np.concatenate([g.integers(0, n0, n_samples), np.repeat(e0, e1.size)])
-        c = np.concatenate([g.integers(0, n1, n_samples), np.tile(e1, e0.size)])
-        return r, c
-
-    r, c = pairs(T, O, edges_t, edges_o)
-    ref = oracle.sample_y(d["X"], d["W_shards"], O, r, c)
-    _sample_close(H, f"cfg{cfg} {op.name} Y", got["Y"][r, c], ref)
-    r, c = pairs(T, I, edges_t, edges_i)
-    ref = oracle.sample_dx(d["dY"], d["W_shards"], I, r, c)
-    _sample_close(H, f"cfg{cfg} {op.name} dX", got["dX"][r, c], ref)
-    r, c = pairs(I, O, edges_i, edges_o)
-    ref = oracle.sample_dw(d["X"], d["dY"], r, c)
-    _sample_close(H, f"cfg{cfg} {op.name} dW", got["dW"][r, c], ref)
+    rows = plan is not None and _cuts_rows(plan, 0, I, O)
+    _check_samples(H, oracle, f"cfg{cfg} {op.name}", d, got, T, I, O, N, max(k, 1), rows, g, n_samples)
     # properties that hold at any size: nothing left unwritten (outputs were NaN-poisoned)
     for name in ("Y", "dX", "dW"):
         assert not np.isnan(H.widen(got[name][:: max(1, got[name].shape[0] // 512)])).any(), f"{name} has unwritten entries"
@@ -223,6 +250,13 @@ def test_config3_layer_with_plan(H, oracle):
         _sampled_check_plan(H, oracle, 3, n, op, w, plan)
 
 
+def _cuts_rows(plan, n, I, O):
+    """Whether the plan cuts operator n along W's rows."""
+    import paper_2209_13258_amd as osdp
+    dim = plan.split_dim_per_op[n] if plan.split_dim_per_op is not None else osdp.OSDP_SPLIT_OUT_FEATURES
+    return dim == osdp.OSDP_SPLIT_IN_FEATURES or (dim == osdp.OSDP_SPLIT_LONGER and I > O)
+
+
 def _sampled_check_plan(H, oracle, cfg, n, op, w, plan):
     """Runs operator n under the plan vector (k taken from plan.k_per_op[n])."""
     import paper_2209_13258_amd as osdp
@@ -238,20 +272,26 @@ def _sampled_check_plan(H, oracle, cfg, n, op, w, plan):
     sc.synchronize()
     got = dev.results()
     g = np.random.default_rng(cfg * 1000 + n)
-    ns = 50_000
-    r, c = g.integers(0, w.T, ns), g.integers(0, O, ns)
-    H.assert_close(f"cfg{cfg} {op.name} Y", got["Y"][r, c], oracle.sample_y(d["X"], d["W_shards"], O, r, c))
-    r, c = g.integers(0, w.T, ns), g.integers(0, I, ns)
-    H.assert_close(f"cfg{cfg} {op.name} dX", got["dX"][r, c], oracle.sample_dx(d["dY"], d["W_shards"], I, r, c))
-    r, c = g.integers(0, I, ns), g.integers(0, O, ns)
-    H.assert_close(f"cfg{cfg} {op.name} dW", got["dW"][r, c], oracle.sample_dw(d["X"], d["dY"], r, c))
+    rows = _cuts_rows(plan, n, I, O)
+    _check_samples(H, oracle, f"cfg{cfg} {op.name}", d, got, w.T, I, O, w.N, max(plan.k_per_op[n], 1), rows, g, 50_000)
     # the plan's k must have been used: peak staging = 2 slots of |W| / k (or one slot when k = 1)
     k = plan.k_per_op[n]
     _, peak = osdp.osdp_split_linear_workspace_bytes(w.T, I, O, w.N, 0, True, plan, n)
-    assert peak == oracle.peak_staging_bytes(I, O, k, 2, 2)
+    law = oracle.peak_staging_bytes_rows if rows else oracle.peak_staging_bytes
+    assert peak == law(I, O, k, 2, 2)
 
 
-@pytest.mark.parametrize("k", [4, 16])
+def test_config3_layer_cut_along_the_longer_dimension(H, oracle):
+    """The plan vector of config 3 with every operator cut along its longer weight dimension (columns for qkv and
+    up, rows for down), the variant the benchmark reports beside the column slices."""
+    import paper_2209_13258_amd as osdp
+    w = wl.workload(3)
+    plan = osdp.Plan([op.k for op in w.ops], split_dim_per_op=[osdp.OSDP_SPLIT_LONGER] * len(w.ops))
+    for n, op in enumerate(w.ops):
+        _sampled_check_plan(H, oracle, 3, n, op, w, plan)
+
+
+@pytest.mark.parametrize("k", [4, 8, 16])
 def test_config4_wide_operator(H, oracle, k):
     import paper_2209_13258_amd as osdp
     w = wl.workload(4, k)
@@ -294,12 +334,7 @@ def test_config5_layer_stack(H, oracle):
         op, d = w.ops[n], data[layer, n]
         _announce("config 5 check", layer, op.name)
         got = dev.results()
-        r, c = g.integers(0, w.T, ns), g.integers(0, op.O, ns)
-        H.assert_close("Y", got["Y"][r, c], oracle.sample_y(d["X"], d["W_shards"], op.O, r, c))
-        r, c = g.integers(0, w.T, ns), g.integers(0, op.I, ns)
-        H.assert_close("dX", got["dX"][r, c], oracle.sample_dx(d["dY"], d["W_shards"], op.I, r, c))
-        r, c = g.integers(0, op.I, ns), g.integers(0, op.O, ns)
-        H.assert_close("dW", got["dW"][r, c], oracle.sample_dw(d["X"], d["dY"], r, c))
+        _check_samples(H, oracle, f"cfg5 layer {layer} {op.name}", d, got, w.T, op.I, op.O, w.N, max(op.k, 1), False, g, ns)
 
 
 # ------------------------------ the split along W's rows (the reduction dimension of the forward product)
@@ -369,12 +404,12 @@ def test_row_split_fwd_bwd_match_oracle(H, oracle, T, I, O, N, k):
 @pytest.mark.parametrize("pair", ["0", "1"])
 @pytest.mark.parametrize("T,I,O,N", [(300, 640, 264, 4), (128, 1024, 256, 2), (1024, 2048, 512, 8),
                                      (256, 640, 256, 4)])  # last: k=1 takes the unchecked kernel, k=2 (320 rows) the checked one for dW
-def test_row_split_is_bit_identical_to_unsplit(H, T, I, O, N, pair, monkeypatch):
+def test_row_split_is_bit_identical_to_unsplit(H, T, I, O, N, pair, debug):
     """dW and dX are concatenated, so they equal the unsplit result bit for bit for every k, staging mode,
     stream choice and launch grouping; Y is a sum carried in the fp32 accumulator and is bit-identical when
     the slice height is a multiple of the MFMA's 16-deep K step."""
     _announce("bit-identity rows", T, I, O, N, "pair", pair)
-    monkeypatch.setenv("OSDP_FWD_PAIR", pair)
+    debug("fwd_pair", pair)
     import paper_2209_13258_amd as osdp
     d = wl.small_case(33, T, I, O, N)
     op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
@@ -676,14 +711,14 @@ def test_config2_one_of_four_slices_zdp(H, oracle, rows):
 
 # ------------------------------------------------ every tile shape of the unchecked kernel
 @pytest.mark.parametrize("T,I,O,N", [(512, 512, 768, 4), (256, 1024, 256, 8)])
-def test_every_tile_shape_gives_the_bits_of_the_checked_kernel(H, oracle, T, I, O, N, monkeypatch):
+def test_every_tile_shape_gives_the_bits_of_the_checked_kernel(H, oracle, T, I, O, N, debug):
     """The host picks tile shapes by cost, so a test shape may never meet some of them: each of the four
     (with its own K block, LDS stage count and launch bounds per operand layout and pipeline depth) is forced in turn, for
     the unsplit operator and for splits in both dimensions, and must reproduce the bounds-checked kernel
     bit for bit (and, through it, the oracle)."""
     import paper_2209_13258_amd as osdp
     d = wl.small_case(71, T, I, O, N)
-    monkeypatch.setenv("OSDP_GEMM", "generic")
+    debug("gemm_generic", 1)
     ref_op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
     ref_op.fwd(1)
     ref_op.bwd(1)
@@ -691,13 +726,13 @@ def test_every_tile_shape_gives_the_bits_of_the_checked_kernel(H, oracle, T, I, 
     want = oracle.linear(d["X"], d["W_shards"], O, dY=d["dY"])
     for name in ("Y", "dX", "dW"):
         H.assert_close(name, ref[name], want[name])
-    monkeypatch.delenv("OSDP_GEMM")
+    debug("gemm_generic", 0)
     sc, sp = H.streams()
     # these shapes give every launch at most one tile per CU, where the library would use its deep-pipeline
     # variants of tiles 1..3 only: both pipelines of each tile are forced in turn
     for tile, deep in (("0", "1"), ("1", "0"), ("1", "1"), ("2", "0"), ("2", "1"), ("3", "0"), ("3", "1")):
-        monkeypatch.setenv("OSDP_TILE", tile)
-        monkeypatch.setenv("OSDP_DEEP", deep)
+        debug("tile", tile)
+        debug("deep", deep)
         for k, dim in ((1, 0), (2, 0), (2, 1)):
             _announce("tile", tile, "deep", deep, T, I, O, N, "k", k, "dim", dim)
             plan = osdp.Plan([k], staging=osdp.OSDP_STAGING_DOUBLE, split_dim_per_op=[dim])
@@ -757,12 +792,12 @@ def test_padded_leading_dimensions_and_many_shards(H, oracle, T, I, O, N, k, dim
 
 # ------------------------------------------------ capture into a HIP graph
 @pytest.mark.parametrize("pair", ["0", "1"])
-def test_calls_can_be_captured_into_a_graph_and_replayed(H, pair, monkeypatch):
+def test_calls_can_be_captured_into_a_graph_and_replayed(H, pair, debug):
     """A forward + backward captured on the compute stream (one-stream and two-stream pipelines, the latter with
     its cross-stream events inside the capture) replays to the bits of the eager calls, every time, with eager work
     and new inputs between the replays."""
     import paper_2209_13258_amd as osdp
-    monkeypatch.setenv("OSDP_FWD_PAIR", pair)   # "0": the forward overlaps gathers on the copy stream; "1": one stream
+    debug("fwd_pair", pair)   # "0": the forward overlaps gathers on the copy stream; "1": one stream
     T, I, O, N, k = 512, 2048, 4096, 8, 2       # 8 MB slices: the backward uses the copy stream too
     d = wl.small_case(91, T, I, O, N)
     op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
@@ -943,7 +978,7 @@ def test_two_host_threads_call_concurrently(H, oracle):
 # ------------------------------------------------ one problem run as two launches
 @pytest.mark.parametrize("T,I,O", [(4096, 256, 4352),    # forward: 16 x 17 large tiles, cut along the columns
                                    (256, 4352, 4096)])   # dW: 17 x 16 large tiles, cut along the rows (shard-major store)
-def test_whole_rounds_plus_remainder_launches_keep_the_bits(H, oracle, T, I, O, monkeypatch):
+def test_whole_rounds_plus_remainder_launches_keep_the_bits(H, oracle, T, I, O, debug):
     """A GEMM whose large tiles fill the CUs once plus a little is run as two launches (whole rounds, remainder):
     same bits as the single launch, and the oracle's values."""
     N = 8
@@ -952,7 +987,7 @@ def test_whole_rounds_plus_remainder_launches_keep_the_bits(H, oracle, T, I, O, 
     ref = oracle.linear(d["X"], d["W_shards"], O, dY=d["dY"])
     res = {}
     for flag in ("0", "1"):
-        monkeypatch.setenv("OSDP_SPLIT_LAUNCH", flag)
+        debug("split_launch", -1 if flag == "1" else 0)
         for k in (1, 2):
             op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
             op.fwd(k)
@@ -962,3 +997,41 @@ def test_whole_rounds_plus_remainder_launches_keep_the_bits(H, oracle, T, I, O, 
         H.assert_close(name, res["1", 1][name], ref[name])
         for k in (1, 2):
             assert np.array_equal(res["0", k][name], res["1", k][name]), f"{name} differs with two launches (k {k})"
+
+
+# ------------------------------------------------ debug mode: poisoned staging slots
+@pytest.mark.parametrize("pair", [0, 1])
+@pytest.mark.parametrize("rows", [False, True])
+def test_poisoned_staging_slots_change_nothing(H, oracle, rows, pair, debug):
+    """With the staging slots filled with NaN patterns whenever no gathered slice is live in them, a GEMM that ran
+    ahead of its gather or a gather that landed on a slice still in use would put NaN (or wrong values) into the
+    outputs: every staging mode, one and two streams, both forward schedules, repeated calls on one workspace."""
+    import paper_2209_13258_amd as osdp
+    T, I, O, N = 512, 1024, 2048, 8
+    d = wl.small_case(131, T, I, O, N)
+    ref = oracle.linear(d["X"], d["W_shards"], O, dY=d["dY"])
+    dim = osdp.OSDP_SPLIT_IN_FEATURES if rows else osdp.OSDP_SPLIT_OUT_FEATURES
+    base_op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+    base_op.fwd(1)
+    base_op.bwd(1)
+    base = base_op.results()
+    debug("poison_staging", 1)
+    debug("fwd_pair", pair)
+    sc, sp = H.streams()
+    for k in (2, 4, 8):
+        for mode in (osdp.OSDP_STAGING_SINGLE, osdp.OSDP_STAGING_DOUBLE, osdp.OSDP_STAGING_HALF):
+            for streams in ((sc, sp), (sc, None)):
+                _announce("poison", "rows" if rows else "columns", "pair", pair, "k", k, "mode", mode, "two streams", streams[1] is not None)
+                plan = osdp.Plan([k], staging=mode, split_dim_per_op=[dim])
+                op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+                torch.cuda.synchronize()
+                with torch.cuda.stream(sc):
+                    for _ in range(3):  # back to back on one workspace: the next call's gathers meet this call's GEMMs
+                        op.fwd(k, plan=plan, streams=streams)
+                        op.bwd(k, plan=plan, streams=streams)
+                sc.synchronize()
+                got = op.results()
+                for name in ("Y", "dX", "dW"):
+                    assert np.array_equal(got[name], base[name]), f"{name} differs from the unsplit result"
+    for name in ("Y", "dX", "dW"):
+        H.assert_close(name, base[name], ref[name])

@@ -285,6 +285,35 @@ def test_argument_errors_are_raised_before_anything_is_enqueued():
     assert e.value.status == -2  # misaligned staging
 
 
+def test_debug_options_take_known_names_and_values_only():
+    for name, good, bad in (("gemm_generic", (0, 1, 0), (-1, 2)), ("tile", (0, 3, -1), (-2, 4)), ("deep", (0, -1), (2,)),
+                            ("split_launch", (0, -1), (-2,)), ("fwd_pair", (0, 1, -1), (2,)),
+                            ("poison_staging", (1, 0), (-1, 2))):
+        for v in good:   # the last good value is the default: the switches are process-wide
+            osdp.osdp_debug_option(name, v)
+        for v in bad:
+            with pytest.raises(osdp.OsdpError) as e:
+                osdp.osdp_debug_option(name, v)
+            assert e.value.status == osdp.binding.OSDP_ERR_INVALID_ARG
+    with pytest.raises(osdp.OsdpError):
+        osdp.osdp_debug_option("no_such_switch", 0)
+
+
+def test_forward_launch_plan_follows_the_pairing_switch():
+    """The pairing switch changes the forward launch plan, and with it the fp32 partial sum a row-slice forward
+    needs between launches: the size query answers for the switch's current value."""
+    T, I, O, N, k = 8192, 4096, 1024, 8, 2
+    plan = osdp.Plan([k], staging=osdp.OSDP_STAGING_DOUBLE, split_dim_per_op=[osdp.OSDP_SPLIT_IN_FEATURES])
+    try:
+        osdp.osdp_debug_option("fwd_pair", 1)
+        paired, _ = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, False, plan)
+        osdp.osdp_debug_option("fwd_pair", 0)
+        single, _ = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, False, plan)
+    finally:
+        osdp.osdp_debug_option("fwd_pair", -1)
+    assert single == paired + T * O * 4   # two accumulating launches carry Y's partial sum through the workspace
+
+
 def test_profile_end_without_begin_is_an_error():
     with pytest.raises(osdp.OsdpError):
         osdp.osdp_profile_end()
