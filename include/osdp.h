@@ -46,7 +46,8 @@
  *   - The library never allocates device memory.  The caller owns all buffers,
  *     including the workspace; the library owns only a few HIP events (at most 64
  *     per calling host thread and device; a thread that ends hands its events to
- *     the threads that start later).
+ *     the threads that start later) and one fixed scratch array per device for
+ *     osdp_split_linear_fwd_noalloc.
  *   - Threads: any host thread may call; calls from different threads share no
  *     state in the library.  Two calls that use the same workspace or outputs
  *     must be ordered by the caller's streams like any other GPU work.
@@ -193,6 +194,22 @@ OSDP_API osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_p
                                   const void *X, int64_t ldx, const void *const *w_shards,
                                   void *Y, int64_t ldy, void *workspace, size_t workspace_bytes,
                                   void *stream_compute, void *stream_copy);
+
+/* For callers that cannot allocate device memory or hand over a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): osdp_split_linear_fwd on one
+ * stream, with the staging slots and the fp32 partial sum kept in a fixed array of
+ * OSDP_NOALLOC_SCRATCH_BYTES that is part of the library's device code (one copy per GPU, held
+ * until the process ends).  Same arguments, layouts, results (bit for bit) and errors as
+ * osdp_split_linear_fwd with stream_copy = NULL; nothing is allocated, no event is created.
+ * OSDP_ERR_WORKSPACE, before anything is enqueued, when the plan needs more than the array holds
+ * (what osdp_split_linear_workspace_bytes reports for the forward pass): raise k.
+ * All calls on one GPU share that GPU's array, which keeps the previous call's contents (every byte a
+ * call reads it has written first, so nothing needs clearing): calls on different streams or from
+ * different threads that overlap in time on one GPU race and must be ordered by the caller. */
+#define OSDP_NOALLOC_SCRATCH_BYTES ((size_t)64 << 20)
+OSDP_API osdp_status osdp_split_linear_fwd_noalloc(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index,
+                                                   const void *X, int64_t ldx, const void *const *w_shards,
+                                                   void *Y, int64_t ldy, void *stream);
 
 /* Section 3.3 applied to the backward pass (the weights are gathered again,
  * Section 2.2): for j = 0..k-1, dW[:, c0_j:c1_j] = X^T . dY[:, c0_j:c1_j]

@@ -28,6 +28,8 @@ OSDP_SPLIT_OUT_FEATURES = 0
 OSDP_SPLIT_IN_FEATURES = 1
 OSDP_SPLIT_LONGER = 2
 
+OSDP_NOALLOC_SCRATCH_BYTES = 64 << 20
+
 OSDP_KERNEL_GATHER = 0
 OSDP_KERNEL_GEMM_FWD = 1
 OSDP_KERNEL_GEMM_DW = 2
@@ -38,7 +40,7 @@ KERNEL_NAMES = ("gather", "gemm_fwd", "gemm_dw", "gemm_dx")
 EXPORTS = (
     "osdp_slice_range", "osdp_row_slice_range", "osdp_split_linear_gather_slice",
     "osdp_split_linear_gather_row_slice", "osdp_split_linear_workspace_bytes", "osdp_split_linear_fwd",
-    "osdp_split_linear_bwd", "osdp_split_linear_fwd_mixed", "osdp_split_linear_bwd_mixed",
+    "osdp_split_linear_bwd", "osdp_split_linear_fwd_noalloc", "osdp_split_linear_fwd_mixed", "osdp_split_linear_bwd_mixed",
     "osdp_granularity_candidates", "osdp_granularity_measure",
     "osdp_granularity_select", "osdp_cost_model", "osdp_plan_search", "osdp_profile_begin", "osdp_profile_end",
     "osdp_debug_option", "osdp_strerror", "osdp_last_error", "osdp_version",
@@ -106,6 +108,8 @@ def _load() -> ctypes.CDLL:
     lib.osdp_split_linear_workspace_bytes.argtypes = [shp, pln, i32, i32, ctypes.POINTER(ctypes.c_size_t),
                                                       ctypes.POINTER(ctypes.c_size_t)]
     lib.osdp_split_linear_fwd.argtypes = [shp, pln, i32, vp, i64, vp, vp, i64, vp, ctypes.c_size_t, vp, vp]
+    lib.osdp_split_linear_fwd_noalloc.argtypes = [shp, pln, i32, vp, i64, vp, vp, i64, vp]
+    lib.osdp_split_linear_fwd_noalloc.restype = ctypes.c_int
     lib.osdp_split_linear_bwd.argtypes = [shp, pln, i32, vp, i64, vp, i64, vp, vp, i64, vp, vp,
                                           ctypes.c_size_t, vp, vp]
     lib.osdp_split_linear_fwd_mixed.argtypes = [shp, pln, i32, vp, i64, vp, vp, i64, vp, i64, vp, ctypes.c_size_t, vp, vp]
@@ -245,6 +249,16 @@ def osdp_split_linear_fwd(X, w_shards, Y, k, workspace, *, plan: Optional[Plan] 
                                      _ptrs(w_shards), int(Y.data_ptr()), Y.stride(0),
                                      int(workspace.data_ptr()), workspace.numel() * workspace.element_size(),
                                      _stream(stream_compute), _stream(stream_copy)))
+
+
+def osdp_split_linear_fwd_noalloc(X, w_shards, Y, k, *, plan: Optional[Plan] = None, op_index: int = 0, stream=None):
+    """The forward on one stream with the library's built-in scratch array in place of a workspace."""
+    T, I = X.shape
+    O = Y.shape[1]
+    shape = _shape(T, I, O, len(w_shards), k)
+    pref, _keep = _plan_ref(plan)
+    _check(lib.osdp_split_linear_fwd_noalloc(ctypes.byref(shape), pref, op_index, int(X.data_ptr()), X.stride(0),
+                                             _ptrs(w_shards), int(Y.data_ptr()), Y.stride(0), _stream(stream)))
 
 
 def osdp_split_linear_bwd(X, dY, w_shards, dX, dw_shards, k, workspace, *, plan: Optional[Plan] = None,

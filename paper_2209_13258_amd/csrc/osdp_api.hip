@@ -831,6 +831,51 @@ osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_plan *plan
                  workspace_bytes, stream_compute, stream_copy);
 }
 
+// ---- forward without a caller workspace ------------------------------------------------------------------------
+// The staging slots (and, for row slices, the fp32 partial sum) live in a fixed array in device memory that is
+// part of the library's code object: nothing is allocated, by the library or by the caller.  Every device has
+// its own copy of the array at its own address, which is looked up once per device.
+constexpr size_t kScratchBytes = OSDP_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kEventDevices] = {};  // device address of `scratch` per device, nullptr: not looked up yet
+
+osdp_status scratch_of_current_device(void **out) {
+  int dev = 0;
+  OSDP_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kEventDevices) return fail(OSDP_ERR_UNSUPPORTED, "device index %d is beyond the %d the library tracks", dev, kEventDevices);
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    OSDP_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));  // the address on the device that is current now
+    if (!p) return fail(OSDP_ERR_HIP, "hipGetSymbolAddress returned a null address for the scratch array");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return OSDP_OK;
+}
+}  // namespace
+
+osdp_status osdp_split_linear_fwd_noalloc(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, const void *X,
+                                          int64_t ldx, const void *const *w_shards, void *Y, int64_t ldy, void *stream) {
+  // one stream: no events are needed (none is created), and the size is known before anything is enqueued
+  Resolved r;
+  osdp_status st = resolve(shape, plan, op_index, /*overlap_possible=*/false, /*is_bwd=*/false, &r);
+  if (st != OSDP_OK) return st;
+  const size_t need = workspace_total(r);
+  if (need > kScratchBytes)
+    return fail(OSDP_ERR_WORKSPACE,
+                "this operator and plan need %zu bytes of staging and partial sums, the built-in scratch array holds %zu: "
+                "raise the granularity or use osdp_split_linear_fwd with a workspace",
+                need, kScratchBytes);
+  void *ws = nullptr;
+  if ((st = scratch_of_current_device(&ws)) != OSDP_OK) return st;
+  return forward(shape, plan, op_index, false, X, ldx, w_shards, Replicas{nullptr, nullptr, 0}, Y, ldy, ws, kScratchBytes,
+                 stream, nullptr);
+}
+
 osdp_status osdp_split_linear_fwd_mixed(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index, const void *X,
                                         int64_t ldx, const void *const *w_shards, const void *const *w_dp, int64_t ld_dp,
                                         void *Y, int64_t ldy, void *workspace, size_t workspace_bytes,

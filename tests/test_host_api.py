@@ -314,6 +314,19 @@ def test_forward_launch_plan_follows_the_pairing_switch():
     assert single == paired + T * O * 4   # two accumulating launches carry Y's partial sum through the workspace
 
 
+def test_no_workspace_forward_refuses_what_its_array_cannot_hold():
+    """The size check of the entry point that allocates nothing comes before any device call."""
+    T, I, O, N = 128, 8192, 8192, 8
+    X = _FakeTensor(0x10000, (T, I))
+    Y = _FakeTensor(0x20000, (T, O))
+    shards = [_FakeTensor(0x30000 + 0x1000 * s, (I * O // N,)) for s in range(N)]
+    need, _ = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, 1, False)
+    assert need > osdp.OSDP_NOALLOC_SCRATCH_BYTES
+    with pytest.raises(osdp.OsdpError) as e:
+        osdp.osdp_split_linear_fwd_noalloc(X, shards, Y, 1)
+    assert e.value.status == osdp.binding.OSDP_ERR_WORKSPACE and "scratch" in str(e.value)
+
+
 def test_profile_end_without_begin_is_an_error():
     with pytest.raises(osdp.OsdpError):
         osdp.osdp_profile_end()
