@@ -387,6 +387,7 @@ OSDP_API osdp_status osdp_plan_search(const osdp_operator_cost *ops, int32_t n, 
  *   "tile"          -1 .. 3  force tile shape 256x256, 256x128, 128x256, 128x128 where it divides the launch
  *   "deep"          -1 | 0   0: launches of at most one tile per CU keep the shallow LDS pipelines
  *   "split_launch"  -1 | 0   0: no launch is cut into whole rounds of large tiles + remainder
+ *   "four_wave"     -1 | 0   0: 256x256 tiles run on the eight-wave kernel instead of the four-wave one
  *   "fwd_pair"      -1 .. 1  0: the forward never runs two staged slices in one launch; 1: whenever it can
  *   "poison_staging" 0 | 1   1: a staging slot is filled with bf16 NaN patterns when a call starts and again as
  *                            soon as the last GEMM that reads its slice has been enqueued (on the compute

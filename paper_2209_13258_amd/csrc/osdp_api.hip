@@ -651,6 +651,7 @@ const DebugSwitch kSwitches[] = {
     {"gemm_generic", &DebugOptions::gemm_generic, 0, 1}, {"tile", &DebugOptions::tile, -1, 3},
     {"deep", &DebugOptions::deep, -1, 1},                {"split_launch", &DebugOptions::split_launch, -1, 1},
     {"fwd_pair", &DebugOptions::fwd_pair, -1, 1},        {"poison_staging", &DebugOptions::poison_staging, 0, 1},
+    {"four_wave", &DebugOptions::four_wave, -1, 1},
 };
 }  // namespace
 

@@ -12,6 +12,7 @@
 // a split operator bit-identical to the unsplit ones.
 #include "gemm_common.h"
 #include "gemm_dma.h"
+#include "gemm_w4.h"
 
 namespace osdp {
 
@@ -176,8 +177,23 @@ hipError_t launch_dma(const GemmParams &p, hipStream_t stream) {
   return hipGetLastError();
 }
 
+// The four-wave 256 x 256 kernel: two K blocks of 64 in LDS (128 KB).
+template <bool kAK, bool kBK, int kEpi, bool kAccIn>
+hipError_t launch_w4(const GemmParams &p, hipStream_t stream) {
+  constexpr size_t lds = 2 * (256 + 256) * 64 * sizeof(uint16_t);
+  static_assert(lds + OSDP_MAX_SHARDS * 8 <= 160 * 1024, "tile does not fit the 160 KB of LDS");
+  auto kernel = gemm_w4_kernel<kAK, kBK, kEpi, kAccIn>;
+  static bool configured[kMaxDevices] = {};
+  hipError_t e = allow_lds(kernel, lds, configured);
+  if (e != hipSuccess) return e;
+  const int tiles_m = p.M / 256, tiles_n = p.N / 256;
+  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n), dim3(256), lds, stream, p, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
 constexpr int kCUs = 256;
 constexpr int kShortK = 1024;
+constexpr int kW4MinK = 192;  // the four-wave kernel's K loop assumes at least three K blocks of 64
 
 // Estimated cost of covering M x N with BM x BN tiles on 256 CUs: tiles per CU times the tile's area, with a
 // penalty for the lower MFMA efficiency of smaller tiles.  Tiles that run two to a CU were measured in pairs; a
@@ -204,10 +220,13 @@ struct TileShape {
   int bm, bn;
   double penalty[3];
 };
-// 8192^3 on MI355X, forward / dW / dX in PFLOP/s: 256x256 1.23 / 1.18-1.24 / 1.26; 256x128 (two workgroups per CU)
-// 1.04 / 0.90 / 1.09; 128x256 (two per CU) 1.19 / 1.02 / 1.06; 128x128 (two per CU) 1.03 / 1.05 / 1.03.
-// K block and LDS stages per layout, also measured: forward (transposing reads of B) runs best with K blocks of
-// 64 in two stages, dW and dX on the 256x256 tile and dW on the 128x128 tile with K blocks of 32 in four stages.
+// 8192^3 on MI355X, forward / dW / dX in PFLOP/s, eight-wave kernels: 256x256 1.22 / 1.23 / 1.26; 256x128 (two
+// workgroups per CU) 1.04 / 0.90 / 1.09; 128x256 (two per CU) 1.19 / 1.02 / 1.06; 128x128 (two per CU) 1.03 / 1.05 /
+// 1.03.  The 256x256 tile runs on the four-wave kernel (gemm_w4.h) whenever K >= 192: 1.43 / 1.30 / 1.45 on the
+// same problem, which is what the penalties of the other shapes are relative to.
+// K block and LDS stages of the eight-wave kernels per layout, also measured: forward (transposing reads of B) runs
+// best with K blocks of 64 in two stages, dW and dX on the 256x256 tile and dW on the 128x128 tile with K blocks of
+// 32 in four stages.
 // The smaller tiles are sized for two workgroups per CU.  A launch with no more tiles than CUs has one, and is
 // then bound by the latency of its loads (1024x4096x8192 for dW on 128x128 tiles: 41 GB/s per CU with 48 KB in
 // flight); it takes the CU's whole LDS for K blocks of 64 in three or four stages, 96 KB in flight: dW 100 -> 88 us,
@@ -215,9 +234,9 @@ struct TileShape {
 // as 8 waves of 32x64 rather than 4 of 64x64, two per SIMD (another 3-10 %; without the deep pipeline it made no
 // difference).
 constexpr TileShape kTiles[4] = {{256, 256, {1.0, 1.0, 1.0}},
-                                 {256, 128, {1.17, 1.32, 1.16}},
-                                 {128, 256, {1.03, 1.16, 1.19}},
-                                 {128, 128, {1.19, 1.13, 1.22}}};
+                                 {256, 128, {1.37, 1.40, 1.33}},
+                                 {128, 256, {1.21, 1.23, 1.37}},
+                                 {128, 128, {1.39, 1.20, 1.40}}};
 
 constexpr int layout_kind(bool a_kcontig, bool b_kcontig) { return (a_kcontig && !b_kcontig) ? 0 : (!a_kcontig ? 1 : 2); }
 
@@ -263,6 +282,8 @@ hipError_t launch_best(const GemmParams &p, hipStream_t stream) {
                       debug_options().deep.load(std::memory_order_relaxed) != 0;  // testing: 0 keeps the shallow pipelines
     switch (best) {
       case 0:
+        if (p.K >= kW4MinK && debug_options().four_wave.load(std::memory_order_relaxed) != 0)
+          return launch_w4<kAK, kBK, kEpi, kAccIn>(p, stream);
         if (kind == 0) return launch_dma<256, 256, 64, 128, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
         return launch_dma<256, 256, 64, 128, 32, 4, kAK, kBK, kEpi, kAccIn>(p, stream);
       case 1:
@@ -378,16 +399,16 @@ bool gemm_takes_two_column_segments(int64_t M, int64_t n_first, int64_t n_second
 }
 
 double gemm_estimate_us(int64_t M, int64_t N, int64_t K) {
-  // one CU sustains about 4e6 flop per microsecond (1 PFLOP/s over 256 CUs) on 256 x 256 tiles
+  // one CU sustains about 5e6 flop per microsecond (1.3 PFLOP/s over 256 CUs) on 256 x 256 tiles
   // (one launch on its best tile: pricing the whole-rounds + remainder pair here instead was measured and made the
   // forward launch grouping of config 3 slightly worse)
   double cost = 0.0;
   if (fast_path(static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), 0, 0) &&
       best_tile(static_cast<int>(M), static_cast<int>(N), 0, 0, &cost) >= 0)
-    return cost * 2.0 * static_cast<double>(K) / 4.0e6 + 6.0;
+    return cost * 2.0 * static_cast<double>(K) / 5.0e6 + 6.0;
   const double tiles = static_cast<double>((M + GBM - 1) / GBM) * static_cast<double>((N + GBN - 1) / GBN);
   const double rounds = static_cast<double>(static_cast<long>((tiles + kCUs - 1) / kCUs));
-  return rounds * GBM * GBN * 4.0 * 2.0 * static_cast<double>(K) / 4.0e6 + 6.0;  // the checked kernel is about 4x slower per tile
+  return rounds * GBM * GBN * 5.0 * 2.0 * static_cast<double>(K) / 5.0e6 + 6.0;  // the checked kernel is about 5x slower per tile
 }
 
 hipError_t check_device() {

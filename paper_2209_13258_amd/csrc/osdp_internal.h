@@ -87,6 +87,7 @@ struct DebugOptions {
   std::atomic<int32_t> deep{-1};           // 0: launches of at most one tile per CU keep the shallow pipelines
   std::atomic<int32_t> split_launch{-1};   // 0: no whole-rounds + remainder launches
   std::atomic<int32_t> fwd_pair{-1};       // 0: the forward never pairs staged slices; 1: whenever the kernel can
+  std::atomic<int32_t> four_wave{-1};      // 0: 256 x 256 tiles run on the eight-wave kernel
   std::atomic<int32_t> poison_staging{0};  // 1: staging slots hold NaN patterns whenever no gathered slice is live in them
 };
 DebugOptions &debug_options();

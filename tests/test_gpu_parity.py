@@ -16,7 +16,7 @@ def H():
     return gpu_harness
 
 
-DEBUG_DEFAULTS = {"gemm_generic": 0, "tile": -1, "deep": -1, "split_launch": -1, "fwd_pair": -1, "poison_staging": 0}
+DEBUG_DEFAULTS = {"four_wave": -1, "gemm_generic": 0, "tile": -1, "deep": -1, "split_launch": -1, "fwd_pair": -1, "poison_staging": 0}
 
 
 @pytest.fixture
