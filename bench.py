@@ -1,6 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the operator-split linear layer (libosdp) on one MI355X.
 
+Default workload: the wide feed-forward pair of the benchmark's configs[3] (h = 8192, 4096 tokens), the one
+whose slice granularity the metric sweeps ("vs k; peak staging MB").
+
 A step is one pass of the whole hot path over one batch of synthetic input:
 for every operator of the workload, the split forward (gather slice j, slice
 GEMM) and then, in reverse operator order, the split backward (gather again,
@@ -21,24 +24,25 @@ import time
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak (vendor figure: 256 CUs x 2.4 GHz x 4096 flop/clk/CU)
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
 
-# L2-miss traffic per launch (bytes, FETCH_SIZE + WRITE_SIZE of two rocprofv3 --pmc runs of this file with
-# --traffic-calibration, each counter scaled by what it read for the three 1 GiB calibration copies: FETCH_SIZE
-# x 2.000, WRITE_SIZE x 1.000; all tile shapes of a kernel kind together, and both dispatches of a launch that the
-# library runs as whole rounds + remainder).  Source:
-# profiles/hbm_traffic_config2_config3.md.  Only valid for the default plan of the workload.
-KIB = 1024
-MEASURED_TRAFFIC = {
-    2: {"gemm_fwd": (73863 + 21438) * KIB, "gemm_dw": (196810 + 8192) * KIB, "gemm_dx": (111427 + 62469) * KIB},
-    3: {"gemm_fwd": (880856 + 126405) * KIB, "gemm_dw": (925151 + 25629) * KIB, "gemm_dx": (807698 + 232924) * KIB},
-}
+# HBM-side traffic per launch of each GEMM kind, from the rocprofv3 --pmc summaries under profiles/ (FETCH_SIZE and
+# WRITE_SIZE, each scaled by what the same counter reads for plain copies of known size): lines of the form
+# "traffic_bytes_per_launch <kernel kind> <bytes>" in profiles/hbm_traffic_config<N>.md.  None where no summary exists.
+def measured_traffic(config, kind):
+    import re
+    from pathlib import Path
+    f = Path(__file__).resolve().parent / "profiles" / f"hbm_traffic_config{config}.md"
+    if not f.exists():
+        return None
+    m = re.search(rf"^traffic_bytes_per_launch\s+{kind}\s+(\d+)", f.read_text(), re.M)
+    return int(m.group(1)) if m else None
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="workload: index into BASELINE.json configs (1-based)")
+    ap.add_argument("--config", type=int, default=4, help="workload: index into BASELINE.json configs (1-based)")
     ap.add_argument("--k", type=int, default=None, help="slice granularity (default: the workload's own)")
     ap.add_argument("--staging", choices=["auto", "single", "double", "half"], default="auto")
     ap.add_argument("--split-dim", choices=["out", "in", "longer"], default="out",
@@ -47,7 +51,10 @@ def parse():
     ap.add_argument("--zdp-slices", type=int, default=None,
                     help="keep only the first Z slices of every operator sharded (ZDP); the others are DP slices "
                          "read from a resident replica (default: every slice ZDP)")
-    ap.add_argument("--no-sweep", action="store_true", help="skip the k sweep and the extra workload")
+    ap.add_argument("--no-sweep", action="store_true", help="skip the k x staging sweep and the other workloads")
+    ap.add_argument("--gathers", choices=["carried", "launched"], default="carried",
+                    help="carried: a GEMM launch takes the next slice's gather along (the library's default); launched: "
+                         "every gather is a kernel launch of its own, on the copy stream where the pipeline overlaps")
     ap.add_argument("--no-auto", action="store_true", help="skip the automatic slice-granularity table")
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="first run three plain copies of 1 GiB through the gather kernel (one shard, one slice, source "
@@ -140,6 +147,8 @@ class Stack:
             torch.cuda.synchronize()
             t1 = time.perf_counter()
             stats = osdp.osdp_profile_end() if profile else None
+            if profile:
+                stats["_overlap"] = osdp.osdp_profile_overlap()
         return (t1 - t0) * 1e3 / steps, stats
 
 
@@ -162,7 +171,10 @@ def per_step_times(st, iters, warmup, serial):
 def kernel_table(stats):
     out = {}
     for name, s in stats.items():
-        if not s["launches"]:
+        if name.startswith("_") or not s["launches"]:
+            continue
+        if name == "gather_carried":   # gathers that ran inside GEMM launches: no time of their own
+            out[name] = dict(launches=s["launches"], mb=round(s["bytes"] / 2 / 2 ** 20, 2))
             continue
         avg_ms = s["ms"] / s["launches"]
         e = dict(launches=s["launches"], avg_us=round(avg_ms * 1e3, 2), total_ms=round(s["ms"], 3))
@@ -172,6 +184,41 @@ def kernel_table(stats):
         e["gbs_algorithmic"] = round(s["bytes"] / (s["ms"] * 1e-3) / 1e9, 1)
         out[name] = e
     return out
+
+
+def measure(st, flops, steps, warmup, serial, config=None):
+    """The figures of one resident stack: median and mean of `steps` individually timed steps, the per-kernel table of a
+    second, instrumented pass of the same steps (every launch bracketed by HIP events on its own stream), the roofline
+    of the GEMM kind with the largest summed time, and where the gathers went."""
+    median_ms, mean_ms = per_step_times(st, steps, warmup, serial)
+    n_prof = max(10, steps // 2)
+    ms_prof, stats = st.run(n_prof, 2, serial=serial, profile=True)
+    ov = stats["_overlap"]
+    kernels = kernel_table(stats)
+    gemms = {k: v for k, v in kernels.items() if k.startswith("gemm")}
+    dom = max(gemms, key=lambda k: gemms[k]["total_ms"])
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": gemms[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(gemms[dom]["tflops"] / PEAK_BF16_TFLOPS, 4),
+                "traffic": measured_traffic(config, dom) if config else None,
+                "algorithmic_bytes": round(stats[dom]["bytes"] / stats[dom]["launches"]),
+                "avg_launch_us": gemms[dom]["avg_us"], "launches_per_step": gemms[dom]["launches"] // n_prof}
+    g, c = kernels.get("gather"), kernels.get("gather_carried")
+    gathers = {"launched_per_step": (g["launches"] // n_prof) if g else 0,
+               "launched_us_per_step": round(g["total_ms"] * 1e3 / n_prof, 1) if g else 0.0,
+               "launched_gbs": g["gbs_algorithmic"] if g else None,
+               "launched_frac_hbm_peak": round(g["gbs_algorithmic"] / PEAK_HBM_GBS, 4) if g else None,
+               "carried_by_gemm_launches_per_step": (c["launches"] // n_prof) if c else 0,
+               "carried_mb_per_step": round(c["mb"] / n_prof, 2) if c else 0.0,
+               # time in which a gather kernel ran and no GEMM did (instrumented pass, all streams on one clock)
+               "exposed_us_per_step": round(ov["gather_exposed_ms"] * 1e3 / n_prof, 1)}
+    tf = flops / (median_ms * 1e-3) / 1e12
+    return {"tflops": round(tf, 2), "frac_bf16_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4),
+            "median_ms_per_step": round(median_ms, 4), "mean_ms_per_step": round(mean_ms, 4), "timed_steps": steps,
+            "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3), "workspace_mb": round(st.workspace_bytes / 2 ** 20, 3),
+            "roofline": roofline, "gathers": gathers,
+            # instrumented pass: the part of a step in which no kernel of the library ran (launch gaps, event handling)
+            "idle_us_per_step": round(ov["idle_ms"] * 1e3 / n_prof, 1),
+            "kernels": kernels}
 
 
 def auto_granularity(st, osdp, torch, steps, warmup):
@@ -205,7 +252,7 @@ def auto_granularity(st, osdp, torch, steps, warmup):
     plan = osdp.Plan([c.k for c in picked], split_dim_per_op=[c.split_dim for c in picked],
                      staging_per_op=[c.staging for c in picked])
     tuned = Stack(st.w, 0, torch, osdp, plan=plan)
-    ms = min(tuned.run(steps, warmup)[0] for _ in range(2))
+    ms = per_step_times(tuned, steps, warmup, False)[0]   # median of individually timed steps
     import workloads as wl
     out["step_under_chosen_plan"] = {"k_per_op": list(plan.k_per_op), "split_dim_per_op": list(plan.split_dim_per_op),
                                      "staging_per_op": [names[m] for m in plan.staging_per_op], "ms_per_step": round(ms, 4),
@@ -265,7 +312,7 @@ def plan_search(w, kernels, staging, rows, torch, osdp, steps, warmup):
         if layer == 0 and m:
             masks[n] |= 1 << j
     st = Stack(w, staging, torch, osdp, rows=rows, zdp_masks=masks)
-    ms = min(st.run(steps, warmup)[0] for _ in range(2))
+    ms = per_step_times(st, steps, warmup, False)[0]   # median of individually timed steps
     return {"found": True, "items": len(items), "memory_limit_mb": round(limit / 2 ** 20, 3),
             "device_info": {"alpha_s": alpha, "beta_s_per_byte": beta, "gemm_flops_per_s": flops_per_s},
             "zdp_mask_per_op": {op.name: bin(m) for op, m in zip(w.ops, masks)}, "zdp_items": int(sum(r["modes"])),
@@ -325,8 +372,10 @@ def main():
     import paper_2209_13258_amd as osdp
     import workloads as wl
 
-    staging = {"auto": osdp.OSDP_STAGING_AUTO, "single": osdp.OSDP_STAGING_SINGLE,
-               "double": osdp.OSDP_STAGING_DOUBLE, "half": osdp.OSDP_STAGING_HALF}[a.staging]
+    modes = {"auto": osdp.OSDP_STAGING_AUTO, "single": osdp.OSDP_STAGING_SINGLE,
+             "double": osdp.OSDP_STAGING_DOUBLE, "half": osdp.OSDP_STAGING_HALF}
+    staging = modes[a.staging]
+    osdp.osdp_debug_option("fused_gather", -1 if a.gathers == "carried" else 0)
     if a.traffic_calibration:
         I, O = 16384, 32768   # 1 GiB of bf16
         src = torch.zeros(I * O, dtype=torch.bfloat16, device="cuda")
@@ -341,24 +390,16 @@ def main():
     longer = a.split_dim == "longer"
     st = Stack(w, staging, torch, osdp, rows=rows, zdp_slices=a.zdp_slices, longer=longer)
     flops = wl.flops(w)
+    default_plan = a.k is None and a.staging == "auto" and not a.serial and not rows and not longer and \
+        a.zdp_slices is None and a.gathers == "carried"
 
+    # ---- the headline: exactly --steps steps after --warmup, one timed region, inputs resident ------------
     torch.cuda.synchronize()
     alloc_before = torch.cuda.memory_allocated()
     torch.cuda.reset_peak_memory_stats()
     ms, _ = st.run(a.steps, a.warmup, serial=a.serial)
     alloc_delta = torch.cuda.max_memory_allocated() - alloc_before   # the library allocates nothing: the workspace is all
-    median_ms, mean_ms = per_step_times(st, 100, 10, a.serial)
-    ms_prof, stats = st.run(a.steps, 2, serial=a.serial, profile=True)
-    kernels = kernel_table(stats)
-    gemms = {k: v for k, v in kernels.items() if k.startswith("gemm")}
-    dom = max(gemms, key=lambda k: gemms[k]["total_ms"])
-    roofline = {"bound": "mfma", "kernel": dom, "achieved": gemms[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(gemms[dom]["tflops"] / PEAK_BF16_TFLOPS, 4),
-                "traffic": (MEASURED_TRAFFIC.get(a.config, {}).get(dom)
-                            if (a.k is None and a.staging == "auto" and not a.serial and not rows
-                                and a.zdp_slices is None) else None),
-                "algorithmic_bytes": round(stats[dom]["bytes"] / stats[dom]["launches"]),
-                "avg_launch_us": gemms[dom]["avg_us"], "launches": gemms[dom]["launches"]}
+    m = measure(st, flops, max(a.steps, 20), a.warmup, a.serial, config=a.config if default_plan else None)
 
     out = {
         "metric": "split-linear fwd+bwd TFLOP/s & % bf16 MFMA peak vs k; peak staging MB",
@@ -367,89 +408,118 @@ def main():
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": w.name, "baseline_config": a.config, "T": w.T, "N_shards": w.N, "layers": w.layers,
                    "ops": {op.name: {"I": op.I, "O": op.O, "k": op.k} for op in w.ops},
-                   "staging": a.staging, "overlap": not a.serial,
+                   "staging": a.staging, "streams": 1 if a.serial else 2, "gathers": a.gathers,
                    "split_dim": "longer" if longer else "in_features" if rows else "out_features",
                    "zdp_slices": "all" if a.zdp_slices is None else a.zdp_slices},
         "frac_bf16_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-        "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3),
-        "workspace_mb": round(st.workspace_bytes / 2 ** 20, 3),
-        "ms_per_step_with_kernel_timing": round(ms_prof, 4),
-        "per_step_events": {"iters": 100, "warmup": 10, "median_ms": round(median_ms, 4), "mean_ms": round(mean_ms, 4)},
+        "peak_staging_mb": m["peak_staging_mb"], "workspace_mb": m["workspace_mb"],
+        "per_step_events": {"iters": m["timed_steps"], "warmup": a.warmup, "median_ms": m["median_ms_per_step"],
+                            "mean_ms": m["mean_ms_per_step"]},
         "device_memory_allocated_during_steps_bytes": int(alloc_delta),
-        "roofline": roofline,
-        "kernels": kernels,
+        "roofline": m["roofline"], "gathers": m["gathers"], "idle_us_per_step": m["idle_us_per_step"],
+        "kernels": m["kernels"],
     }
+    sub_steps, sub_warm = max(20, a.steps // 2), max(3, a.warmup // 2)
 
     if not a.no_sweep and a.zdp_slices is None:
-        # Section 3.3, last paragraph: the same granularity with fewer and fewer slices in ZDP mode
-        modes = {}
-        kmax = max(max(op.k, 1) for op in w.ops)
-        for z in sorted({kmax, kmax // 2, 1, 0}, reverse=True):
-            sm = Stack(w, staging, torch, osdp, rows=rows, zdp_slices=z)
-            msz = min(sm.run(max(5, a.steps // 2), max(2, a.warmup // 2), serial=a.serial)[0] for _ in range(2))
-            modes[str(z)] = {"tflops": round(flops / (msz * 1e-3) / 1e12, 2), "ms_per_step": round(msz, 4),
-                             "peak_staging_mb": round(sm.peak_staging / 2 ** 20, 3),
-                             "dp_replica_mb": round(sum((max(op.k, 1) - min(z, max(op.k, 1))) * op.I * op.O * 2 / max(op.k, 1)
-                                                        for op in w.ops) * w.layers / 2 ** 20, 3)}
-            del sm
-            torch.cuda.empty_cache()
-        out["zdp_slices_of_k"] = modes
+        # the gather kernel on its own: one slice of the first operator, back to back (achieved HBM rate of the copy)
+        op0 = w.ops[0]
+        k0 = max(op0.k, 1)
+        stg = torch.empty(op0.I * (op0.O // k0), dtype=torch.bfloat16, device="cuda")
+        cur = torch.cuda.current_stream()
+        for _ in range(3):
+            osdp.osdp_split_linear_gather_slice(op0.I, op0.O, k0, 0, st.ops[0]["W"], stg, stream=cur)
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+        for e0, e1 in ev:
+            e0.record(cur)
+            osdp.osdp_split_linear_gather_slice(op0.I, op0.O, k0, 0, st.ops[0]["W"], stg, stream=cur)
+            e1.record(cur)
+        torch.cuda.synchronize()
+        t = sorted(e0.elapsed_time(e1) for e0, e1 in ev)[len(ev) // 2]
+        gbs = 2 * stg.numel() * 2 / (t * 1e-3) / 1e9
+        out["gather_kernel_alone"] = {"slice_mb": round(stg.numel() * 2 / 2 ** 20, 2), "median_us": round(t * 1e3, 2),
+                                      "gbs_read_plus_write": round(gbs, 1), "frac_hbm_peak": round(gbs / PEAK_HBM_GBS, 4)}
+        del stg
+
     if not a.no_sweep and a.zdp_slices is None:
-        out["plan_search"] = plan_search(w, kernels, staging, rows, torch, osdp, max(5, a.steps // 2), max(2, a.warmup // 2))
-    if not a.no_auto:
-        out["auto_granularity"] = auto_granularity(st, osdp, torch, max(5, a.steps // 2), max(2, a.warmup // 2))
-    if not a.no_sweep:
+        # Section 4.3, slice granularity: every k of the workload's sweep under every staging mode (column slices, gathers
+        # carried by the GEMM launches), then the same k with every operator cut along its longer dimension, and
+        # with every gather a launch of its own on the copy stream (the two-stream pipeline)
         sweep = {}
         for k in (w.k_sweep or ()):
             wk = wl.workload(a.config, k)
+            fk = wl.flops(wk)
+            row = {}
+            for mname in ("single", "double", "half"):
+                if k == 1 and mname != "single":
+                    continue
+                del st
+                torch.cuda.empty_cache()
+                st = Stack(wk, modes[mname], torch, osdp, rows=rows)
+                mk = measure(st, fk, sub_steps, sub_warm, a.serial)
+                row[mname] = {key: mk[key] for key in ("tflops", "frac_bf16_mfma_peak", "median_ms_per_step", "peak_staging_mb",
+                                                       "workspace_mb", "gathers", "idle_us_per_step")}
+                row[mname]["roofline_frac"] = {kk: vv.get("frac_mfma_peak") for kk, vv in mk["kernels"].items() if kk.startswith("gemm")}
+            if k > 1:
+                del st
+                torch.cuda.empty_cache()
+                st = Stack(wk, modes["double"], torch, osdp, longer=True)
+                ml = per_step_times(st, sub_steps, sub_warm, a.serial)[0]
+                row["double_longer_split_dim"] = {"tflops": round(fk / (ml * 1e-3) / 1e12, 2), "median_ms_per_step": round(ml, 4),
+                                                  "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3),
+                                                  "workspace_mb": round(st.workspace_bytes / 2 ** 20, 3)}
+                del st
+                torch.cuda.empty_cache()
+                osdp.osdp_debug_option("fused_gather", 0)
+                st = Stack(wk, modes["double"], torch, osdp, rows=rows)
+                m2 = measure(st, fk, sub_steps, sub_warm, False)
+                osdp.osdp_debug_option("fused_gather", -1 if a.gathers == "carried" else 0)
+                row["double_gathers_launched_two_streams"] = {key: m2[key] for key in ("tflops", "median_ms_per_step", "gathers", "idle_us_per_step")}
+            sweep[str(k)] = row
+        out["k_sweep"] = sweep
+        del st
+        torch.cuda.empty_cache()
+        st = Stack(w, staging, torch, osdp, rows=rows, longer=longer)
+
+    if not a.no_sweep and a.zdp_slices is None:
+        # Section 3.3, last paragraph: the same granularity with fewer and fewer slices in ZDP mode
+        zmodes = {}
+        kmax = max(max(op.k, 1) for op in w.ops)
+        for z in sorted({kmax, kmax // 2, 1, 0}, reverse=True):
+            sm = Stack(w, staging, torch, osdp, rows=rows, zdp_slices=z)
+            msz = per_step_times(sm, sub_steps, sub_warm, a.serial)[0]
+            zmodes[str(z)] = {"tflops": round(flops / (msz * 1e-3) / 1e12, 2), "median_ms_per_step": round(msz, 4),
+                              "peak_staging_mb": round(sm.peak_staging / 2 ** 20, 3),
+                              "dp_replica_mb": round(sum((max(op.k, 1) - min(z, max(op.k, 1))) * op.I * op.O * 2 / max(op.k, 1)
+                                                         for op in w.ops) * w.layers / 2 ** 20, 3)}
+            del sm
+            torch.cuda.empty_cache()
+        out["zdp_slices_of_k"] = zmodes
+        out["plan_search"] = plan_search(w, m["kernels"], staging, rows, torch, osdp, sub_steps, sub_warm)
+    if not a.no_auto:
+        out["auto_granularity"] = auto_granularity(st, osdp, torch, sub_steps, sub_warm)
+    if not a.no_sweep and default_plan:
+        # the other workloads under their own plan vectors, each with its own roofline
+        also = []
+        for cfg in (c for c in (2, 3, 5) if c != a.config):
             del st
             torch.cuda.empty_cache()
-            st = Stack(wk, staging, torch, osdp, rows=rows)
-            # the sweep's figures are the faster of two timed runs each (the chip's clocks sometimes take a few
-            # milliseconds to come back up after the idle time spent allocating the next stack)
-            msk = min(st.run(max(5, a.steps // 2), max(2, a.warmup // 2), serial=a.serial)[0] for _ in range(2))
-            mss = min(st.run(max(5, a.steps // 2), 2, serial=True)[0] for _ in range(2))
-            _, sk = st.run(max(5, a.steps // 4), 2, serial=a.serial, profile=True)
-            kt = kernel_table(sk)
-            tf = wl.flops(wk) / (msk * 1e-3) / 1e12
-            sweep[str(k)] = {"tflops": round(tf, 2), "frac_bf16_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4),
-                             "ms_per_step": round(msk, 4), "ms_per_step_serial": round(mss, 4),
-                             "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3),
-                             "gather_gbs": kt.get("gather", {}).get("gbs_algorithmic"),
-                             "gather_frac_hbm_peak": round(kt.get("gather", {}).get("gbs_algorithmic", 0) / PEAK_HBM_GBS, 4)}
-            if k > 1:  # the same granularity with W cut along the other dimension
-                del st
-                torch.cuda.empty_cache()
-                st = Stack(wk, staging, torch, osdp, rows=not rows)
-                mso = min(st.run(max(5, a.steps // 2), max(2, a.warmup // 2), serial=a.serial)[0] for _ in range(2))
-                sweep[str(k)]["tflops_other_split_dim"] = round(wl.flops(wk) / (mso * 1e-3) / 1e12, 2)
-                sweep[str(k)]["peak_staging_mb_other_split_dim"] = round(st.peak_staging / 2 ** 20, 3)
-                del st
-                torch.cuda.empty_cache()
-                st = Stack(wk, staging, torch, osdp, longer=True)   # every operator cut along its longer dimension
-                msl = min(st.run(max(5, a.steps // 2), max(2, a.warmup // 2), serial=a.serial)[0] for _ in range(2))
-                sweep[str(k)]["tflops_longer_split_dim"] = round(wl.flops(wk) / (msl * 1e-3) / 1e12, 2)
-        out["k_sweep"] = sweep
-        if a.config == 2:  # the larger workloads under their own plan vectors (config 3 is where the 70 % target applies)
-            also = []
-            for cfg in (3, 4, 5):
-                del st
-                torch.cuda.empty_cache()
-                wc = wl.workload(cfg)
-                entry = {"workload": wc.name, "baseline_config": cfg, "plan": {op.name: op.k for op in wc.ops}}
-                for label, kw in (("", dict(rows=rows)), ("_longer_split_dim", dict(longer=True))):
-                    st = Stack(wc, staging, torch, osdp, **kw)
-                    msc = min(st.run(5, 2, serial=a.serial)[0] for _ in range(2))
-                    tfc = wl.flops(wc) / (msc * 1e-3) / 1e12
-                    entry.update({"ms_per_step" + label: round(msc, 4), "tflops" + label: round(tfc, 2),
-                                  "frac_bf16_mfma_peak" + label: round(tfc / PEAK_BF16_TFLOPS, 4),
-                                  "peak_staging_mb" + label: round(st.peak_staging / 2 ** 20, 3),
-                                  "workspace_mb" + label: round(st.workspace_bytes / 2 ** 20, 3)})
-                    if label == "":
-                        del st
-                        torch.cuda.empty_cache()
-                also.append(entry)
-            out["also"] = also
+            wc = wl.workload(cfg)
+            st = Stack(wc, staging, torch, osdp)
+            mc = measure(st, wl.flops(wc), sub_steps, sub_warm, False, config=cfg)
+            entry = {"workload": wc.name, "baseline_config": cfg, "plan": {op.name: op.k for op in wc.ops}}
+            entry.update({key: mc[key] for key in ("tflops", "frac_bf16_mfma_peak", "median_ms_per_step", "mean_ms_per_step",
+                                                   "timed_steps", "peak_staging_mb", "workspace_mb", "roofline", "gathers",
+                                                   "idle_us_per_step", "kernels")})
+            del st
+            torch.cuda.empty_cache()
+            st = Stack(wc, staging, torch, osdp, longer=True)
+            mlc = per_step_times(st, sub_steps, sub_warm, False)[0]
+            entry["longer_split_dim"] = {"tflops": round(wl.flops(wc) / (mlc * 1e-3) / 1e12, 2), "median_ms_per_step": round(mlc, 4),
+                                         "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3),
+                                         "workspace_mb": round(st.workspace_bytes / 2 ** 20, 3)}
+            also.append(entry)
+        out["also"] = also
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, rows=rows)
     print(json.dumps(out), flush=True)

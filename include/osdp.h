@@ -387,7 +387,10 @@ OSDP_API osdp_status osdp_plan_search(const osdp_operator_cost *ops, int32_t n, 
  *   "tile"          -1 .. 3  force tile shape 256x256, 256x128, 128x256, 128x128 where it divides the launch
  *   "deep"          -1 | 0   0: launches of at most one tile per CU keep the shallow LDS pipelines
  *   "split_launch"  -1 | 0   0: no launch is cut into whole rounds of large tiles + remainder
- *   "four_wave"     -1 | 0   0: 256x256 tiles run on the eight-wave kernel instead of the four-wave one
+ *   "four_wave"     -1 .. 1  0: 256x256 tiles always run on the eight-wave kernel; 1: on the four-wave kernel
+ *                            whenever it takes the launch (K >= 192), also where the eight-wave one measured faster
+ *   "fused_gather"  -1 | 0   0: every gather is a launch of its own (on stream_copy where the pipeline overlaps);
+ *                            otherwise a GEMM launch takes the next slice's gather along wherever it can
  *   "fwd_pair"      -1 .. 1  0: the forward never runs two staged slices in one launch; 1: whenever it can
  *   "poison_staging" 0 | 1   1: a staging slot is filled with bf16 NaN patterns when a call starts and again as
  *                            soon as the last GEMM that reads its slice has been enqueued (on the compute
@@ -405,7 +408,9 @@ typedef enum {
   OSDP_KERNEL_GEMM_FWD = 1,
   OSDP_KERNEL_GEMM_DW = 2,
   OSDP_KERNEL_GEMM_DX = 3,
-  OSDP_KERNEL_KINDS = 4
+  OSDP_KERNEL_GATHER_CARRIED = 4, /* gathers that ran inside a GEMM launch: launches and bytes only, their time is
+                                     part of the GEMM launches that carried them */
+  OSDP_KERNEL_KINDS = 5
 } osdp_kernel_kind;
 
 typedef struct {
@@ -422,6 +427,14 @@ typedef struct {
  * undisturbed: the event records sit between the kernels. */
 OSDP_API osdp_status osdp_profile_begin(int32_t max_launches);
 OSDP_API osdp_status osdp_profile_end(osdp_kernel_stats *stats);
+
+/* After osdp_profile_end: how the launches of the profiled region lay in time (all streams on one clock).
+ *   span_ms           : first launch start to last launch end
+ *   idle_ms           : the part of the span in which no kernel of the library ran (launch gaps, event handling)
+ *   gather_exposed_ms : the time in which a gather kernel ran and no GEMM did, i.e. gather time that no GEMM hid
+ *                       (gathers carried inside GEMM launches are not kernels of their own and do not appear here)
+ * Any pointer may be NULL.  Host only. */
+OSDP_API osdp_status osdp_profile_overlap(double *span_ms, double *idle_ms, double *gather_exposed_ms);
 
 OSDP_API const char *osdp_strerror(osdp_status status);
 OSDP_API const char *osdp_last_error(void);

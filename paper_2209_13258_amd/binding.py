@@ -34,15 +34,16 @@ OSDP_KERNEL_GATHER = 0
 OSDP_KERNEL_GEMM_FWD = 1
 OSDP_KERNEL_GEMM_DW = 2
 OSDP_KERNEL_GEMM_DX = 3
-OSDP_KERNEL_KINDS = 4
-KERNEL_NAMES = ("gather", "gemm_fwd", "gemm_dw", "gemm_dx")
+OSDP_KERNEL_GATHER_CARRIED = 4
+OSDP_KERNEL_KINDS = 5
+KERNEL_NAMES = ("gather", "gemm_fwd", "gemm_dw", "gemm_dx", "gather_carried")
 
 EXPORTS = (
     "osdp_slice_range", "osdp_row_slice_range", "osdp_split_linear_gather_slice",
     "osdp_split_linear_gather_row_slice", "osdp_split_linear_workspace_bytes", "osdp_split_linear_fwd",
     "osdp_split_linear_bwd", "osdp_split_linear_fwd_noalloc", "osdp_split_linear_fwd_mixed", "osdp_split_linear_bwd_mixed",
     "osdp_granularity_candidates", "osdp_granularity_measure",
-    "osdp_granularity_select", "osdp_cost_model", "osdp_plan_search", "osdp_profile_begin", "osdp_profile_end",
+    "osdp_granularity_select", "osdp_cost_model", "osdp_plan_search", "osdp_profile_begin", "osdp_profile_end", "osdp_profile_overlap",
     "osdp_debug_option", "osdp_strerror", "osdp_last_error", "osdp_version",
 )
 
@@ -129,6 +130,8 @@ def _load() -> ctypes.CDLL:
     lib.osdp_debug_option.restype = ctypes.c_int
     lib.osdp_profile_begin.argtypes = [i32]
     lib.osdp_profile_end.argtypes = [ctypes.POINTER(osdp_kernel_stats)]
+    lib.osdp_profile_overlap.argtypes = [ctypes.POINTER(ctypes.c_double)] * 3
+    lib.osdp_profile_overlap.restype = ctypes.c_int
     for name in ("osdp_slice_range", "osdp_row_slice_range", "osdp_split_linear_gather_slice",
                  "osdp_split_linear_gather_row_slice", "osdp_split_linear_workspace_bytes",
                  "osdp_split_linear_fwd", "osdp_split_linear_bwd", "osdp_split_linear_fwd_mixed",
@@ -389,3 +392,10 @@ def osdp_profile_end():
     _check(lib.osdp_profile_end(stats))
     return {KERNEL_NAMES[i]: dict(launches=stats[i].launches, ms=stats[i].ms, flops=stats[i].flops,
                                   bytes=stats[i].bytes) for i in range(OSDP_KERNEL_KINDS)}
+
+
+def osdp_profile_overlap():
+    """After osdp_profile_end: dict(span_ms, idle_ms, gather_exposed_ms) of the profiled region."""
+    span, idle, exposed = ctypes.c_double(), ctypes.c_double(), ctypes.c_double()
+    _check(lib.osdp_profile_overlap(ctypes.byref(span), ctypes.byref(idle), ctypes.byref(exposed)))
+    return dict(span_ms=span.value, idle_ms=idle.value, gather_exposed_ms=exposed.value)

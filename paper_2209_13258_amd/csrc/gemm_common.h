@@ -18,6 +18,19 @@ __device__ __forceinline__ f32x4 mma_16x16x32(bf16x8 a_rows, bf16x8 b_cols, f32x
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(b_cols, a_rows, c, 0, 0, 0);
 }
 
+// A slice gather that rides along with a GEMM launch (four-wave kernel only): the copy Ws[r, c] = W[r0 + r, c0 + c]
+// of osdp_gather.hip, cut into one piece of 256 vectors per workgroup and K block and issued in the shadow of the
+// MFMAs.  dst is the dense destination, total_vecs its size in 16-byte vectors (below 2^32).
+struct GatherJob {
+  ShardTable src;
+  ShardLayout lay;
+  uint32_t r0;
+  uint32_t vecs_per_row;
+  uint64_t c0;
+  uint64_t total_vecs;
+  uint4 *dst;
+};
+
 struct GemmParams {
   int32_t M, N, K;
   const uint16_t *A;
@@ -36,6 +49,7 @@ struct GemmParams {
   int64_t c0;          // shard-major epilogue: column of the full matrix where C starts
   int64_t r0;          // shard-major epilogue: row of the full matrix where C starts
   ShardTable shards;
+  GatherJob job;       // only read by kernels instantiated to carry one
 };
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
@@ -115,7 +129,7 @@ __device__ __forceinline__ void store_acc4(const GemmParams &p, f32x4 c, int m, 
     }
     dst = s_tab[s] + off;
   }
-  *reinterpret_cast<uint2 *>(dst) = o;
+  store_global8(dst, o);
 }
 
 template <int MB, int NB, int kEpi>

@@ -78,7 +78,13 @@ struct W4Operand {
   static __device__ __forceinline__ bf16x8 frag(const uint16_t *slot, int mn0, int kk, int lane) { return Base::frag(slot, mn0, kk, lane); }
 };
 
-template <bool kAK, bool kBKc, int kEpi, bool kAccIn>
+// kCopy: the launch also carries p.job, the gather of a slice that a later launch will read (the forward GEMM of
+// slice j gathers slice j+1 into the other staging slot; a dW launch, which needs no weights, gathers the slices of
+// the dX pass that follows it).  Every workgroup copies total_vecs / gridDim.x vectors, 256 per K block: one 16-byte
+// load and one 16-byte store per lane and block, against that block's 16 KB of operand loads per wave.  A gather
+// kernel of its own cannot run beside this kernel, whose four waves hold every register of their SIMDs: on a second
+// stream it only takes turns with the tiles, and both get slower.
+template <bool kAK, bool kBKc, int kEpi, bool kAccIn, bool kCopy = false>
 __global__ __launch_bounds__(256, 1)
 void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
   constexpr int BM = 256, BN = 256, WM = 128, WN = 128;
@@ -95,6 +101,51 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
     s_tab = tab;
   }
   const int tid = threadIdx.x;
+  // ---- the carried gather: this workgroup's range of vectors, piece i = vectors first + 256 i + tid ----------
+  // Pieces beyond the range copy the range's last vector again (the same bytes to the same place), so that every
+  // K block runs the same instructions; a workgroup whose range is empty does that with the job's vector 0.
+  uint64_t copy_first = 0, copy_last = 0;
+  uint32_t copy_pieces = 0;
+  const uint16_t *const *g_tab = nullptr;
+  if constexpr (kCopy) {
+    __shared__ const uint16_t *gtab[OSDP_MAX_SHARDS];
+    if (tid < OSDP_MAX_SHARDS) gtab[tid] = static_cast<const uint16_t *>(p.job.src.p[tid]);
+    g_tab = gtab;  // read after the prologue's barrier
+    const uint64_t per_wg = ((p.job.total_vecs + gridDim.x - 1) / gridDim.x + 255) & ~static_cast<uint64_t>(255);
+    const uint64_t first = static_cast<uint64_t>(blockIdx.x) * per_wg;
+    if (first < p.job.total_vecs) {
+      const uint64_t end = first + per_wg < p.job.total_vecs ? first + per_wg : p.job.total_vecs;
+      copy_first = first;
+      copy_last = end - 1;
+      copy_pieces = static_cast<uint32_t>((end - first + 255) / 256);
+    }
+  }
+  // source address of this lane's vector of piece i
+  auto copy_src = [&](uint32_t i, uint32_t *v_out) -> const uint4 * {
+    uint64_t v = copy_first + static_cast<uint64_t>(i) * 256 + tid;
+    v = v < copy_last ? v : copy_last;
+    const uint32_t v32 = static_cast<uint32_t>(v);
+    const uint32_t rd = v32 / p.job.vecs_per_row, cv = v32 - rd * p.job.vecs_per_row;
+    const uint32_t r = p.job.r0 + rd;
+    uint32_t s;
+    uint64_t off;
+    if (p.job.lay.rows_per_shard > 0) {
+      s = r / static_cast<uint32_t>(p.job.lay.rows_per_shard);
+      off = static_cast<uint64_t>(r - s * p.job.lay.rows_per_shard) * p.job.lay.O + p.job.c0 + cv * 8u;
+    } else {
+      const uint64_t f = static_cast<uint64_t>(r) * p.job.lay.O + p.job.c0 + cv * 8u;
+      s = static_cast<uint32_t>(f / static_cast<uint64_t>(p.job.lay.L));
+      off = f - static_cast<uint64_t>(s) * p.job.lay.L;
+    }
+    *v_out = v32;
+    return reinterpret_cast<const uint4 *>(g_tab[s] + off);
+  };
+  uint4 copy_data = {0u, 0u, 0u, 0u};  // the piece in flight
+  uint32_t copy_v = 0;                 // its destination vector
+  uint32_t copy_i = 0;                 // its index
+  const uint4 *copy_ptr = nullptr;     // source and destination vector of the piece after it
+  uint32_t copy_next_v = 0;
+
   int tm, tn;
   tile_of_block(tiles_m, tiles_n, &tm, &tn);
   const int m0 = tm * BM, n0 = tn * BN;
@@ -169,6 +220,10 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
   block_issued();
   wait_vmcnt<L>();
   __builtin_amdgcn_s_barrier();
+  if constexpr (kCopy) {  // piece 0 of the carried gather (the barrier has published the shard table)
+    copy_ptr = copy_src(0, &copy_v);
+    copy_data = load_global16(copy_ptr);
+  }
   {
     const uint16_t *sA = smem, *sB = smem + OpA::kElems;
 #pragma unroll
@@ -195,6 +250,15 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
         issue(ls, Int<i / 4>{}, advA, advB);
         if (i / 4 == L - 1 && advance) block_issued();
       }
+      // carried gather: in the block's first K step the address of the next piece is worked out; in the second,
+      // just behind the barrier where every load has landed, the piece in registers goes out and the next comes in
+      if constexpr (kCopy && !kLoad && i == 40) copy_ptr = copy_src(copy_i + 1, &copy_next_v);
+      if constexpr (kCopy && kLoad && i == 0) store_global16(p.job.dst + copy_v, copy_data);
+      if constexpr (kCopy && kLoad && i == 1) {
+        copy_data = load_global16(copy_ptr);
+        copy_v = copy_next_v;
+        ++copy_i;
+      }
       __builtin_amdgcn_sched_barrier(0);
     });
   };
@@ -218,6 +282,15 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
     cur ^= 1;
   }
   wait_vmcnt<0>();  // surplus loads must have landed before the workgroup gives its LDS back
+  if constexpr (kCopy) {
+    // the piece still in registers, and whatever the K loop was too short for
+    store_global16(p.job.dst + copy_v, copy_data);
+    for (uint32_t i = copy_i + 1; i < copy_pieces; ++i) {
+      uint32_t v;
+      const uint4 *src = copy_src(i, &v);
+      store_global16(p.job.dst + v, load_global16(src));
+    }
+  }
 
   asm volatile("s_nop 15");
   asm volatile("s_nop 15");

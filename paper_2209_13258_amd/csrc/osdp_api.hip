@@ -14,6 +14,7 @@
 #include <cstring>
 #include <mutex>
 #include <string>
+#include <utility>
 #include <vector>
 
 #include "osdp_internal.h"
@@ -271,10 +272,15 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
         t_pair += accum_us(j, j + 2) + exposed;
       }
     }
-    // measured on configs 2 to 5 with both choices forced: sharing a launch was never slower and up to 6 % faster
-    // than the estimate predicted (two streams cost events and contend for memory), so it only loses when the
-    // estimate puts it clearly behind, as it does when the gathers dwarf the GEMMs (few tokens)
-    pair_fwd = pair_fwd && t_pair < 1.10 * t_single;
+    // With gathers that ride along inside the GEMM launches, one launch per slice exposes the first gather only.
+    // With gathers as launches of their own (measured on configs 2 to 5 with both choices forced) sharing a launch
+    // was never slower and up to 6 % faster than the estimate predicted (two streams cost events, and a gather kernel
+    // beside the GEMMs only takes turns with their tiles), so there it only loses when the estimate puts it clearly
+    // behind, as it does when the gathers dwarf the GEMMs (few tokens).
+    if (debug_options().fused_gather.load(std::memory_order_relaxed) != 0)
+      pair_fwd = pair_fwd && t_pair < t_single + gather_estimate_us(D * width(0));  // unpaired: only the first gather is exposed
+    else
+      pair_fwd = pair_fwd && t_pair < 1.10 * t_single;
     const int forced = debug_options().fwd_pair.load(std::memory_order_relaxed);  // testing: 0 never pairs, 1 pairs whenever the kernel can
     if (forced == 0) pair_fwd = false;
     if (forced == 1) {
@@ -313,6 +319,11 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
         const int64_t w = span(a, std::min(n, a + cand));
         t += rows ? gemm_estimate_us(w, O, T) : gemm_estimate_us(I, w, T);
       }
+      // the gathers of a staging group ride along with a dW launch that starts in the group: groups without
+      // one run theirs as launches of their own
+      if (debug_options().fused_gather.load(std::memory_order_relaxed) != 0)
+        for (int64_t g0 = 0; g0 < n; g0 += r->slots)
+          if (g0 % cand != 0) t += gather_estimate_us(D * span(g0, std::min<int64_t>(n, g0 + r->slots)));
       if (best < 0.0 || t < 0.97 * best) { best = t; per = cand; }
       if (cand == n) break;
     }
@@ -464,7 +475,23 @@ struct Profile {
   size_t max_launches = 0;
   std::vector<TimedLaunch> launches;
   std::vector<hipEvent_t> spare;  // timed events kept for reuse
+  int64_t carried_launches = 0;   // gathers that ran inside a GEMM launch
+  double carried_bytes = 0.0;
+  // filled by osdp_profile_end for osdp_profile_overlap: [start, stop) of every timed launch in ms from the first event
+  std::vector<std::pair<double, double>> gemm_iv, gather_iv;
 };
+
+// Total length of the union of intervals (sorts its argument).
+double union_length(std::vector<std::pair<double, double>> &iv) {
+  std::sort(iv.begin(), iv.end());
+  double total = 0.0, end = -1.0e300;
+  for (const auto &i : iv) {
+    if (i.second <= end) continue;
+    total += i.second - std::max(i.first, end);
+    end = i.second;
+  }
+  return total;
+}
 
 thread_local Profile t_profile;
 
@@ -505,11 +532,42 @@ hipError_t do_gather(const Resolved &r, const ShardTable &tab, const Slice &s, v
   });
 }
 
+// The gather of sub-slice range s into `slot`, as a request a GEMM launch can take along.
+GatherRequest gather_request(const Resolved &r, const ShardTable &tab, const Slice &s, void *slot) {
+  GatherRequest g{};
+  g.shards = tab;
+  g.layout = r.layout;
+  const int64_t w = s.c1 - s.c0;
+  if (r.rows) { g.r0 = s.c0; g.rows = w; g.c0 = 0; g.w = r.O; }
+  else { g.r0 = 0; g.rows = r.I; g.c0 = s.c0; g.w = w; }
+  g.staging = slot;
+  return g;
+}
+
+hipError_t gather_now(const GatherRequest &g, hipStream_t stream) {
+  return timed(OSDP_KERNEL_GATHER, 0.0, 4.0 * static_cast<double>(g.rows) * static_cast<double>(g.w), stream, [&] {
+    return launch_gather(g.shards, g.layout, g.r0, g.rows, g.c0, g.w, g.staging, stream);
+  });
+}
+
+// One GEMM launch; a gather attached to it (g.carry) runs inside the launch when its kernel can take it along, else
+// as a launch of its own right behind it.
 hipError_t do_gemm(int kind, const GemmProblem &g, hipStream_t stream) {
   const double M = g.M, N = g.N, K = g.K;
   const double out_bytes = g.epilogue == Epilogue::kF32Workspace ? 4.0 : 2.0;
   const double bytes = 2.0 * M * K + 2.0 * K * N + out_bytes * M * N + (g.acc_in ? 4.0 * M * N : 0.0);
-  return timed(kind, 2.0 * M * N * K, bytes, stream, [&] { return launch_gemm(g, stream); });
+  bool carried = false;
+  GemmProblem q = g;
+  q.carried = &carried;
+  hipError_t e = timed(kind, 2.0 * M * N * K, bytes, stream, [&] { return launch_gemm(q, stream); });
+  if (e != hipSuccess || !g.carry) return e;
+  if (!carried) return gather_now(*g.carry, stream);
+  Profile &pf = t_profile;
+  if (pf.active) {
+    pf.carried_launches += 1;
+    pf.carried_bytes += 4.0 * static_cast<double>(g.carry->rows) * static_cast<double>(g.carry->w);
+  }
+  return hipSuccess;
 }
 
 // The GEMM that consumes the staged sub-slices [j0, j1): one in B0, or two in B0 and B1.
@@ -651,7 +709,7 @@ const DebugSwitch kSwitches[] = {
     {"gemm_generic", &DebugOptions::gemm_generic, 0, 1}, {"tile", &DebugOptions::tile, -1, 3},
     {"deep", &DebugOptions::deep, -1, 1},                {"split_launch", &DebugOptions::split_launch, -1, 1},
     {"fwd_pair", &DebugOptions::fwd_pair, -1, 1},        {"poison_staging", &DebugOptions::poison_staging, 0, 1},
-    {"four_wave", &DebugOptions::four_wave, -1, 1},
+    {"four_wave", &DebugOptions::four_wave, -1, 1},      {"fused_gather", &DebugOptions::fused_gather, -1, 1},
 };
 }  // namespace
 
@@ -781,6 +839,26 @@ static osdp_status forward(const osdp_shape *shape, const osdp_plan *plan, int32
   // is on: with such launches there is nothing to overlap, and everything goes on the compute stream, event-free.
   bool pairs = false;
   for (const Slice &l : r.fwd) pairs = pairs || l.c1 - l.c0 == 2;
+  // One launch per sub-slice and two slots: the GEMM of sub-slice j takes the gather of sub-slice j+1 along, into
+  // the slot that the GEMM of sub-slice j-1 has finished with (it ran earlier on the same stream).  Only the first
+  // gather is a launch of its own; nothing else is exposed, and no second stream or event is involved.
+  const bool fused = r.slots == 2 && n > 1 && !pairs && debug_options().fused_gather.load(std::memory_order_relaxed) != 0;
+  if (fused) {
+    for (int j = 0; j < n; ++j) {
+      void *slot = ws + static_cast<size_t>(j % 2) * r.slot_bytes;
+      if (j == 0 && !r.dp[0]) OSDP_HIP(do_gather(r, tab, r.sub[0], slot, sc));
+      GemmProblem g = weight_gemm(r, /*is_fwd=*/true, j, j + 1, weights_of(r, rep, j, slot), WeightView{nullptr, 0}, X, ldx,
+                                  Y, ldy, acc, static_cast<size_t>(j), static_cast<size_t>(n));
+      GatherRequest next;
+      if (j + 1 < n && !r.dp[j + 1]) {
+        next = gather_request(r, tab, r.sub[j + 1], ws + static_cast<size_t>((j + 1) % 2) * r.slot_bytes);
+        g.carry = &next;
+      }
+      OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_FWD, g, sc));
+      if (poison && !r.dp[j]) OSDP_HIP(launch_fill16(slot, r.slot_bytes, kPoison, sc));
+    }
+    return OSDP_OK;
+  }
   const bool overlap = two_streams && r.slots == 2 && n > 1 && !pairs;
   hipStream_t sg = overlap ? sp : sc;
   hipEvent_t slot_free[2] = {nullptr, nullptr};  // recorded on the compute stream after the last GEMM that read the slot
@@ -920,8 +998,11 @@ static osdp_status backward(const osdp_shape *shape, const osdp_plan *plan, int3
   // The gathers of a group run on the copy stream behind dW.  Each group then costs four event operations, which
   // is more than a small gather takes (measured: with 4 MB groups one stream is 5-12 % faster, with 25 MB groups
   // two streams are 1 % faster), so small groups stay on the compute stream.
+  // Unless switched off, the gathers of a group do not run as launches of their own at all: the dW launches that
+  // precede the group's dX passes need no weights, and take them along (see the forward pass).
+  const bool fused = debug_options().fused_gather.load(std::memory_order_relaxed) != 0;
   constexpr double kWorthOverlappingUs = 14.0;
-  const bool overlap = two_streams && r.slots == 2 && n > 1 &&
+  const bool overlap = !fused && two_streams && r.slots == 2 && n > 1 &&
                        gather_estimate_us(static_cast<int64_t>(r.slot_bytes)) >= kWorthOverlappingUs;  // two slots of slot_bytes / 2 elements
   hipStream_t sg = overlap ? sp : sc;
   hipEvent_t released = nullptr;  // recorded on the compute stream when a group's last GEMM has been enqueued
@@ -936,9 +1017,17 @@ static osdp_status backward(const osdp_shape *shape, const osdp_plan *plan, int3
     // (a pair of gathered sub-slices that one dX launch will read: one copy, across the two slots)
     const bool joint = staged_jointly(r, g0, g1) && next_pass < r.pass.size() && r.pass[next_pass].c0 == g0 &&
                        r.pass[next_pass].c1 == g1;
-    if (joint) OSDP_HIP(do_gather(r, tab, joint_range(r, g0), ws, sg));
-    for (int j = g0; j < g1 && !joint; ++j)
-      if (!r.dp[j]) OSDP_HIP(do_gather(r, tab, r.sub[j], ws + static_cast<size_t>(j - g0) * r.slot_bytes, sg));
+    GatherRequest pending[2];
+    int n_pending = 0, next_pending = 0;
+    if (fused) {
+      if (joint) pending[n_pending++] = gather_request(r, tab, joint_range(r, g0), ws);
+      for (int j = g0; j < g1 && !joint; ++j)
+        if (!r.dp[j]) pending[n_pending++] = gather_request(r, tab, r.sub[j], ws + static_cast<size_t>(j - g0) * r.slot_bytes);
+    } else {
+      if (joint) OSDP_HIP(do_gather(r, tab, joint_range(r, g0), ws, sg));
+      for (int j = g0; j < g1 && !joint; ++j)
+        if (!r.dp[j]) OSDP_HIP(do_gather(r, tab, r.sub[j], ws + static_cast<size_t>(j - g0) * r.slot_bytes, sg));
+    }
     hipEvent_t gathered = nullptr;
     if (overlap) {
       OSDP_HIP(g_events.get(&gathered));
@@ -946,9 +1035,11 @@ static osdp_status backward(const osdp_shape *shape, const osdp_plan *plan, int3
     }
     // dW launches whose range starts in this group: they need no weights and run while the gathers are in flight
     for (; next_dw < r.dw.size() && r.dw[next_dw].c0 < g1; ++next_dw) {
-      const GemmProblem gw = dw_gemm(r, static_cast<int>(r.dw[next_dw].c0), static_cast<int>(r.dw[next_dw].c1), X, ldx, dY, lddy, gtab, rep);
+      GemmProblem gw = dw_gemm(r, static_cast<int>(r.dw[next_dw].c0), static_cast<int>(r.dw[next_dw].c1), X, ldx, dY, lddy, gtab, rep);
+      if (next_pending < n_pending) gw.carry = &pending[next_pending++];
       OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DW, gw, sc));
     }
+    for (; next_pending < n_pending; ++next_pending) OSDP_HIP(gather_now(pending[next_pending], sc));  // no dW launch left to take it along
     if (overlap) OSDP_HIP(hipStreamWaitEvent(sc, gathered, 0));
     // the dX launches of the group (column slices: the fp32 partial sum is carried in the workspace between them)
     for (; next_pass < r.pass.size() && r.pass[next_pass].c1 <= g1; ++next_pass) {
@@ -1133,6 +1224,8 @@ osdp_status osdp_profile_begin(int32_t max_launches) {
     pf.spare.push_back(t.stop);
   }
   pf.launches.clear();
+  pf.carried_launches = 0;
+  pf.carried_bytes = 0.0;
   pf.max_launches = static_cast<size_t>(max_launches);
   pf.active = true;
   return OSDP_OK;
@@ -1145,9 +1238,13 @@ osdp_status osdp_profile_end(osdp_kernel_stats *stats) {
   pf.active = false;
   std::memset(stats, 0, sizeof(osdp_kernel_stats) * OSDP_KERNEL_KINDS);
   OSDP_HIP(hipDeviceSynchronize());
+  pf.gemm_iv.clear();
+  pf.gather_iv.clear();
   for (TimedLaunch &t : pf.launches) {
-    float ms = 0.f;
+    float ms = 0.f, from0 = 0.f;
     OSDP_HIP(hipEventElapsedTime(&ms, t.start, t.stop));
+    OSDP_HIP(hipEventElapsedTime(&from0, pf.launches.front().start, t.start));
+    (t.kind == OSDP_KERNEL_GATHER ? pf.gather_iv : pf.gemm_iv).push_back({from0, static_cast<double>(from0) + ms});
     osdp_kernel_stats &s = stats[t.kind];
     s.launches += 1;
     s.ms += ms;
@@ -1157,6 +1254,25 @@ osdp_status osdp_profile_end(osdp_kernel_stats *stats) {
     pf.spare.push_back(t.stop);
   }
   pf.launches.clear();
+  stats[OSDP_KERNEL_GATHER_CARRIED].launches = pf.carried_launches;
+  stats[OSDP_KERNEL_GATHER_CARRIED].bytes = pf.carried_bytes;
+  return OSDP_OK;
+}
+
+osdp_status osdp_profile_overlap(double *span_ms, double *idle_ms, double *gather_exposed_ms) {
+  Profile &pf = t_profile;
+  if (pf.active) return fail(OSDP_ERR_INVALID_ARG, "osdp_profile_end has not been called");
+  std::vector<std::pair<double, double>> all = pf.gemm_iv, gemm = pf.gemm_iv, gather = pf.gather_iv;
+  all.insert(all.end(), gather.begin(), gather.end());
+  double lo = 0.0, hi = 0.0;
+  for (size_t i = 0; i < all.size(); ++i) {
+    lo = i ? std::min(lo, all[i].first) : all[i].first;
+    hi = i ? std::max(hi, all[i].second) : all[i].second;
+  }
+  const double busy = union_length(all), busy_gemm = union_length(gemm);
+  if (span_ms) *span_ms = hi - lo;
+  if (idle_ms) *idle_ms = (hi - lo) - busy;
+  if (gather_exposed_ms) *gather_exposed_ms = busy - busy_gemm;  // time covered by gathers and by no GEMM
   return OSDP_OK;
 }
 

@@ -52,13 +52,13 @@ __global__ __launch_bounds__(kThreads) void gather_slice_kernel(
           s = static_cast<uint32_t>(f / static_cast<uint64_t>(lay.L));
           off = f - static_cast<uint64_t>(s) * lay.L;
         }
-        val[u] = *reinterpret_cast<const uint4 *>(s_tab[s] + off);
+        val[u] = load_global16(s_tab[s] + off);
       }
     }
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const uint64_t v = base + u * kThreads + threadIdx.x;
-      if (v < total_vecs) dst[v] = val[u];
+      if (v < total_vecs) store_global16(dst + v, val[u]);
     }
   }
 }

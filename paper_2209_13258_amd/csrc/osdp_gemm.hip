@@ -178,11 +178,11 @@ hipError_t launch_dma(const GemmParams &p, hipStream_t stream) {
 }
 
 // The four-wave 256 x 256 kernel: two K blocks of 64 in LDS (128 KB).
-template <bool kAK, bool kBK, int kEpi, bool kAccIn>
+template <bool kAK, bool kBK, int kEpi, bool kAccIn, bool kCopy>
 hipError_t launch_w4(const GemmParams &p, hipStream_t stream) {
   constexpr size_t lds = 2 * (256 + 256) * 64 * sizeof(uint16_t);
-  static_assert(lds + OSDP_MAX_SHARDS * 8 <= 160 * 1024, "tile does not fit the 160 KB of LDS");
-  auto kernel = gemm_w4_kernel<kAK, kBK, kEpi, kAccIn>;
+  static_assert(lds + 2 * OSDP_MAX_SHARDS * 8 <= 160 * 1024, "tile does not fit the 160 KB of LDS");
+  auto kernel = gemm_w4_kernel<kAK, kBK, kEpi, kAccIn, kCopy>;
   static bool configured[kMaxDevices] = {};
   hipError_t e = allow_lds(kernel, lds, configured);
   if (e != hipSuccess) return e;
@@ -194,6 +194,7 @@ hipError_t launch_w4(const GemmParams &p, hipStream_t stream) {
 constexpr int kCUs = 256;
 constexpr int kShortK = 1024;
 constexpr int kW4MinK = 192;  // the four-wave kernel's K loop assumes at least three K blocks of 64
+constexpr int kW4MinKdW = 8192;
 
 // Estimated cost of covering M x N with BM x BN tiles on 256 CUs: tiles per CU times the tile's area, with a
 // penalty for the lower MFMA efficiency of smaller tiles.  Tiles that run two to a CU were measured in pairs; a
@@ -256,8 +257,9 @@ int best_tile(int M, int N, int n_split, int kind, double *cost) {
   return best;
 }
 
+// *carry: the launch has a gather to carry (GemmParams::job is filled in); cleared by the launch that takes it.
 template <bool kAK, bool kBK, int kEpi, bool kAccIn>
-hipError_t launch_best(const GemmParams &p, hipStream_t stream) {
+hipError_t launch_best(const GemmParams &p, hipStream_t stream, bool *carry) {
   constexpr int kind = layout_kind(kAK, kBK);
   if (fast_path(p.M, p.N, p.K, p.k_split, p.n_split)) {
     int best = best_tile(p.M, p.N, p.n_split, kind, nullptr);
@@ -280,10 +282,20 @@ hipError_t launch_best(const GemmParams &p, hipStream_t stream) {
     // the whole LDS for a deeper pipeline instead (twice the bytes in flight).
     const bool deep = best > 0 && static_cast<long>(p.M / kTiles[best].bm) * (p.N / kTiles[best].bn) <= kCUs &&
                       debug_options().deep.load(std::memory_order_relaxed) != 0;  // testing: 0 keeps the shallow pipelines
+    const int fw = debug_options().four_wave.load(std::memory_order_relaxed);  // testing: 0 never, 1 whenever it can
     switch (best) {
       case 0:
-        if (p.K >= kW4MinK && debug_options().four_wave.load(std::memory_order_relaxed) != 0)
-          return launch_w4<kAK, kBK, kEpi, kAccIn>(p, stream);
+        // (dW, both operands MN-contiguous: twice the fragment-read instructions and a serial epilogue per wave;
+        // measured through the library, the four-wave kernel is 4-9 % ahead from K = 8192 and 3 % behind at K = 4096)
+        if (p.K >= kW4MinK && fw != 0 && (fw == 1 || p.K >= (kind == 1 ? kW4MinKdW : kW4MinK))) {
+          if constexpr (!(kAK && kBK)) {  // dX launches read every staged slice there is: they never carry a gather
+            if (*carry) {
+              *carry = false;
+              return launch_w4<kAK, kBK, kEpi, kAccIn, true>(p, stream);
+            }
+          }
+          return launch_w4<kAK, kBK, kEpi, kAccIn, false>(p, stream);
+        }
         if (kind == 0) return launch_dma<256, 256, 64, 128, 64, 2, kAK, kBK, kEpi, kAccIn>(p, stream);
         return launch_dma<256, 256, 64, 128, 32, 4, kAK, kBK, kEpi, kAccIn>(p, stream);
       case 1:
@@ -367,22 +379,22 @@ double plan_launches(int M, int N, int K, int kind, int *axis, int *cut) {
 }
 
 template <bool kAK, bool kBK, int kEpi, bool kAccIn>
-hipError_t launch_planned(const GemmParams &p, hipStream_t stream) {
+hipError_t launch_planned(const GemmParams &p, hipStream_t stream, bool *carry) {
   if (!p.k_split && !p.n_split && fast_path(p.M, p.N, p.K, 0, 0)) {
     int axis, cut;
     plan_launches(p.M, p.N, p.K, layout_kind(kAK, kBK), &axis, &cut);
     if (axis == 1) {
-      hipError_t e = launch_best<kAK, kBK, kEpi, kAccIn>(column_range<kBK, kEpi>(p, 0, cut), stream);
+      hipError_t e = launch_best<kAK, kBK, kEpi, kAccIn>(column_range<kBK, kEpi>(p, 0, cut), stream, carry);
       if (e != hipSuccess) return e;
-      return launch_best<kAK, kBK, kEpi, kAccIn>(column_range<kBK, kEpi>(p, cut, p.N), stream);
+      return launch_best<kAK, kBK, kEpi, kAccIn>(column_range<kBK, kEpi>(p, cut, p.N), stream, carry);
     }
     if (axis == 0) {
-      hipError_t e = launch_best<kAK, kBK, kEpi, kAccIn>(row_range<kAK, kEpi>(p, 0, cut), stream);
+      hipError_t e = launch_best<kAK, kBK, kEpi, kAccIn>(row_range<kAK, kEpi>(p, 0, cut), stream, carry);
       if (e != hipSuccess) return e;
-      return launch_best<kAK, kBK, kEpi, kAccIn>(row_range<kAK, kEpi>(p, cut, p.M), stream);
+      return launch_best<kAK, kBK, kEpi, kAccIn>(row_range<kAK, kEpi>(p, cut, p.M), stream, carry);
     }
   }
-  return launch_best<kAK, kBK, kEpi, kAccIn>(p, stream);
+  return launch_best<kAK, kBK, kEpi, kAccIn>(p, stream, carry);
 }
 
 }  // namespace
@@ -428,10 +440,9 @@ hipError_t check_device() {
   return v > 0 ? hipSuccess : hipErrorInvalidDevice;
 }
 
-hipError_t launch_gemm(const GemmProblem &q, hipStream_t stream) {
-  if (q.M < 0 || q.N < 0 || q.K < 0) return hipErrorInvalidValue;
-  if (q.M == 0 || q.N == 0) return hipSuccess;  // nothing to write; K == 0 still writes the empty sum
-  GemmParams p;
+namespace {
+hipError_t dispatch_gemm(const GemmProblem &q, hipStream_t stream, bool *carry) {
+  GemmParams p{};
   p.M = q.M; p.N = q.N; p.K = q.K;
   p.A = static_cast<const uint16_t *>(q.A); p.lda = q.lda;
   p.B = static_cast<const uint16_t *>(q.B); p.ldb = q.ldb;
@@ -440,6 +451,15 @@ hipError_t launch_gemm(const GemmProblem &q, hipStream_t stream) {
   p.lay = q.layout; p.c0 = q.c0; p.r0 = q.r0; p.shards = q.shards;
   p.B2 = static_cast<const uint16_t *>(q.B2); p.ldb2 = q.ldb2;
   p.k_split = q.B2 ? q.k_split : 0; p.n_split = q.B2 ? q.n_split : 0;
+  if (*carry) {
+    const GatherRequest &g = *q.carry;
+    const uint64_t total = static_cast<uint64_t>(g.rows) * (static_cast<uint64_t>(g.w) / 8);
+    if (g.w % 8 || (total >> 32) || (reinterpret_cast<uintptr_t>(g.staging) & 15u)) return hipErrorInvalidValue;
+    p.job.src = g.shards; p.job.lay = g.layout;
+    p.job.r0 = static_cast<uint32_t>(g.r0); p.job.c0 = static_cast<uint64_t>(g.c0);
+    p.job.vecs_per_row = static_cast<uint32_t>(g.w / 8); p.job.total_vecs = total;
+    p.job.dst = static_cast<uint4 *>(g.staging);
+  }
   if ((p.k_split || p.n_split) && !q.a_kcontig) return hipErrorInvalidValue;  // dW never takes a second segment
   if (p.k_split && p.n_split) return hipErrorInvalidValue;
   constexpr int kRow = static_cast<int>(Epilogue::kBf16RowMajor), kShard = static_cast<int>(Epilogue::kBf16ShardMajor),
@@ -447,18 +467,33 @@ hipError_t launch_gemm(const GemmProblem &q, hipStream_t stream) {
   const bool acc = q.acc_in != nullptr;
   // The three GEMMs of the split linear layer, with the four accumulate forms for forward and dX, are the only combinations built.
   if (q.a_kcontig && !q.b_kcontig) {                                               // forward (accumulating when the reduction dimension is split)
-    if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_planned<true, false, kRow, true>(p, stream) : launch_planned<true, false, kRow, false>(p, stream);
-    if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_planned<true, false, kF32, true>(p, stream) : launch_planned<true, false, kF32, false>(p, stream);
+    if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_planned<true, false, kRow, true>(p, stream, carry) : launch_planned<true, false, kRow, false>(p, stream, carry);
+    if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_planned<true, false, kF32, true>(p, stream, carry) : launch_planned<true, false, kF32, false>(p, stream, carry);
   }
   if (!q.a_kcontig && !q.b_kcontig && !acc) {                                      // dW: into the shards, or (DP slice) a plain array
-    if (q.epilogue == Epilogue::kBf16ShardMajor) return launch_planned<false, false, kShard, false>(p, stream);
-    if (q.epilogue == Epilogue::kBf16RowMajor) return launch_planned<false, false, kRow, false>(p, stream);
+    if (q.epilogue == Epilogue::kBf16ShardMajor) return launch_planned<false, false, kShard, false>(p, stream, carry);
+    if (q.epilogue == Epilogue::kBf16RowMajor) return launch_planned<false, false, kRow, false>(p, stream, carry);
   }
   if (q.a_kcontig && q.b_kcontig) {                                                // dX
-    if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_planned<true, true, kRow, true>(p, stream) : launch_planned<true, true, kRow, false>(p, stream);
-    if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_planned<true, true, kF32, true>(p, stream) : launch_planned<true, true, kF32, false>(p, stream);
+    if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_planned<true, true, kRow, true>(p, stream, carry) : launch_planned<true, true, kRow, false>(p, stream, carry);
+    if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_planned<true, true, kF32, true>(p, stream, carry) : launch_planned<true, true, kF32, false>(p, stream, carry);
   }
   return hipErrorInvalidValue;
+}
+}  // namespace
+
+hipError_t launch_gemm(const GemmProblem &q, hipStream_t stream) {
+  if (q.M < 0 || q.N < 0 || q.K < 0) return hipErrorInvalidValue;
+  const GatherRequest *g = q.carry;
+  const bool has_gather = g && g->rows > 0 && g->w > 0;
+  if (has_gather && !q.carried) return hipErrorInvalidValue;  // the caller must learn whether the gather is still to do
+  bool carry = has_gather;
+  if (q.M > 0 && q.N > 0) {  // else nothing to write; K == 0 still writes the empty sum
+    const hipError_t e = dispatch_gemm(q, stream, &carry);
+    if (e != hipSuccess) return e;
+  }
+  if (q.carried) *q.carried = has_gather && !carry;
+  return hipSuccess;
 }
 
 }  // namespace osdp

@@ -9,6 +9,22 @@
 
 namespace osdp {
 
+// 16- and 8-byte accesses through pointers that are known to be device (global) memory but that the compiler sees as
+// generic, e.g. shard pointers fetched from a table in LDS: without the address space it emits FLAT instructions,
+// which check the address against the LDS and scratch apertures and count on both memory counters.
+typedef unsigned int osdp_u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int osdp_u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 load_global16(const void *p) {
+  const osdp_u32x4 v = *(const __attribute__((address_space(1))) osdp_u32x4 *)(p);
+  return uint4{v[0], v[1], v[2], v[3]};
+}
+__device__ __forceinline__ void store_global16(void *p, uint4 v) {
+  *(__attribute__((address_space(1))) osdp_u32x4 *)(p) = osdp_u32x4{v.x, v.y, v.z, v.w};
+}
+__device__ __forceinline__ void store_global8(void *p, uint2 v) {
+  *(__attribute__((address_space(1))) osdp_u32x2 *)(p) = osdp_u32x2{v.x, v.y};
+}
+
 // Device pointers of the N shard buffers, passed to kernels by value.
 struct ShardTable {
   void *p[OSDP_MAX_SHARDS];
@@ -28,6 +44,14 @@ enum class Epilogue : int32_t {
   kBf16RowMajor = 0,   // C -> bf16, row-major with ldc
   kBf16ShardMajor = 1, // C -> bf16, scattered into the shard-major layout at column offset c0
   kF32Workspace = 2    // C -> fp32, row-major with ldc (the dX accumulator between slices)
+};
+
+// A slice gather: Ws[r, c] = W[r0 + r, c0 + c] for r < rows, c < w, into the dense row-major staging [rows x w].
+struct GatherRequest {
+  ShardTable shards;
+  ShardLayout layout;
+  int64_t r0, rows, c0, w;
+  void *staging;
 };
 
 // One GEMM launch: C[M x N] (+)= A[M x K] . B[K x N], bf16 inputs, fp32 accumulate.
@@ -55,6 +79,11 @@ struct GemmProblem {
   ShardTable shards;    // kBf16ShardMajor only
   int64_t c0;           // kBf16ShardMajor only: column offset of C inside the full matrix
   int64_t r0;           // kBf16ShardMajor only: row offset of C inside the full matrix
+  // Optional: a gather (into a staging slot this launch does not read) that the launch may take along.  The
+  // four-wave kernel runs it inside the launch, in the shadow of its MFMAs, and sets *carried; any other kernel
+  // leaves *carried false and the gather to the caller.  carried must be given when carry is.
+  const GatherRequest *carry;
+  bool *carried;
 };
 
 // Enqueue on `stream`.  Returns hipSuccess or the launch error.
@@ -87,7 +116,8 @@ struct DebugOptions {
   std::atomic<int32_t> deep{-1};           // 0: launches of at most one tile per CU keep the shallow pipelines
   std::atomic<int32_t> split_launch{-1};   // 0: no whole-rounds + remainder launches
   std::atomic<int32_t> fwd_pair{-1};       // 0: the forward never pairs staged slices; 1: whenever the kernel can
-  std::atomic<int32_t> four_wave{-1};      // 0: 256 x 256 tiles run on the eight-wave kernel
+  std::atomic<int32_t> fused_gather{-1};   // 0: gathers always run as launches of their own (second stream where given)
+  std::atomic<int32_t> four_wave{-1};      // 0: 256 x 256 tiles run on the eight-wave kernel; 1: on the four-wave kernel wherever it can
   std::atomic<int32_t> poison_staging{0};  // 1: staging slots hold NaN patterns whenever no gathered slice is live in them
 };
 DebugOptions &debug_options();

@@ -16,7 +16,7 @@ def H():
     return gpu_harness
 
 
-DEBUG_DEFAULTS = {"four_wave": -1, "gemm_generic": 0, "tile": -1, "deep": -1, "split_launch": -1, "fwd_pair": -1, "poison_staging": 0}
+DEBUG_DEFAULTS = {"four_wave": -1, "fused_gather": -1, "gemm_generic": 0, "tile": -1, "deep": -1, "split_launch": -1, "fwd_pair": -1, "poison_staging": 0}
 
 
 @pytest.fixture
@@ -730,9 +730,12 @@ def test_every_tile_shape_gives_the_bits_of_the_checked_kernel(H, oracle, T, I, 
     sc, sp = H.streams()
     # these shapes give every launch at most one tile per CU, where the library would use its deep-pipeline
     # variants of tiles 1..3 only: both pipelines of each tile are forced in turn
-    for tile, deep in (("0", "1"), ("1", "0"), ("1", "1"), ("2", "0"), ("2", "1"), ("3", "0"), ("3", "1")):
+    # (tile 0 twice: on the eight-wave kernel, and on the four-wave kernel also where the library would not pick it)
+    for tile, deep, four_wave in (("0", "1", 0), ("0", "1", 1), ("1", "0", -1), ("1", "1", -1), ("2", "0", -1), ("2", "1", -1),
+                                  ("3", "0", -1), ("3", "1", -1)):
         debug("tile", tile)
         debug("deep", deep)
+        debug("four_wave", four_wave)
         for k, dim in ((1, 0), (2, 0), (2, 1)):
             _announce("tile", tile, "deep", deep, T, I, O, N, "k", k, "dim", dim)
             plan = osdp.Plan([k], staging=osdp.OSDP_STAGING_DOUBLE, split_dim_per_op=[dim])
@@ -1000,12 +1003,14 @@ def test_whole_rounds_plus_remainder_launches_keep_the_bits(H, oracle, T, I, O, 
 
 
 # ------------------------------------------------ debug mode: poisoned staging slots
+@pytest.mark.parametrize("fused", [-1, 0])
 @pytest.mark.parametrize("pair", [0, 1])
 @pytest.mark.parametrize("rows", [False, True])
-def test_poisoned_staging_slots_change_nothing(H, oracle, rows, pair, debug):
+def test_poisoned_staging_slots_change_nothing(H, oracle, rows, pair, fused, debug):
     """With the staging slots filled with NaN patterns whenever no gathered slice is live in them, a GEMM that ran
     ahead of its gather or a gather that landed on a slice still in use would put NaN (or wrong values) into the
-    outputs: every staging mode, one and two streams, both forward schedules, repeated calls on one workspace."""
+    outputs: every staging mode, one and two streams, both forward schedules, gathers carried inside the GEMM launches
+    and gathers as launches of their own, repeated calls on one workspace."""
     import paper_2209_13258_amd as osdp
     T, I, O, N = 512, 1024, 2048, 8
     d = wl.small_case(131, T, I, O, N)
@@ -1017,6 +1022,7 @@ def test_poisoned_staging_slots_change_nothing(H, oracle, rows, pair, debug):
     base = base_op.results()
     debug("poison_staging", 1)
     debug("fwd_pair", pair)
+    debug("fused_gather", fused)
     sc, sp = H.streams()
     for k in (2, 4, 8):
         for mode in (osdp.OSDP_STAGING_SINGLE, osdp.OSDP_STAGING_DOUBLE, osdp.OSDP_STAGING_HALF):
@@ -1035,3 +1041,38 @@ def test_poisoned_staging_slots_change_nothing(H, oracle, rows, pair, debug):
                     assert np.array_equal(got[name], base[name]), f"{name} differs from the unsplit result"
     for name in ("Y", "dX", "dW"):
         H.assert_close(name, base[name], ref[name])
+
+
+@pytest.mark.parametrize("T,I,O,N", [(512, 1024, 2304, 9),    # 9 shards do not divide 1024 rows: the general flat map
+                                     (768, 2048, 1024, 8),    # row-block shards
+                                     (256, 512, 1024, 64)])   # 64 shards of 8 rows
+def test_gathers_carried_by_gemm_launches_match_the_gather_kernel(H, oracle, T, I, O, N, debug):
+    """A GEMM launch on the large tile takes the next slice's gather along; the staged bytes, and so every result
+    bit, must be those of the gather kernel: both split dimensions, every staging mode, k up to 4, against the
+    unsplit result and the oracle.  The shapes keep every launch on the kernel that can carry a gather."""
+    import paper_2209_13258_amd as osdp
+    d = wl.small_case(141, T, I, O, N)
+    ref = oracle.linear(d["X"], d["W_shards"], O, dY=d["dY"])
+    base_op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+    base_op.fwd(1)
+    base_op.bwd(1)
+    base = base_op.results()
+    for name in ("Y", "dX", "dW"):
+        H.assert_close(name, base[name], ref[name])
+    sc, sp = H.streams()
+    for fused in (-1, 0):
+        debug("fused_gather", fused)
+        for dim in (osdp.OSDP_SPLIT_OUT_FEATURES, osdp.OSDP_SPLIT_IN_FEATURES):
+            for k in (2, 4):
+                for mode in (osdp.OSDP_STAGING_SINGLE, osdp.OSDP_STAGING_DOUBLE, osdp.OSDP_STAGING_HALF):
+                    _announce("carried gathers", T, I, O, N, "fused", fused, "dim", dim, "k", k, "mode", mode)
+                    plan = osdp.Plan([k], staging=mode, split_dim_per_op=[dim])
+                    op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+                    torch.cuda.synchronize()
+                    with torch.cuda.stream(sc):
+                        op.fwd(k, plan=plan, streams=(sc, sp))
+                        op.bwd(k, plan=plan, streams=(sc, sp))
+                    sc.synchronize()
+                    got = op.results()
+                    for name in ("Y", "dX", "dW"):
+                        assert np.array_equal(got[name], base[name]), f"{name} differs from the unsplit result"
