@@ -48,6 +48,16 @@ __device__ __forceinline__ void mma_16x16x32_agpr(f32x4 &c, bf16x8 a_rows, bf16x
   asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(b_cols), "v"(a_rows));
 }
 
+// A wave-level direct-to-LDS load that is issued with all lanes off when `on` is 0 (it then moves nothing): the loads
+// of K blocks beyond the last, which the uniform K loop below would otherwise fetch for nobody.  All 64 lanes are
+// active wherever the kernel calls this, so EXEC is put back to all ones.
+__device__ __forceinline__ void dma16_if(uint32_t on, const uint16_t *src, uint32_t dst) {  // on: 0 or 0xffffffff
+  const uint32_t m0 = __builtin_amdgcn_readfirstlane(dst), half = __builtin_amdgcn_readfirstlane(on);
+  asm volatile("s_mov_b32 exec_lo, %0\n\ts_mov_b32 exec_hi, %0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
+               "global_load_lds_dwordx4 %2, off\n\ts_mov_b64 exec, -1"
+               ::"s"(half), "s"(m0), "v"(src) : "memory");
+}
+
 // One operand's share of a ring slot: 256 rows (or columns) x 64 k, 32 KB, filled by 32 wave-level
 // direct-to-LDS loads of 1 KB, eight per wave.
 template <bool kKC>
@@ -190,15 +200,16 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
 #pragma unroll
   for (int i = 0; i < OpB::kLoads; ++i) dstB[i] = OpA::kElems * 2 + OpB::chunk(wave, i) * 1024;
 
+  uint32_t load_mask = ~0u;  // all lanes while there are K blocks left to load, none afterwards
   auto issue = [&](int slot, auto idx, int64_t advA, int64_t advB) {
     constexpr int i = decltype(idx)::value;
     const uint32_t sb = lds_base + slot * (kSlotElems * 2);
     if constexpr (i < OpA::kLoads) {
-      dma16(srcA[i], sb + dstA[i]);
+      dma16_if(load_mask, srcA[i], sb + dstA[i]);
       srcA[i] += advA;
     } else {
       constexpr int j = i - OpA::kLoads;
-      dma16(srcB[j], sb + dstB[j]);
+      dma16_if(load_mask, srcB[j], sb + dstB[j]);
       srcB[j] += advB;
     }
   };
@@ -263,8 +274,8 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
     });
   };
 
-  // Every block runs the same code: the last two blocks still issue loads (of the last block again, into slots
-  // nobody reads any more) and the last still reads fragments nobody uses.  The host sends K >= 192.
+  // Every block runs the same code: the last two blocks still issue their load instructions (with every lane off,
+  // see dma16_if) and the last still reads fragments nobody uses.  The host sends K >= 192.
   int cur = 0;
   int ahead = 2;  // index of the block the source pointers stand at
   for (int b = 0; b < nb; ++b) {
@@ -277,8 +288,9 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
     const bool advance = ahead + 1 < nb;
+    load_mask = ahead < nb ? ~0u : 0u;  // this step loads block `ahead`: there is none beyond nb - 1
     kstep(Int<1>{}, Int<1>{}, sn, 0, cur, advance ? stepA : 0, advance ? stepB : 0, advance);
-    ahead += advance ? 1 : 0;
+    ahead += 1;
     cur ^= 1;
   }
   wait_vmcnt<0>();  // surplus loads must have landed before the workgroup gives its LDS back
