@@ -418,6 +418,9 @@ def main():
         "device_memory_allocated_during_steps_bytes": int(alloc_delta),
         "roofline": m["roofline"], "gathers": m["gathers"], "idle_us_per_step": m["idle_us_per_step"],
         "kernels": m["kernels"],
+        # steps of the headline workload run so far (warm-up, timed region, individually timed steps, instrumented
+        # pass): what a kernel trace of `--no-sweep --no-auto` divides by
+        "headline_steps_executed": a.warmup + a.steps + a.warmup + max(a.steps, 20) + 2 + max(10, max(a.steps, 20) // 2),
     }
     sub_steps, sub_warm = max(20, a.steps // 2), max(3, a.warmup // 2)
 
