@@ -168,7 +168,9 @@ OSDP_API osdp_status osdp_split_linear_gather_row_slice(const osdp_shape *shape,
  * needs, and how many of them hold gathered weights at the peak
  * (Section 3.3: size(MatMul)/slice_granularity per live slice).
  * Workspace layout: [staging slots][fp32 accumulator: T*I for dX, backward with column slices and more than
- * one dX launch; T*O for Y, forward with row slices and more than one launch].
+ * one dX launch; T*O for Y, forward with row slices and more than one launch][fp32 planes: forward with column
+ * slices, T <= 4096 and I >= 16384, where the product is summed in parts of 8192 input features: parts x T x
+ * (columns of the widest launch) x 4 bytes].
  * With OSDP_STAGING_AUTO the total covers both the one-stream and the two-stream call.
  * Either output pointer may be NULL. Host only. */
 OSDP_API osdp_status osdp_split_linear_workspace_bytes(const osdp_shape *shape, const osdp_plan *plan,
@@ -189,7 +191,11 @@ OSDP_API osdp_status osdp_split_linear_workspace_bytes(const osdp_shape *shape, 
  * Y += X[:, r0_j:r1_j] . Wr_j, the sum carried in fp32 (through the workspace between launches) in ascending
  * j and rounded to bf16 once.
  * Y is bit-identical for every k, staging mode and stream choice (row slices: when every slice height is a
- * multiple of 16). */
+ * multiple of 16).  With column slices, T <= 4096 and I >= 16384 (few output tiles per slice, a long reduction)
+ * the product is the sum over min(I / 8192, 8) parts of the input features, each part accumulated on its own and
+ * the parts added in ascending order in fp32 before the one rounding to bf16 (when that number of parts times 64
+ * divides I): the unsplit operator (k = 1) is computed the same way, so this too is independent of k.  (Row slices always
+ * continue one accumulator chain.) */
 OSDP_API osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index,
                                   const void *X, int64_t ldx, const void *const *w_shards,
                                   void *Y, int64_t ldy, void *workspace, size_t workspace_bytes,
@@ -381,12 +387,14 @@ OSDP_API osdp_status osdp_plan_search(const osdp_operator_cost *ops, int32_t n, 
 
 /* ---- test and debug switches ------------------------------------------------
  * Process-wide switches for tests and for hunting stream races; none of them
- * changes a result bit.  Initial values come from the environment variables
+ * but "split_k" changes a result bit.  Initial values come from the environment variables
  * OSDP_DEBUG_<NAME IN CAPITALS>, read once when the library is first used.
  *   "gemm_generic"   0 | 1   1: every GEMM runs on the bounds-checked kernel
  *   "tile"          -1 .. 3  force tile shape 256x256, 256x128, 128x256, 128x128 where it divides the launch
  *   "deep"          -1 | 0   0: launches of at most one tile per CU keep the shallow LDS pipelines
  *   "split_launch"  -1 | 0   0: no launch is cut into whole rounds of large tiles + remainder
+ *   "split_k"       -1 | 0   0: forward products are never summed in parts of the reduction (the one switch that
+ *                            changes result bits: those of the products that are otherwise summed in parts)
  *   "four_wave"     -1 .. 1  0: 256x256 tiles always run on the eight-wave kernel; 1: on the four-wave kernel
  *                            whenever it takes the launch (K >= 192), also where the eight-wave one measured faster
  *   "fused_gather"  -1 | 0   0: every gather is a launch of its own (on stream_copy where the pipeline overlaps);

@@ -41,6 +41,8 @@ struct GemmParams {
   int64_t ldb2;
   int32_t k_split;     // 0: none
   int32_t n_split;     // 0: none
+  int32_t k_parts;     // > 1 (fp32 workspace epilogue with ldc = N, no second K segment): the grid is k_parts times the
+                       // tiles, part s takes k in [s K / k_parts, (s + 1) K / k_parts) and writes plane s of C ([M x N] fp32 each)
   void *C;
   int64_t ldc;
   const float *acc_in;
@@ -71,17 +73,25 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 constexpr int kXcds = 8;
 constexpr int kGroupM = 4;
 
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int *tm, int *tn) {
+// Logical id of this workgroup: the ids an XCD runs are consecutive.
+__device__ __forceinline__ int logical_block() {
   const int nb = gridDim.x, bid = blockIdx.x;
   const int xcd = bid % kXcds, idx = bid / kXcds;
   const int base = nb / kXcds, rem = nb % kXcds;
-  const int pid = xcd * base + (xcd < rem ? xcd : rem) + idx;
+  return xcd * base + (xcd < rem ? xcd : rem) + idx;
+}
+
+__device__ __forceinline__ void tile_of_pid(int pid, int tiles_m, int tiles_n, int *tm, int *tn) {
   const int per_group = kGroupM * tiles_n;
   const int group = pid / per_group, in_group = pid - group * per_group;
   const int first_m = group * kGroupM;
   const int gm = (tiles_m - first_m) < kGroupM ? (tiles_m - first_m) : kGroupM;
   *tm = first_m + in_group % gm;
   *tn = in_group / gm;
+}
+
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int *tm, int *tn) {
+  tile_of_pid(logical_block(), tiles_m, tiles_n, tm, tn);
 }
 
 // Accumulator layout of one wave: acc[bm][bn][i] is C[m][n] with

@@ -140,24 +140,36 @@ void gemm_dma_kernel(GemmParams p, int tiles_m, int tiles_n) {
   if (kEpi == static_cast<int>(Epilogue::kBf16ShardMajor)) {
     if (tid < OSDP_MAX_SHARDS) s_tab[tid] = static_cast<uint16_t *>(p.shards.p[tid]);
   }
+  // A launch split along K: the logical ids of one part are consecutive, each part runs its own range of k and
+  // stores its own fp32 plane (the planes lie one below the other: ldc = N).
   int tm, tn;
-  tile_of_block(tiles_m, tiles_n, &tm, &tn);
+  int pid = logical_block();
+  int K = p.K, plane_row = 0;
+  int64_t k0 = 0;
+  if (p.k_parts > 1) {
+    const int tiles = tiles_m * tiles_n, part = pid / tiles;
+    pid -= part * tiles;
+    K = p.K / p.k_parts;
+    k0 = static_cast<int64_t>(part) * K;
+    plane_row = part * p.M;
+  }
+  tile_of_pid(pid, tiles_m, tiles_n, &tm, &tn);
   const int m0 = tm * BM, n0 = tn * BN;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave / (BN / WN)) * WM, wn = (wave % (BN / WN)) * WN;
   const int l16 = lane & 15, q4 = lane >> 4;
 
-  const uint16_t *gA = (kAK ? p.A + static_cast<int64_t>(m0) * p.lda : p.A + m0) + OpA::lane_src(wave, lane, p.lda);
+  const uint16_t *gA = (kAK ? p.A + static_cast<int64_t>(m0) * p.lda + k0 : p.A + m0 + k0 * p.lda) + OpA::lane_src(wave, lane, p.lda);
   // B may come in two column segments (two staged slices): the tile lies in one of them
   const bool second = p.n_split && n0 >= p.n_split;
   const uint16_t *baseB = second ? p.B2 : p.B;
   const int64_t ldb = second ? p.ldb2 : p.ldb;
   const int nB = second ? n0 - p.n_split : n0;
-  const uint16_t *tileB = kBK ? baseB + static_cast<int64_t>(nB) * ldb : baseB + nB;
+  const uint16_t *tileB = kBK ? baseB + static_cast<int64_t>(nB) * ldb + k0 : baseB + nB + k0 * ldb;
   const uint16_t *gB = tileB + OpB::lane_src(wave, lane, ldb);
   const int64_t lsA = OpA::load_stride(p.lda), lsB = OpB::load_stride(ldb);
   const int64_t bsA = OpA::block_stride(p.lda), bsB = OpB::block_stride(ldb);
-  const int nk = p.K / BK;
+  const int nk = K / BK;
 
   f32x4 acc[MB][NB];
   if (kAccIn) {
@@ -295,7 +307,7 @@ void gemm_dma_kernel(GemmParams p, int tiles_m, int tiles_n) {
     }
   }
 
-  store_acc_tile<MB, NB, kEpi>(p, acc, m0 + wm, n0 + wn, l16, q4, s_tab);
+  store_acc_tile<MB, NB, kEpi>(p, acc, plane_row + m0 + wm, n0 + wn, l16, q4, s_tab);
 }
 
 }  // namespace

@@ -156,8 +156,21 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
   const uint4 *copy_ptr = nullptr;     // source and destination vector of the piece after it
   uint32_t copy_next_v = 0;
 
+  // A launch split along K: the logical ids of one part are consecutive (so an XCD's tiles still share panels),
+  // each part runs its own range of k and stores its own fp32 plane.
   int tm, tn;
-  tile_of_block(tiles_m, tiles_n, &tm, &tn);
+  int pid = logical_block();
+  int K = p.K;
+  int64_t k0 = 0;    // first k of this workgroup's part
+  int plane_row = 0;  // its plane starts at this row of C (the planes lie one below the other: ldc = N)
+  if (p.k_parts > 1) {
+    const int tiles = tiles_m * tiles_n, part = pid / tiles;
+    pid -= part * tiles;
+    K = p.K / p.k_parts;
+    k0 = static_cast<int64_t>(part) * K;
+    plane_row = part * p.M;
+  }
+  tile_of_pid(pid, tiles_m, tiles_n, &tm, &tn);
   const int m0 = tm * BM, n0 = tn * BN;
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
@@ -169,8 +182,8 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
   const int nB = second ? n0 - p.n_split : n0;
   const uint16_t *srcA[OpA::kLoads], *srcB[OpB::kLoads];
   {
-    const uint16_t *a0 = (kAK ? p.A + static_cast<int64_t>(m0) * p.lda : p.A + m0) + OpA::lane_src(wave, lane, p.lda);
-    const uint16_t *b0 = (kBKc ? baseB + static_cast<int64_t>(nB) * ldb : baseB + nB) + OpB::lane_src(wave, lane, ldb);
+    const uint16_t *a0 = (kAK ? p.A + static_cast<int64_t>(m0) * p.lda + k0 : p.A + m0 + k0 * p.lda) + OpA::lane_src(wave, lane, p.lda);
+    const uint16_t *b0 = (kBKc ? baseB + static_cast<int64_t>(nB) * ldb + k0 : baseB + nB + k0 * ldb) + OpB::lane_src(wave, lane, ldb);
 #pragma unroll
     for (int i = 0; i < OpA::kLoads; ++i) srcA[i] = a0 + OpA::load_rows(i) * p.lda;
 #pragma unroll
@@ -178,7 +191,7 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
   }
   const int64_t stepA = OpA::block_stride(p.lda);
   int64_t stepB = OpB::block_stride(ldb);
-  const int nb = p.K / 64;
+  const int nb = K / 64;
   int first_seg = p.k_split ? p.k_split / 64 : nb;
 
   f32x4 acc[MB][NB];
@@ -306,7 +319,7 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
 
   asm volatile("s_nop 15");
   asm volatile("s_nop 15");
-  store_acc_tile<MB, NB, kEpi>(p, acc, m0 + wm, n0 + wn, l16, q4, s_tab);
+  store_acc_tile<MB, NB, kEpi>(p, acc, plane_row + m0 + wm, n0 + wn, l16, q4, s_tab);
 }
 
 }  // namespace

@@ -74,6 +74,7 @@ struct Resolved {
   size_t slot_bytes;         // one staging slot, rounded up to kSlotAlign
   size_t peak_staging;       // gathered-weight bytes live at the peak (unrounded)
   size_t acc_bytes;          // fp32 accumulator T x D (more than one accumulating launch: dX for column slices, Y for row slices)
+  size_t parts_bytes;        // fp32 planes of the widest forward launch when the product is split along K (0: it is not)
   // launch plan; every entry is a range [c0, c1) of sub-slice indices
   std::vector<Slice> fwd;    // forward GEMM launches: one sub-slice, or two staged ones in one launch
   std::vector<Slice> group;  // backward: sub-slices staged together
@@ -89,8 +90,12 @@ struct Replicas {
   int64_t ld;
 };
 
-// Rough duration of one gather launch in microseconds (read + write of the slice at about 3 TB/s).
-double gather_estimate_us(int64_t elems) { return 4.0 * static_cast<double>(elems) / 3.0e6 + 6.0; }
+// Rough duration of one gather launch in microseconds: read + write of the slice at 5.5 TB/s plus the launch
+// (measured alone between GEMMs: 32 MiB slices 17 us, 64 MiB 28 us, 128 MiB 44 us, 2 MiB 6 us).
+double gather_estimate_us(int64_t elems) { return 4.0 * static_cast<double>(elems) / 5.5e6 + 6.0; }
+// A gather that rides along inside a GEMM launch slows that launch by nearly what the gather takes alone (measured:
+// 64 MiB slices add 25 us to a 190 us launch, 28 us as a launch of their own); what it saves is the launch and its gap.
+constexpr double kCarriedShare = 0.9;
 
 void slice_bounds(int64_t len, int64_t k, int64_t j, int64_t *c0, int64_t *c1) {
   *c0 = (j * len) / k;
@@ -255,7 +260,7 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
   // mode would degenerate to SINGLE with nothing left for the next gather to overlap)
   bool pair_fwd = r->slots == 2 && n >= 2 && mode != OSDP_STAGING_HALF;
   if (pair_fwd) {
-    double t_single = 0.0, t_pair = 0.0;
+    double t_single = 0.0, t_pair = 0.0, t_carried = 0.0;
     const double acc_trip_us = 8.0 * static_cast<double>(T) * static_cast<double>(D) / 3.0e6;  // fp32 out and back in
     for (int64_t j = 0; j + 1 < n; j += 2) {
       pair_fwd = pair_fwd && can_pair(fwd_concat, j);
@@ -264,6 +269,8 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
       const double exposed = (!r->dp[j] && !r->dp[j + 1]) ? gather_estimate_us(D * (width(j) + width(j + 1)))
                              : (r->dp[j] ? 0.0 : gather_estimate_us(D * width(j))) +
                                (r->dp[j + 1] ? 0.0 : gather_estimate_us(D * width(j + 1)));
+      for (int64_t q = j; q < j + 2; ++q)
+        if (!r->dp[q]) t_carried += (q == 0 ? 1.0 : kCarriedShare) * gather_estimate_us(D * width(q));
       if (fwd_concat) {
         t_single += concat_us(j, j + 1) + concat_us(j + 1, j + 2);
         t_pair += concat_us(j, j + 2) + exposed;
@@ -272,13 +279,15 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
         t_pair += accum_us(j, j + 2) + exposed;
       }
     }
-    // With gathers that ride along inside the GEMM launches, one launch per slice exposes the first gather only.
-    // With gathers as launches of their own (measured on configs 2 to 5 with both choices forced) sharing a launch
-    // was never slower and up to 6 % faster than the estimate predicted (two streams cost events, and a gather kernel
-    // beside the GEMMs only takes turns with their tiles), so there it only loses when the estimate puts it clearly
-    // behind, as it does when the gathers dwarf the GEMMs (few tokens).
+    // One launch per slice takes the next slice's gather along, which costs the launch nearly the gather's own
+    // time (measured on config 4's operators, forward alone: 8192 -> 32768 at k = 8 in pairs 1691 us, singly with
+    // carried gathers 1777 us, singly on one slot 1704 us), so ties go to the pairs, which also copy in fewer, larger
+    // pieces.  With gathers as launches of their own on a second stream (measured on configs 2 to 5 with both choices
+    // forced) sharing a launch was never slower and up to 6 % faster than the estimate predicted (two streams cost
+    // events, and a gather kernel beside the GEMMs only takes turns with their tiles), so there it only loses when
+    // the estimate puts it clearly behind, as it does when the gathers dwarf the GEMMs (few tokens).
     if (debug_options().fused_gather.load(std::memory_order_relaxed) != 0)
-      pair_fwd = pair_fwd && t_pair < t_single + gather_estimate_us(D * width(0));  // unpaired: only the first gather is exposed
+      pair_fwd = pair_fwd && t_pair <= 1.03 * (t_single + t_carried);
     else
       pair_fwd = pair_fwd && t_pair < 1.10 * t_single;
     const int forced = debug_options().fwd_pair.load(std::memory_order_relaxed);  // testing: 0 never pairs, 1 pairs whenever the kernel can
@@ -347,10 +356,20 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
   }
   const size_t accumulating = is_bwd ? (bwd_concat ? 0 : r->pass.size()) : (fwd_concat ? 0 : r->fwd.size());
   r->acc_bytes = accumulating > 1 ? static_cast<size_t>(T) * static_cast<size_t>(D) * 4 : 0;
+  // Forward products of few tokens with a long reduction run as parts of the reduction side by side, each into
+  // an fp32 plane of the launch's shape (with DP slices the launches may be merged at call time, up to all columns).
+  r->parts_bytes = 0;
+  if (!is_bwd && fwd_concat) {
+    int64_t widest = 0;
+    for (const Slice &l : r->fwd) widest = std::max(widest, span(l.c0, l.c1));
+    if (r->any_dp) widest = O;
+    r->parts_bytes = gemm_forward_parts_bytes(T, widest, D);
+  }
   return OSDP_OK;
 }
 
-size_t workspace_total(const Resolved &r) { return r.slot_bytes * r.slots + r.acc_bytes; }
+// Staging slots, the fp32 partial sum, the planes of forward launches split along K.
+size_t workspace_total(const Resolved &r) { return r.slot_bytes * r.slots + r.acc_bytes + r.parts_bytes; }
 
 osdp_status fill_table(const void *const *ptrs, int32_t N, const char *name, ShardTable *t) {
   if (!ptrs) return fail(OSDP_ERR_INVALID_ARG, "%s is NULL", name);
@@ -709,7 +728,7 @@ const DebugSwitch kSwitches[] = {
     {"gemm_generic", &DebugOptions::gemm_generic, 0, 1}, {"tile", &DebugOptions::tile, -1, 3},
     {"deep", &DebugOptions::deep, -1, 1},                {"split_launch", &DebugOptions::split_launch, -1, 1},
     {"fwd_pair", &DebugOptions::fwd_pair, -1, 1},        {"poison_staging", &DebugOptions::poison_staging, 0, 1},
-    {"four_wave", &DebugOptions::four_wave, -1, 1},      {"fused_gather", &DebugOptions::fused_gather, -1, 1},
+    {"split_k", &DebugOptions::split_k, -1, 1},          {"four_wave", &DebugOptions::four_wave, -1, 1},      {"fused_gather", &DebugOptions::fused_gather, -1, 1},
 };
 }  // namespace
 
@@ -830,6 +849,8 @@ static osdp_status forward(const osdp_shape *shape, const osdp_plan *plan, int32
 
   char *ws = static_cast<char *>(workspace);
   float *acc = reinterpret_cast<float *>(ws + r.slot_bytes * r.slots);  // row slices: Y's fp32 partial sum
+  void *planes = r.parts_bytes ? ws + r.slot_bytes * r.slots + r.acc_bytes : nullptr;  // planes of launches split along K
+  const size_t planes_bytes = r.parts_bytes;
   const int n = static_cast<int>(r.sub.size());
   // Debug mode: a slot holds NaN patterns whenever no gathered slice is live in it, so that a GEMM that ran ahead
   // of its gather, or a gather that overwrote a slice still being read, shows up as NaN (or wrong) outputs.
@@ -854,6 +875,7 @@ static osdp_status forward(const osdp_shape *shape, const osdp_plan *plan, int32
         next = gather_request(r, tab, r.sub[j + 1], ws + static_cast<size_t>((j + 1) % 2) * r.slot_bytes);
         g.carry = &next;
       }
+      g.parts = planes; g.parts_bytes = planes_bytes;
       OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_FWD, g, sc));
       if (poison && !r.dp[j]) OSDP_HIP(launch_fill16(slot, r.slot_bytes, kPoison, sc));
     }
@@ -880,11 +902,12 @@ static osdp_status forward(const osdp_shape *shape, const osdp_plan *plan, int32
     }
     if (joint) OSDP_HIP(do_gather(r, tab, joint_range(r, j0), ws, sg));  // one copy for both, across the two slots
     if (overlap && gathered) OSDP_HIP(edge(sp, sc));
-    const GemmProblem g =
+    GemmProblem g =
         joint ? weight_gemm(r, /*is_fwd=*/true, j0, j1, joint_view(r, j0, ws), WeightView{nullptr, 0}, X, ldx, Y, ldy, acc,
                             li, r.fwd.size())
               : weight_gemm(r, /*is_fwd=*/true, j0, j1, weights_of(r, rep, j0, slot_of[0]),
                             weights_of(r, rep, j1 - 1, slot_of[1]), X, ldx, Y, ldy, acc, li, r.fwd.size());
+    g.parts = planes; g.parts_bytes = planes_bytes;
     OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_FWD, g, sc));
     if (poison && gathered) {  // the slices this launch read are dead: poison their slots before they are handed back
       if (joint) OSDP_HIP(launch_fill16(ws, r.slot_bytes * 2, kPoison, sc));
@@ -1044,7 +1067,7 @@ static osdp_status backward(const osdp_shape *shape, const osdp_plan *plan, int3
     // the dX launches of the group (column slices: the fp32 partial sum is carried in the workspace between them)
     for (; next_pass < r.pass.size() && r.pass[next_pass].c1 <= g1; ++next_pass) {
       const int j0 = static_cast<int>(r.pass[next_pass].c0), j1 = static_cast<int>(r.pass[next_pass].c1);
-      const GemmProblem gx =
+      GemmProblem gx =
           joint ? weight_gemm(r, /*is_fwd=*/false, j0, j1, joint_view(r, j0, ws), WeightView{nullptr, 0}, dY, lddy, dX, lddx,
                               acc, next_pass, r.pass.size())
                 : weight_gemm(r, /*is_fwd=*/false, j0, j1,

@@ -82,7 +82,14 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
     __syncthreads();  // with K = 0 the loop below, and its barriers, do not run
   }
   const int tiles_m = (p.M + GBM - 1) / GBM;
-  const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
+  // a launch split along K: part s of the grid takes its range of k and stores plane s (the planes lie one below the other)
+  const int tiles = tiles_m * ((p.N + GBN - 1) / GBN);
+  const int part = p.k_parts > 1 ? blockIdx.x / tiles : 0;
+  const int bid = blockIdx.x - part * tiles;
+  const int k_len = p.k_parts > 1 ? p.K / p.k_parts : p.K;
+  const int k_begin = part * k_len, k_end = k_begin + k_len;
+  const int plane_row = part * p.M;
+  const int tm = bid % tiles_m, tn = bid / tiles_m;
   const int m0 = tm * GBM, n0 = tn * GBN;
   const int lane = tid & 63, wave = tid >> 6;
   const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
@@ -108,10 +115,10 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
       }
     }
 
-  for (int k0 = 0; k0 < p.K; k0 += GBK) {
+  for (int k0 = k_begin; k0 < k_end; k0 += GBK) {
     uint4 va[2], vb[2];
-    generic_load<kAK>(p.A, p.lda, p.M, m0, k0, p.K, va);
-    generic_load<kBK>(p.B, p.ldb, p.N, n0, k0, p.K, vb);
+    generic_load<kAK>(p.A, p.lda, p.M, m0, k0, k_end, va);
+    generic_load<kBK>(p.B, p.ldb, p.N, n0, k0, k_end, vb);
     __syncthreads();  // the previous block's LDS reads are done
     generic_store_lds<kAK>(As, va);
     generic_store_lds<kBK>(Bs, vb);
@@ -134,14 +141,15 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(GemmParams p) {
     for (int bn = 0; bn < 4; ++bn) {
       const int m = m0 + wm + bm * 16 + l16, n = n0 + wn + bn * 16 + 4 * q;
       if (m >= p.M || n >= p.N) continue;  // N is a multiple of 8 and n of 4: the 4 columns are in or out together
-      store_acc4<kEpi>(p, acc[bm][bn], m, n, s_tab);
+      store_acc4<kEpi>(p, acc[bm][bn], plane_row + m, n, s_tab);
     }
 }
 
 template <bool kAK, bool kBK, int kEpi, bool kAccIn>
 hipError_t launch_generic(const GemmParams &p, hipStream_t stream) {
   const int tiles = ((p.M + GBM - 1) / GBM) * ((p.N + GBN - 1) / GBN);
-  hipLaunchKernelGGL((gemm_generic_kernel<kAK, kBK, kEpi, kAccIn>), dim3(tiles), dim3(256), 0, stream, p);
+  const int parts = p.k_parts > 1 ? p.k_parts : 1;
+  hipLaunchKernelGGL((gemm_generic_kernel<kAK, kBK, kEpi, kAccIn>), dim3(tiles * parts), dim3(256), 0, stream, p);
   return hipGetLastError();
 }
 
@@ -173,7 +181,8 @@ hipError_t launch_dma(const GemmParams &p, hipStream_t stream) {
   hipError_t e = allow_lds(kernel, lds, configured);
   if (e != hipSuccess) return e;
   const int tiles_m = p.M / BM, tiles_n = p.N / BN;
-  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n), dim3(kWaves * 64), lds, stream, p, tiles_m, tiles_n);
+  const int parts = p.k_parts > 1 ? p.k_parts : 1;
+  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n * parts), dim3(kWaves * 64), lds, stream, p, tiles_m, tiles_n);
   return hipGetLastError();
 }
 
@@ -187,8 +196,36 @@ hipError_t launch_w4(const GemmParams &p, hipStream_t stream) {
   hipError_t e = allow_lds(kernel, lds, configured);
   if (e != hipSuccess) return e;
   const int tiles_m = p.M / 256, tiles_n = p.N / 256;
-  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n), dim3(256), lds, stream, p, tiles_m, tiles_n);
+  const int parts = p.k_parts > 1 ? p.k_parts : 1;
+  hipLaunchKernelGGL(kernel, dim3(tiles_m * tiles_n * parts), dim3(256), lds, stream, p, tiles_m, tiles_n);
   return hipGetLastError();
+}
+
+// Adds up the fp32 planes of a launch that was split along K, plane 0 first, and stores the sum through the
+// launch's own epilogue.  One thread per 4 consecutive columns.
+template <int kEpi>
+__global__ __launch_bounds__(256)
+void combine_parts_kernel(GemmParams p, const float *parts, int n_parts) {
+  uint16_t *const *s_tab = nullptr;
+  if constexpr (kEpi == static_cast<int>(Epilogue::kBf16ShardMajor)) {
+    __shared__ uint16_t *tab[OSDP_MAX_SHARDS];
+    if (threadIdx.x < OSDP_MAX_SHARDS) tab[threadIdx.x] = static_cast<uint16_t *>(p.shards.p[threadIdx.x]);
+    __syncthreads();
+    s_tab = tab;
+  }
+  const int64_t plane = static_cast<int64_t>(p.M) * p.N;
+  const int64_t v = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x;
+  if (v * 4 >= plane) return;
+  const int per_row = p.N / 4;
+  const int m = static_cast<int>(v / per_row), n = static_cast<int>(v - static_cast<int64_t>(m) * per_row) * 4;
+  const float4 *src = reinterpret_cast<const float4 *>(parts) + v;
+  float4 a = src[0];
+  for (int s = 1; s < n_parts; ++s) {
+    const float4 b = src[static_cast<int64_t>(s) * (plane / 4)];
+    a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w;
+  }
+  const f32x4 c = {a.x, a.y, a.z, a.w};
+  store_acc4<kEpi>(p, c, m, n, s_tab);
 }
 
 constexpr int kCUs = 256;
@@ -200,9 +237,9 @@ constexpr int kW4MinKdW = 8192;
 // penalty for the lower MFMA efficiency of smaller tiles.  Tiles that run two to a CU were measured in pairs; a
 // CU's odd last tile runs alone and slower, which is priced as one and a half tiles.  0 when the tile does not
 // divide the problem.
-double tile_cost(int M, int N, int BM, int BN, double penalty) {
+double tile_cost(int M, int N, int BM, int BN, double penalty, int parts = 1) {
   if (M % BM || N % BN) return 0.0;
-  const long tiles = static_cast<long>(M / BM) * (N / BN);
+  const long tiles = static_cast<long>(M / BM) * (N / BN) * parts;
   const long per_cu = (tiles + kCUs - 1) / kCUs;
   const bool two_per_cu = BM * BN < 256 * 256;
   const double units = (two_per_cu && per_cu % 2) ? static_cast<double>(per_cu) + 0.5 : static_cast<double>(per_cu);
@@ -242,12 +279,14 @@ constexpr TileShape kTiles[4] = {{256, 256, {1.0, 1.0, 1.0}},
 constexpr int layout_kind(bool a_kcontig, bool b_kcontig) { return (a_kcontig && !b_kcontig) ? 0 : (!a_kcontig ? 1 : 2); }
 
 // Cheapest tile for M x N; a column split must fall on a tile boundary.  -1: none divides the problem.
-int best_tile(int M, int N, int n_split, int kind, double *cost) {
+// parts > 1: the launch has that many workgroups per tile (parts of the reduction); the cost is in tile passes over
+// the whole reduction all the same, so the caller divides it by parts.
+int best_tile(int M, int N, int n_split, int kind, double *cost, int parts = 1) {
   int best = -1;
   double best_cost = 0.0;
   for (int i = 0; i < 4; ++i) {
     if (n_split % kTiles[i].bn) continue;
-    const double c = tile_cost(M, N, kTiles[i].bm, kTiles[i].bn, kTiles[i].penalty[kind]);
+    const double c = tile_cost(M, N, kTiles[i].bm, kTiles[i].bn, kTiles[i].penalty[kind], parts);
     if (c > 0.0 && (best < 0 || c < best_cost)) {
       best = i;
       best_cost = c;
@@ -257,12 +296,40 @@ int best_tile(int M, int N, int n_split, int kind, double *cost) {
   return best;
 }
 
+// ---- forward launches split along K --------------------------------------------------------------------------
+// A slice of a wide operator applied to few tokens (4096 x 1024 x 32768) has few output tiles and a long reduction:
+// most CUs get no 256 x 256 tile, and the 128 x 128 tiles that would occupy them run at 70 % of the large tile's
+// rate.  The forward product of such an operator is therefore defined as the sum of kPartK-long parts of the
+// reduction: the parts run side by side as one launch (grid = parts x tiles), each into its own fp32 plane, and a
+// second kernel adds the planes, plane 0 first, and rounds to bf16.  The number of parts depends on the token count
+// and the reduction length alone - never on the slice width, the tile shape or the kernel - so Y keeps the same bits
+// for every k, as the unsplit operator (k = 1) runs the same parts.
+// Measured on 4096 tokens, 32768 -> 8192, whole steps with parts of 16384 / 8192 / 4096 against none, in TFLOP/s:
+// k = 8 two slots 1130 / 1122 / 1068 against 1082; k = 16 978 / 1017 / 981 against 987; k = 4 1181 / 1170 / 1107
+// against 1187; k = 8 one slot 975 / 1020 / 979 against 986; k = 8 half slices 926 / 920 / 884 against 826.
+constexpr int kPartK = 8192;          // length of a part
+constexpr int kPartMaxTokens = 4096;  // more tokens than this fill the CUs with any slice width that is worth staging
+constexpr int kMaxParts = 8;
+
+int forward_k_parts(int64_t M, int64_t K) {
+  if (debug_options().split_k.load(std::memory_order_relaxed) == 0) return 1;  // testing: one part always
+  if (M <= 0 || M > kPartMaxTokens || K < 2 * kPartK) return 1;
+  const int parts = static_cast<int>(std::min<int64_t>(K / kPartK, kMaxParts));
+  return K % (static_cast<int64_t>(parts) * 64) ? 1 : parts;
+}
+
+// Estimated duration of the combining kernel: the planes read, the result written.
+double combine_estimate_us(int64_t M, int64_t N, int parts) {
+  return (4.0 * parts + 2.0) * static_cast<double>(M) * static_cast<double>(N) / 3.0e6 + 8.0;
+}
+
 // *carry: the launch has a gather to carry (GemmParams::job is filled in); cleared by the launch that takes it.
 template <bool kAK, bool kBK, int kEpi, bool kAccIn>
 hipError_t launch_best(const GemmParams &p, hipStream_t stream, bool *carry) {
   constexpr int kind = layout_kind(kAK, kBK);
-  if (fast_path(p.M, p.N, p.K, p.k_split, p.n_split)) {
-    int best = best_tile(p.M, p.N, p.n_split, kind, nullptr);
+  const int parts = p.k_parts > 1 ? p.k_parts : 1;  // parts of the reduction run as further tiles of the same launch
+  if (fast_path(p.M, p.N, p.K / parts, p.k_split, p.n_split)) {
+    int best = best_tile(p.M, p.N, p.n_split, kind, nullptr, parts);
     const int forced = debug_options().tile.load(std::memory_order_relaxed);  // testing: tile 0..3 when it divides the problem
     const bool force = forced >= 0 && forced <= 3;
     if (force) {
@@ -280,14 +347,14 @@ hipError_t launch_best(const GemmParams &p, hipStream_t stream, bool *carry) {
     }
     // A launch of at most one tile per CU cannot hide the latency of its loads behind a second workgroup: it gets
     // the whole LDS for a deeper pipeline instead (twice the bytes in flight).
-    const bool deep = best > 0 && static_cast<long>(p.M / kTiles[best].bm) * (p.N / kTiles[best].bn) <= kCUs &&
+    const bool deep = best > 0 && static_cast<long>(p.M / kTiles[best].bm) * (p.N / kTiles[best].bn) * parts <= kCUs &&
                       debug_options().deep.load(std::memory_order_relaxed) != 0;  // testing: 0 keeps the shallow pipelines
     const int fw = debug_options().four_wave.load(std::memory_order_relaxed);  // testing: 0 never, 1 whenever it can
     switch (best) {
       case 0:
         // (dW, both operands MN-contiguous: twice the fragment-read instructions and a serial epilogue per wave;
         // measured through the library, the four-wave kernel is 4-9 % ahead from K = 8192 and 3 % behind at K = 4096)
-        if (p.K >= kW4MinK && fw != 0 && (fw == 1 || p.K >= (kind == 1 ? kW4MinKdW : kW4MinK))) {
+        if (p.K / parts >= kW4MinK && fw != 0 && (fw == 1 || p.K >= (kind == 1 ? kW4MinKdW : kW4MinK))) {
           if constexpr (!(kAK && kBK)) {  // dX launches read every staged slice there is: they never carry a gather
             if (*carry) {
               *carry = false;
@@ -379,7 +446,26 @@ double plan_launches(int M, int N, int K, int kind, int *axis, int *cut) {
 }
 
 template <bool kAK, bool kBK, int kEpi, bool kAccIn>
-hipError_t launch_planned(const GemmParams &p, hipStream_t stream, bool *carry) {
+hipError_t launch_planned(const GemmParams &p, hipStream_t stream, bool *carry, float *planes, size_t planes_bytes) {
+  if constexpr (kAK && !kBK && !kAccIn && kEpi == static_cast<int>(Epilogue::kBf16RowMajor)) {
+    // (a caller that passes no planes asks for the one-part product: the forward of row slices, whose launches
+    // continue one accumulator chain instead)
+    const int parts = (p.k_split || !planes) ? 1 : forward_k_parts(p.M, p.K);
+    if (parts > 1) {
+      if (planes_bytes < static_cast<size_t>(parts) * p.M * p.N * 4) return hipErrorInvalidValue;
+      constexpr int kF32 = static_cast<int>(Epilogue::kF32Workspace);
+      GemmParams s = p;
+      s.k_parts = parts;
+      s.C = planes;
+      s.ldc = p.N;
+      hipError_t e = launch_best<kAK, kBK, kF32, false>(s, stream, carry);
+      if (e != hipSuccess) return e;
+      const int64_t vecs = static_cast<int64_t>(p.M) * p.N / 4;
+      hipLaunchKernelGGL((combine_parts_kernel<kEpi>), dim3(static_cast<unsigned>((vecs + 255) / 256)), dim3(256), 0, stream, p,
+                         static_cast<const float *>(planes), parts);
+      return hipGetLastError();
+    }
+  }
   if (!p.k_split && !p.n_split && fast_path(p.M, p.N, p.K, 0, 0)) {
     int axis, cut;
     plan_launches(p.M, p.N, p.K, layout_kind(kAK, kBK), &axis, &cut);
@@ -416,11 +502,22 @@ double gemm_estimate_us(int64_t M, int64_t N, int64_t K) {
   // forward launch grouping of config 3 slightly worse)
   double cost = 0.0;
   if (fast_path(static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), 0, 0) &&
-      best_tile(static_cast<int>(M), static_cast<int>(N), 0, 0, &cost) >= 0)
+      best_tile(static_cast<int>(M), static_cast<int>(N), 0, 0, &cost) >= 0) {
+    const int parts = forward_k_parts(M, K);  // (the estimate serves forward launches; other products of such shapes are rare)
+    if (parts > 1) {
+      best_tile(static_cast<int>(M), static_cast<int>(N), 0, 0, &cost, parts);
+      return cost / parts * 2.0 * static_cast<double>(K) / 5.0e6 + combine_estimate_us(M, N, parts) + 6.0;
+    }
     return cost * 2.0 * static_cast<double>(K) / 5.0e6 + 6.0;
+  }
   const double tiles = static_cast<double>((M + GBM - 1) / GBM) * static_cast<double>((N + GBN - 1) / GBN);
   const double rounds = static_cast<double>(static_cast<long>((tiles + kCUs - 1) / kCUs));
   return rounds * GBM * GBN * 5.0 * 2.0 * static_cast<double>(K) / 5.0e6 + 6.0;  // the checked kernel is about 5x slower per tile
+}
+
+size_t gemm_forward_parts_bytes(int64_t M, int64_t N, int64_t K) {
+  const int parts = forward_k_parts(M, K);
+  return parts > 1 && N > 0 ? static_cast<size_t>(parts) * static_cast<size_t>(M) * static_cast<size_t>(N) * 4 : 0;
 }
 
 hipError_t check_device() {
@@ -462,21 +559,23 @@ hipError_t dispatch_gemm(const GemmProblem &q, hipStream_t stream, bool *carry) 
   }
   if ((p.k_split || p.n_split) && !q.a_kcontig) return hipErrorInvalidValue;  // dW never takes a second segment
   if (p.k_split && p.n_split) return hipErrorInvalidValue;
+  float *planes = static_cast<float *>(q.parts);
+  const size_t planes_bytes = q.parts_bytes;
   constexpr int kRow = static_cast<int>(Epilogue::kBf16RowMajor), kShard = static_cast<int>(Epilogue::kBf16ShardMajor),
                 kF32 = static_cast<int>(Epilogue::kF32Workspace);
   const bool acc = q.acc_in != nullptr;
   // The three GEMMs of the split linear layer, with the four accumulate forms for forward and dX, are the only combinations built.
   if (q.a_kcontig && !q.b_kcontig) {                                               // forward (accumulating when the reduction dimension is split)
-    if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_planned<true, false, kRow, true>(p, stream, carry) : launch_planned<true, false, kRow, false>(p, stream, carry);
-    if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_planned<true, false, kF32, true>(p, stream, carry) : launch_planned<true, false, kF32, false>(p, stream, carry);
+    if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_planned<true, false, kRow, true>(p, stream, carry, planes, planes_bytes) : launch_planned<true, false, kRow, false>(p, stream, carry, planes, planes_bytes);
+    if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_planned<true, false, kF32, true>(p, stream, carry, planes, planes_bytes) : launch_planned<true, false, kF32, false>(p, stream, carry, planes, planes_bytes);
   }
   if (!q.a_kcontig && !q.b_kcontig && !acc) {                                      // dW: into the shards, or (DP slice) a plain array
-    if (q.epilogue == Epilogue::kBf16ShardMajor) return launch_planned<false, false, kShard, false>(p, stream, carry);
-    if (q.epilogue == Epilogue::kBf16RowMajor) return launch_planned<false, false, kRow, false>(p, stream, carry);
+    if (q.epilogue == Epilogue::kBf16ShardMajor) return launch_planned<false, false, kShard, false>(p, stream, carry, planes, planes_bytes);
+    if (q.epilogue == Epilogue::kBf16RowMajor) return launch_planned<false, false, kRow, false>(p, stream, carry, planes, planes_bytes);
   }
   if (q.a_kcontig && q.b_kcontig) {                                                // dX
-    if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_planned<true, true, kRow, true>(p, stream, carry) : launch_planned<true, true, kRow, false>(p, stream, carry);
-    if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_planned<true, true, kF32, true>(p, stream, carry) : launch_planned<true, true, kF32, false>(p, stream, carry);
+    if (q.epilogue == Epilogue::kBf16RowMajor) return acc ? launch_planned<true, true, kRow, true>(p, stream, carry, planes, planes_bytes) : launch_planned<true, true, kRow, false>(p, stream, carry, planes, planes_bytes);
+    if (q.epilogue == Epilogue::kF32Workspace) return acc ? launch_planned<true, true, kF32, true>(p, stream, carry, planes, planes_bytes) : launch_planned<true, true, kF32, false>(p, stream, carry, planes, planes_bytes);
   }
   return hipErrorInvalidValue;
 }

@@ -84,6 +84,10 @@ struct GemmProblem {
   // leaves *carried false and the gather to the caller.  carried must be given when carry is.
   const GatherRequest *carry;
   bool *carried;
+  // Room for the fp32 planes of a forward launch split along K (gemm_forward_parts_bytes says how much the
+  // product needs; with less the launch fails).  nullptr: the product is computed in one part whatever its shape.
+  void *parts;
+  size_t parts_bytes;
 };
 
 // Enqueue on `stream`.  Returns hipSuccess or the launch error.
@@ -99,6 +103,11 @@ bool gemm_takes_two_column_segments(int64_t M, int64_t n_first, int64_t n_second
 // Rough duration in microseconds of one M x N x K GEMM launch (tile rounds over the CUs at the
 // throughput measured for each tile shape); only used to choose between launch groupings.
 double gemm_estimate_us(int64_t M, int64_t N, int64_t K);
+
+// Bytes of fp32 planes that launch_gemm needs in GemmProblem::parts for a forward product (A K-contiguous, B
+// N-contiguous, bf16 row-major result, no accumulator) of M x N x K; 0: that product is not split along K.  The
+// number of parts is a function of M and K alone.
+size_t gemm_forward_parts_bytes(int64_t M, int64_t N, int64_t K);
 
 // Ws[r, c] = W[r0 + r, c0 + c] for r < rows, c < w; Ws dense row-major [rows x w].
 hipError_t launch_gather(const ShardTable &shards, const ShardLayout &layout, int64_t r0, int64_t rows, int64_t c0,
@@ -118,6 +127,7 @@ struct DebugOptions {
   std::atomic<int32_t> fwd_pair{-1};       // 0: the forward never pairs staged slices; 1: whenever the kernel can
   std::atomic<int32_t> fused_gather{-1};   // 0: gathers always run as launches of their own (second stream where given)
   std::atomic<int32_t> four_wave{-1};      // 0: 256 x 256 tiles run on the eight-wave kernel; 1: on the four-wave kernel wherever it can
+  std::atomic<int32_t> split_k{-1};        // 0: forward products are never split along K (changes the bits of those that are)
   std::atomic<int32_t> poison_staging{0};  // 1: staging slots hold NaN patterns whenever no gathered slice is live in them
 };
 DebugOptions &debug_options();

@@ -16,7 +16,7 @@ def H():
     return gpu_harness
 
 
-DEBUG_DEFAULTS = {"four_wave": -1, "fused_gather": -1, "gemm_generic": 0, "tile": -1, "deep": -1, "split_launch": -1, "fwd_pair": -1, "poison_staging": 0}
+DEBUG_DEFAULTS = {"split_k": -1, "four_wave": -1, "fused_gather": -1, "gemm_generic": 0, "tile": -1, "deep": -1, "split_launch": -1, "fwd_pair": -1, "poison_staging": 0}
 
 
 @pytest.fixture
@@ -1076,3 +1076,60 @@ def test_gathers_carried_by_gemm_launches_match_the_gather_kernel(H, oracle, T, 
                     got = op.results()
                     for name in ("Y", "dX", "dW"):
                         assert np.array_equal(got[name], base[name]), f"{name} differs from the unsplit result"
+
+
+# ------------------------------------------------ forward products that run as parts of the reduction
+@pytest.mark.parametrize("T,I,O,N", [(512, 32768, 1024, 8),    # four parts of 8192
+                                     (300, 49152, 520, 4)])    # six parts; ragged T and slices: the checked kernel
+def test_forward_parts_of_a_long_reduction_keep_the_bits_for_every_k_and_kernel(H, oracle, T, I, O, N, debug):
+    """Few tokens and a long reduction: the forward product is the sum of 8192-long parts, each computed into an fp32
+    plane of its own and added in order.  The number of parts depends on T and I alone, so Y keeps the unsplit
+    operator's bits for every k, staging mode, pairing, tile shape and kernel; against the oracle it stays within the
+    tolerance, as does the one-part product (switch off), whose bits differ."""
+    import paper_2209_13258_amd as osdp
+    d = wl.small_case(151, T, I, O, N)
+    want = oracle.linear(d["X"], d["W_shards"], O, want=("Y",))
+    parts = I // 8192
+    tot_on = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, 1, False)[0]
+    debug("split_k", 0)
+    tot_off = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, 1, False)[0]
+    one = H.Operator(d["X"], None, d["W_shards"], O)
+    one.fwd(1)
+    torch.cuda.synchronize()
+    one_part = H.to_bits(one.Y)
+    H.assert_close("Y (one part)", one_part, want["Y"])
+    debug("split_k", -1)
+    assert tot_on - tot_off == parts * T * O * 4   # the planes of the unsplit operator's one launch
+    base_op = H.Operator(d["X"], None, d["W_shards"], O)
+    base_op.fwd(1)
+    torch.cuda.synchronize()
+    base = H.to_bits(base_op.Y)
+    H.assert_close("Y", base, want["Y"])
+    assert not np.array_equal(base, one_part)   # the parts are really summed separately
+    sc, sp = H.streams()
+    fast = T % 128 == 0 and O % 128 == 0
+    settings = [dict()] + ([dict(tile=t, four_wave=f) for t, f in ((0, 0), (0, 1), (1, -1), (2, -1), (3, -1))] if fast else []) \
+        + [dict(gemm_generic=1)]
+    for setting in settings:
+        for name, value in setting.items():
+            debug(name, value)
+        for k in (1, 2, 4, 8):
+            if O % k or (O // k) % 8:
+                continue
+            for mode in (osdp.OSDP_STAGING_SINGLE, osdp.OSDP_STAGING_DOUBLE, osdp.OSDP_STAGING_HALF):
+                if mode == osdp.OSDP_STAGING_HALF and (O // k) % 16:
+                    continue
+                for pair in (0, 1):
+                    if mode != osdp.OSDP_STAGING_DOUBLE and pair:
+                        continue
+                    debug("fwd_pair", pair)
+                    _announce("forward parts", T, I, O, N, setting, "k", k, "mode", mode, "pair", pair)
+                    plan = osdp.Plan([k], staging=mode)
+                    op = H.Operator(d["X"], None, d["W_shards"], O)
+                    torch.cuda.synchronize()
+                    with torch.cuda.stream(sc):
+                        op.fwd(k, plan=plan, streams=(sc, sp))
+                    sc.synchronize()
+                    assert np.array_equal(H.to_bits(op.Y), base), f"Y differs from k=1 ({setting}, k={k}, mode={mode}, pair={pair})"
+        for name in setting:
+            debug(name, DEBUG_DEFAULTS[name])
