@@ -643,10 +643,12 @@ def test_per_slice_modes_match_oracle(H, oracle, T, I, O, N, k, mask, rows):
 
 
 @pytest.mark.parametrize("rows", [False, True])
-def test_per_slice_modes_are_bit_identical_to_all_zdp(H, oracle, rows):
+@pytest.mark.parametrize("T,I,O,N,k", [(256, 512, 1024, 4, 4),
+                                       (256, 16384, 1024, 4, 4)])  # column slices: the forward sums two parts of the reduction,
+                                                                   # also in launches that read a DP and a ZDP slice
+def test_per_slice_modes_are_bit_identical_to_all_zdp(H, oracle, rows, T, I, O, N, k):
     """With the replicas holding the same values as the shards, every mask gives the bits of the all-ZDP plan."""
     import paper_2209_13258_amd as osdp
-    T, I, O, N, k = 256, 512, 1024, 4, 4
     if rows:
         I, O = O, I
     dim = osdp.OSDP_SPLIT_IN_FEATURES if rows else osdp.OSDP_SPLIT_OUT_FEATURES
