@@ -449,7 +449,10 @@ def main():
         # carried by the GEMM launches), then the same k with every operator cut along its longer dimension, and
         # with every gather a launch of its own on the copy stream (the two-stream pipeline)
         sweep = {}
-        for k in (w.k_sweep or ()):
+        ks = tuple(w.k_sweep or ())
+        if ks and 1 not in ks:
+            ks = (1,) + ks   # the unsplit operator (the whole weight staged): what every k is set against
+        for k in ks:
             wk = wl.workload(a.config, k)
             fk = wl.flops(wk)
             row = {}
@@ -479,6 +482,11 @@ def main():
                 osdp.osdp_debug_option("fused_gather", -1 if a.gathers == "carried" else 0)
                 row["double_gathers_launched_two_streams"] = {key: m2[key] for key in ("tflops", "median_ms_per_step", "gathers", "idle_us_per_step")}
             sweep[str(k)] = row
+        if "1" in sweep:   # time(k) / time(unsplit): what splitting costs, overlap and all
+            t1 = sweep["1"]["single"]["median_ms_per_step"]
+            for row in sweep.values():
+                for entry in row.values():
+                    entry["time_vs_unsplit"] = round(entry["median_ms_per_step"] / t1, 4)
         out["k_sweep"] = sweep
         del st
         torch.cuda.empty_cache()
