@@ -240,7 +240,7 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
   auto width = [&](int64_t j) { return r->sub[j].c1 - r->sub[j].c0; };
   auto span = [&](int64_t a, int64_t b) { return r->sub[b - 1].c1 - r->sub[a].c0; };
   // one launch over sub-slices [a, b): concatenating (T x span x D) or accumulating (T x D x span)
-  auto concat_us = [&](int64_t a, int64_t b) { return gemm_estimate_us(T, span(a, b), D); };
+  auto concat_us = [&](int64_t a, int64_t b) { return gemm_estimate_us(T, span(a, b), D, /*forward_parts=*/!rows); };
   auto accum_us = [&](int64_t a, int64_t b) { return gemm_estimate_us(T, D, span(a, b)); };
   // Two neighbouring gathered sub-slices can always share a launch: they are gathered by one copy into the two
   // slots taken as one buffer and read as one slice.  When one of them is a DP slice (read in place) the launch

@@ -496,14 +496,14 @@ bool gemm_takes_two_column_segments(int64_t M, int64_t n_first, int64_t n_second
          best_tile(static_cast<int>(M), static_cast<int>(n_first + n_second), static_cast<int>(n_first), 0, nullptr) >= 0;
 }
 
-double gemm_estimate_us(int64_t M, int64_t N, int64_t K) {
+double gemm_estimate_us(int64_t M, int64_t N, int64_t K, bool forward_parts) {
   // one CU sustains about 5e6 flop per microsecond (1.3 PFLOP/s over 256 CUs) on 256 x 256 tiles
   // (one launch on its best tile: pricing the whole-rounds + remainder pair here instead was measured and made the
   // forward launch grouping of config 3 slightly worse)
   double cost = 0.0;
   if (fast_path(static_cast<int>(M), static_cast<int>(N), static_cast<int>(K), 0, 0) &&
       best_tile(static_cast<int>(M), static_cast<int>(N), 0, 0, &cost) >= 0) {
-    const int parts = forward_k_parts(M, K);  // (the estimate serves forward launches; other products of such shapes are rare)
+    const int parts = forward_parts ? forward_k_parts(M, K) : 1;
     if (parts > 1) {
       best_tile(static_cast<int>(M), static_cast<int>(N), 0, 0, &cost, parts);
       return cost / parts * 2.0 * static_cast<double>(K) / 5.0e6 + combine_estimate_us(M, N, parts) + 6.0;

@@ -102,7 +102,9 @@ bool gemm_takes_two_column_segments(int64_t M, int64_t n_first, int64_t n_second
 
 // Rough duration in microseconds of one M x N x K GEMM launch (tile rounds over the CUs at the
 // throughput measured for each tile shape); only used to choose between launch groupings.
-double gemm_estimate_us(int64_t M, int64_t N, int64_t K);
+// forward_parts: the product is a forward launch over column slices, which runs in parts of the reduction when few
+// tokens meet a long reduction.
+double gemm_estimate_us(int64_t M, int64_t N, int64_t K, bool forward_parts = false);
 
 // Bytes of fp32 planes that launch_gemm needs in GemmProblem::parts for a forward product (A K-contiguous, B
 // N-contiguous, bf16 row-major result, no accumulator) of M x N x K; 0: that product is not split along K.  The
