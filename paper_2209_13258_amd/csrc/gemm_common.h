@@ -19,8 +19,8 @@ __device__ __forceinline__ f32x4 mma_16x16x32(bf16x8 a_rows, bf16x8 b_cols, f32x
 }
 
 // A slice gather that rides along with a GEMM launch (four-wave kernel only): the copy Ws[r, c] = W[r0 + r, c0 + c]
-// of osdp_gather.hip, cut into one piece of 256 vectors per workgroup and K block and issued in the shadow of the
-// MFMAs.  dst is the dense destination, total_vecs its size in 16-byte vectors (below 2^32).
+// of osdp_gather.hip, cut into one piece of 256 vectors per workgroup and K block and issued between the
+// MFMAs (it saves the launch, not the memory time: the kernel is bound by the same memory pipe).  dst is the dense destination, total_vecs its size in 16-byte vectors (below 2^32).
 struct GatherJob {
   ShardTable src;
   ShardLayout lay;

@@ -93,7 +93,9 @@ struct W4Operand {
 // the dX pass that follows it).  Every workgroup copies total_vecs / gridDim.x vectors, 256 per K block: one 16-byte
 // load and one 16-byte store per lane and block, against that block's 16 KB of operand loads per wave.  A gather
 // kernel of its own cannot run beside this kernel, whose four waves hold every register of their SIMDs: on a second
-// stream it only takes turns with the tiles, and both get slower.
+// stream it only takes turns with the tiles, and both get slower.  The carried copy is not free either (the kernel
+// is bound by the memory pipe the copy shares: a 64 MiB slice adds 25 us to a 190 us launch, against 28 us as a
+// launch of its own); it saves the launch, its gap and every cross-stream event.
 template <bool kAK, bool kBKc, int kEpi, bool kAccIn, bool kCopy = false>
 __global__ __launch_bounds__(256, 1)
 void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {

@@ -80,7 +80,7 @@ struct GemmProblem {
   int64_t c0;           // kBf16ShardMajor only: column offset of C inside the full matrix
   int64_t r0;           // kBf16ShardMajor only: row offset of C inside the full matrix
   // Optional: a gather (into a staging slot this launch does not read) that the launch may take along.  The
-  // four-wave kernel runs it inside the launch, in the shadow of its MFMAs, and sets *carried; any other kernel
+  // four-wave kernel runs it inside the launch, between its MFMAs, and sets *carried; any other kernel
   // leaves *carried false and the gather to the caller.  carried must be given when carry is.
   const GatherRequest *carry;
   bool *carried;
