@@ -203,7 +203,7 @@ OSDP_API osdp_status osdp_split_linear_fwd(const osdp_shape *shape, const osdp_p
 
 /* For callers that cannot allocate device memory or hand over a workspace (code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc): osdp_split_linear_fwd on one
- * stream, with the staging slots and the fp32 partial sum kept in a fixed array of
+ * stream, with the staging slots, the fp32 partial sum and the fp32 planes of a forward summed in parts kept in a fixed array of
  * OSDP_NOALLOC_SCRATCH_BYTES that is part of the library's device code (one copy per GPU, held
  * until the process ends).  Same arguments, layouts, results (bit for bit) and errors as
  * osdp_split_linear_fwd with stream_copy = NULL; nothing is allocated, no event is created.
