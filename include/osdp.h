@@ -108,9 +108,12 @@ typedef enum {
   OSDP_STAGING_AUTO = 0,   /* DOUBLE when two distinct streams are given and k > 1, else SINGLE */
   OSDP_STAGING_SINGLE = 1, /* one slot of one slice (size/k): gather and GEMM alternate, no overlap */
   OSDP_STAGING_DOUBLE = 2, /* two slots of one slice (2*size/k): gather j+1 overlaps GEMM j        */
-  OSDP_STAGING_HALF = 3    /* two slots of half a slice (size/k in total): every slice is processed
-                              as two half-width sub-slices, each with a GEMM launch of its own, so
-                              that the gather of one half overlaps the GEMM of the other          */
+  OSDP_STAGING_HALF = 3    /* two slots of half a slice (size/k in total): a slice is processed either as
+                              two half-width sub-slices in a ring (the gather of one half rides along
+                              with the GEMM of the other) or, when the library estimates that faster,
+                              as one slice staged across both slots (the SINGLE schedule).  On one
+                              GPU the ring seldom pays: half-width launches have half the output
+                              tiles, and an overlapped gather costs the GEMM beside it what it saves */
 } osdp_staging_mode;
 
 /* Which dimension of W the k slices cut. */

@@ -256,9 +256,10 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
   // fewer half-empty rounds of tiles; row slices: one trip of the fp32 partial sum through the workspace less)
   // at the price of exposing their gathers; taken when the estimate says it pays.
   r->fwd.clear();
-  // (never with half-slice staging: a launch over both halves would hold the whole staging area, and the
-  // mode would degenerate to SINGLE with nothing left for the next gather to overlap)
-  bool pair_fwd = r->slots == 2 && n >= 2 && mode != OSDP_STAGING_HALF;
+  // (with half-slice staging a launch over both halves is the one-slot schedule: one copy of the whole slice, one
+  // GEMM; the estimate decides here too, because on one GPU a gather that overlaps costs the GEMM beside it what
+  // it saves, while half-width launches have half the output tiles)
+  bool pair_fwd = r->slots == 2 && n >= 2;
   if (pair_fwd) {
     double t_single = 0.0, t_pair = 0.0, t_carried = 0.0;
     const double acc_trip_us = 8.0 * static_cast<double>(T) * static_cast<double>(D) / 3.0e6;  // fp32 out and back in
