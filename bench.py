@@ -168,6 +168,28 @@ def per_step_times(st, iters, warmup, serial):
     return ms[len(ms) // 2], sum(ms) / len(ms)
 
 
+def graph_replay_ms(st, iters, warmup):
+    """One step captured into a HIP graph on the compute stream (the cross-stream edges of the two-stream pipeline
+    inside the capture), then replayed: median ms per replay.  What the launch gaps of the eager step cost."""
+    torch = st.torch
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=st.sc):
+        st.step(False)
+    with torch.cuda.stream(st.sc):
+        for _ in range(warmup):
+            graph.replay()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+        for e0, e1 in ev:
+            e0.record(st.sc)
+            graph.replay()
+            e1.record(st.sc)
+        torch.cuda.synchronize()
+    ms = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+    del graph
+    return ms[len(ms) // 2]
+
+
 def kernel_table(stats):
     out = {}
     for name, s in stats.items():
@@ -423,6 +445,10 @@ def main():
         "headline_steps_executed": a.warmup + a.steps + a.warmup + max(a.steps, 20) + 2 + max(10, max(a.steps, 20) // 2),
     }
     sub_steps, sub_warm = max(20, a.steps // 2), max(3, a.warmup // 2)
+    if not a.serial and a.zdp_slices is None:
+        # the same step captured into a HIP graph and replayed: what the eager step's launch gaps cost
+        mg = graph_replay_ms(st, max(a.steps, 20), a.warmup)
+        out["graph_replay"] = {"tflops": round(flops / (mg * 1e-3) / 1e12, 2), "median_ms_per_step": round(mg, 4)}
 
     if not a.no_sweep and a.zdp_slices is None:
         # the gather kernel on its own: one slice of the first operator, back to back (achieved HBM rate of the copy)
@@ -518,7 +544,9 @@ def main():
             wc = wl.workload(cfg)
             st = Stack(wc, staging, torch, osdp)
             mc = measure(st, wl.flops(wc), sub_steps, sub_warm, False, config=cfg)
-            entry = {"workload": wc.name, "baseline_config": cfg, "plan": {op.name: op.k for op in wc.ops}}
+            mg = graph_replay_ms(st, sub_steps, sub_warm)
+            entry = {"workload": wc.name, "baseline_config": cfg, "plan": {op.name: op.k for op in wc.ops},
+                     "graph_replay": {"tflops": round(wl.flops(wc) / (mg * 1e-3) / 1e12, 2), "median_ms_per_step": round(mg, 4)}}
             entry.update({key: mc[key] for key in ("tflops", "frac_bf16_mfma_peak", "median_ms_per_step", "mean_ms_per_step",
                                                    "timed_steps", "peak_staging_mb", "workspace_mb", "roofline", "gathers",
                                                    "idle_us_per_step", "kernels")})
