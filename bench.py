@@ -190,6 +190,56 @@ def graph_replay_ms(st, iters, warmup):
     return ms[len(ms) // 2]
 
 
+def library_vs_vendor_gemm(torch, osdp, size=8192, reps=10):
+    """The three GEMM layouts of the path on one cube, library launches (k = 1, timed by the library's own events)
+    beside torch.matmul (the vendor GEMM library) on the same box in the same process: context for the roofline
+    fractions, since boxes and their power limits differ."""
+    T = I = O = size
+    N = 8
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    X = torch.randn(T, I, generator=g, device="cuda").to(torch.bfloat16)
+    dY = torch.randn(T, O, generator=g, device="cuda").to(torch.bfloat16)
+    Wd = (torch.randn(I, O, generator=g, device="cuda") * 0.02).to(torch.bfloat16)
+    L = I * O // N
+    W = [Wd.reshape(-1)[s * L:(s + 1) * L].clone() for s in range(N)]
+    dW = [torch.empty(L, dtype=torch.bfloat16, device="cuda") for _ in range(N)]
+    Y = torch.empty(T, O, dtype=torch.bfloat16, device="cuda")
+    dX = torch.empty(T, I, dtype=torch.bfloat16, device="cuda")
+    plan = osdp.Plan([1])
+    need = max(osdp.osdp_split_linear_workspace_bytes(T, I, O, N, 1, b, plan, 0)[0] for b in (False, True))
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    sc = torch.cuda.Stream()
+    with torch.cuda.stream(sc):
+        for rep in range(2):
+            if rep == 1:
+                osdp.osdp_profile_begin()
+            for _ in range(reps if rep else 3):
+                osdp.osdp_split_linear_fwd(X, W, Y, 1, ws, plan=plan, stream_compute=sc)
+                osdp.osdp_split_linear_bwd(X, dY, W, dX, dW, 1, ws, plan=plan, stream_compute=sc)
+            sc.synchronize()
+        st = osdp.osdp_profile_end()
+    flops = 2.0 * size ** 3
+    lib = {kind: round(flops / (st[name]["ms"] / st[name]["launches"] * 1e-3) / 1e12, 1)
+           for kind, name in (("fwd_nn", "gemm_fwd"), ("dx_nt", "gemm_dx"), ("dw_tn", "gemm_dw"))}
+
+    def vendor(fn):
+        for _ in range(3):
+            fn()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for e0, e1 in ev:
+            e0.record()
+            fn()
+            e1.record()
+        torch.cuda.synchronize()
+        ms = sorted(e0.elapsed_time(e1) for e0, e1 in ev)[reps // 2]
+        return round(flops / (ms * 1e-3) / 1e12, 1)
+    ven = {"fwd_nn": vendor(lambda: torch.matmul(X, Wd)), "dx_nt": vendor(lambda: torch.matmul(dY, Wd.t())),
+           "dw_tn": vendor(lambda: torch.matmul(X.t(), dY))}
+    return {"shape": [size, size, size], "library_tflops": lib, "torch_matmul_tflops": ven,
+            "note": "library: per-launch HIP events around each kernel; torch.matmul: events around each call, median"}
+
+
 def kernel_table(stats):
     out = {}
     for name, s in stats.items():
@@ -535,6 +585,11 @@ def main():
         out["plan_search"] = plan_search(w, m["kernels"], staging, rows, torch, osdp, sub_steps, sub_warm)
     if not a.no_auto:
         out["auto_granularity"] = auto_granularity(st, osdp, torch, sub_steps, sub_warm)
+    if not a.no_sweep and default_plan:
+        del st
+        torch.cuda.empty_cache()
+        out["gemm_8192_cubed_library_vs_vendor"] = library_vs_vendor_gemm(torch, osdp)
+        st = Stack(w, staging, torch, osdp, rows=rows, longer=longer)
     if not a.no_sweep and default_plan:
         # the other workloads under their own plan vectors, each with its own roofline
         also = []
