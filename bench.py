@@ -45,9 +45,10 @@ def parse():
     ap.add_argument("--config", type=int, default=4, help="workload: index into BASELINE.json configs (1-based)")
     ap.add_argument("--k", type=int, default=None, help="slice granularity (default: the workload's own)")
     ap.add_argument("--staging", choices=["auto", "single", "double", "half"], default="auto")
-    ap.add_argument("--split-dim", choices=["out", "in", "longer"], default="out",
+    ap.add_argument("--split-dim", choices=["out", "in", "longer", "perpass"], default="out",
                     help="cut W along its output features (columns), its input features (rows, the reduction "
-                         "dimension), or per operator along the longer of the two")
+                         "dimension), per operator along the longer of the two, or along the columns in the forward pass and "
+                         "the rows in the backward pass (no fp32 partial sum in either)")
     ap.add_argument("--zdp-slices", type=int, default=None,
                     help="keep only the first Z slices of every operator sharded (ZDP); the others are DP slices "
                          "read from a resident replica (default: every slice ZDP)")
@@ -68,7 +69,7 @@ class Stack:
     """All operators of a workload resident on the GPU, with one shared workspace."""
 
     def __init__(self, w, staging, torch, osdp, seed=0, rows=False, plan=None, zdp_slices=None, zdp_masks=None,
-                 longer=False):
+                 longer=False, per_pass=False):
         self.w, self.torch, self.osdp = w, torch, osdp
         g = torch.Generator(device="cuda")
         g.manual_seed(220913258 + seed)
@@ -90,6 +91,8 @@ class Stack:
         dims = [osdp.OSDP_SPLIT_IN_FEATURES if rows else osdp.OSDP_SPLIT_OUT_FEATURES] * len(w.ops)
         if longer:
             dims = [osdp.OSDP_SPLIT_LONGER] * len(w.ops)
+        if per_pass:
+            dims = [osdp.OSDP_SPLIT_PER_PASS] * len(w.ops)
         self.plan = plan or osdp.Plan([op.k for op in w.ops], staging=staging, split_dim_per_op=dims)
         # zdp_slices = z: the first z slices of every operator stay sharded (ZDP), the others are DP slices read from
         # a resident full-layout replica, their gradients written to a full-layout array
@@ -460,9 +463,10 @@ def main():
     w = wl.workload(a.config, a.k)
     rows = a.split_dim == "in"
     longer = a.split_dim == "longer"
-    st = Stack(w, staging, torch, osdp, rows=rows, zdp_slices=a.zdp_slices, longer=longer)
+    per_pass = a.split_dim == "perpass"
+    st = Stack(w, staging, torch, osdp, rows=rows, zdp_slices=a.zdp_slices, longer=longer, per_pass=per_pass)
     flops = wl.flops(w)
-    default_plan = a.k is None and a.staging == "auto" and not a.serial and not rows and not longer and \
+    default_plan = a.k is None and a.staging == "auto" and not a.serial and not rows and not longer and not per_pass and \
         a.zdp_slices is None and a.gathers == "carried"
 
     # ---- the headline: exactly --steps steps after --warmup, one timed region, inputs resident ------------
@@ -481,7 +485,7 @@ def main():
         "config": {"workload": w.name, "baseline_config": a.config, "T": w.T, "N_shards": w.N, "layers": w.layers,
                    "ops": {op.name: {"I": op.I, "O": op.O, "k": op.k} for op in w.ops},
                    "staging": a.staging, "streams": 1 if a.serial else 2, "gathers": a.gathers,
-                   "split_dim": "longer" if longer else "in_features" if rows else "out_features",
+                   "split_dim": "longer" if longer else "per_pass" if per_pass else "in_features" if rows else "out_features",
                    "zdp_slices": "all" if a.zdp_slices is None else a.zdp_slices},
         "frac_bf16_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
         "peak_staging_mb": m["peak_staging_mb"], "workspace_mb": m["workspace_mb"],
@@ -522,8 +526,9 @@ def main():
 
     if not a.no_sweep and a.zdp_slices is None:
         # Section 4.3, slice granularity: every k of the workload's sweep under every staging mode (column slices, gathers
-        # carried by the GEMM launches), then the same k with every operator cut along its longer dimension, and
-        # with every gather a launch of its own on the copy stream (the two-stream pipeline)
+        # carried by the GEMM launches), then the same k with every operator cut along its longer dimension, with the
+        # columns cut in the forward pass and the rows in the backward pass, and with every gather a launch of its own
+        # on the copy stream (the two-stream pipeline)
         sweep = {}
         ks = tuple(w.k_sweep or ())
         if ks and 1 not in ks:
@@ -552,6 +557,13 @@ def main():
                                                   "workspace_mb": round(st.workspace_bytes / 2 ** 20, 3)}
                 del st
                 torch.cuda.empty_cache()
+                st = Stack(wk, modes["double"], torch, osdp, per_pass=True)
+                mp = per_step_times(st, sub_steps, sub_warm, a.serial)[0]
+                row["double_per_pass_split_dim"] = {"tflops": round(fk / (mp * 1e-3) / 1e12, 2), "median_ms_per_step": round(mp, 4),
+                                                    "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3),
+                                                    "workspace_mb": round(st.workspace_bytes / 2 ** 20, 3)}
+                del st
+                torch.cuda.empty_cache()
                 osdp.osdp_debug_option("fused_gather", 0)
                 st = Stack(wk, modes["double"], torch, osdp, rows=rows)
                 m2 = measure(st, fk, sub_steps, sub_warm, False)
@@ -566,7 +578,7 @@ def main():
         out["k_sweep"] = sweep
         del st
         torch.cuda.empty_cache()
-        st = Stack(w, staging, torch, osdp, rows=rows, longer=longer)
+        st = Stack(w, staging, torch, osdp, rows=rows, longer=longer, per_pass=per_pass)
 
     if not a.no_sweep and a.zdp_slices is None:
         # Section 3.3, last paragraph: the same granularity with fewer and fewer slices in ZDP mode
@@ -589,7 +601,7 @@ def main():
         del st
         torch.cuda.empty_cache()
         out["gemm_8192_cubed_library_vs_vendor"] = library_vs_vendor_gemm(torch, osdp)
-        st = Stack(w, staging, torch, osdp, rows=rows, longer=longer)
+        st = Stack(w, staging, torch, osdp, rows=rows, longer=longer, per_pass=per_pass)
     if not a.no_sweep and default_plan:
         # the other workloads under their own plan vectors, each with its own roofline
         also = []
@@ -612,6 +624,13 @@ def main():
             entry["longer_split_dim"] = {"tflops": round(wl.flops(wc) / (mlc * 1e-3) / 1e12, 2), "median_ms_per_step": round(mlc, 4),
                                          "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3),
                                          "workspace_mb": round(st.workspace_bytes / 2 ** 20, 3)}
+            del st
+            torch.cuda.empty_cache()
+            st = Stack(wc, staging, torch, osdp, per_pass=True)
+            mpc = per_step_times(st, sub_steps, sub_warm, False)[0]
+            entry["per_pass_split_dim"] = {"tflops": round(wl.flops(wc) / (mpc * 1e-3) / 1e12, 2), "median_ms_per_step": round(mpc, 4),
+                                           "peak_staging_mb": round(st.peak_staging / 2 ** 20, 3),
+                                           "workspace_mb": round(st.workspace_bytes / 2 ** 20, 3)}
             also.append(entry)
         out["also"] = also
     if not a.no_cpu:

@@ -121,9 +121,14 @@ typedef enum {
   OSDP_SPLIT_OUT_FEATURES = 0, /* columns of W: Y and dW concatenate, dX is summed                   */
   OSDP_SPLIT_IN_FEATURES = 1,  /* rows of W, the forward product's reduction dimension (Section 3.3
                                   as printed): Y is summed, dW and dX concatenate                     */
-  OSDP_SPLIT_LONGER = 2        /* whichever of the two is longer (columns when I == O): the fp32 partial
+  OSDP_SPLIT_LONGER = 2,       /* whichever of the two is longer (columns when I == O): the fp32 partial
                                   sum is T x the other dimension, and measured on MI355X the longer cut
                                   is the faster one at every granularity                              */
+  OSDP_SPLIT_PER_PASS = 3      /* columns in the forward pass, rows in the backward pass: Y, dX and dW are
+                                  all concatenations, no fp32 partial sum exists in either pass; every
+                                  slice is still size/k (the passes gather differently shaped slices of
+                                  the same size).  Needs both I/k and O/k bounds on multiples of 8; not
+                                  with slices in DP mode                                               */
 } osdp_split_dim;
 
 /* The per-operator execution plan (the paper's plan vector p over the n
@@ -232,7 +237,8 @@ OSDP_API osdp_status osdp_split_linear_fwd_noalloc(const osdp_shape *shape, cons
  *   dw_shards : host array of N device pointers, each L elements
  * With row slices: dW[r0_j:r1_j, :] = X[:, r0_j:r1_j]^T . dY and dX[:, r0_j:r1_j] = dY . Wr_j^T, no sum.
  * dW is bit-identical for every k and split dimension; dX is too when every slice width is a
- * multiple of 16 (row slices: always). */
+ * multiple of 16 (row slices: always; with T <= 4096 and O >= 16384 their dX is summed in parts of 8192 output
+ * features, like the forward product of column slices, whatever k). */
 OSDP_API osdp_status osdp_split_linear_bwd(const osdp_shape *shape, const osdp_plan *plan, int32_t op_index,
                                   const void *X, int64_t ldx, const void *dY, int64_t lddy,
                                   const void *const *w_shards, void *dX, int64_t lddx,

@@ -27,6 +27,7 @@ OSDP_STAGING_HALF = 3
 OSDP_SPLIT_OUT_FEATURES = 0
 OSDP_SPLIT_IN_FEATURES = 1
 OSDP_SPLIT_LONGER = 2
+OSDP_SPLIT_PER_PASS = 3
 
 OSDP_NOALLOC_SCRATCH_BYTES = 64 << 20
 

@@ -74,7 +74,7 @@ struct Resolved {
   size_t slot_bytes;         // one staging slot, rounded up to kSlotAlign
   size_t peak_staging;       // gathered-weight bytes live at the peak (unrounded)
   size_t acc_bytes;          // fp32 accumulator T x D (more than one accumulating launch: dX for column slices, Y for row slices)
-  size_t parts_bytes;        // fp32 planes of the widest forward launch when the product is split along K (0: it is not)
+  size_t parts_bytes;        // fp32 planes of the widest concatenating launch (forward of column slices, dX of row slices) when the product is split along K (0: it is not)
   // launch plan; every entry is a range [c0, c1) of sub-slice indices
   std::vector<Slice> fwd;    // forward GEMM launches: one sub-slice, or two staged ones in one launch
   std::vector<Slice> group;  // backward: sub-slices staged together
@@ -129,7 +129,7 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
   if (st != OSDP_OK) return st;
   int64_t k = shape->k;
   int32_t mode = OSDP_STAGING_AUTO;
-  bool rows = false;
+  bool rows = false, per_pass = false;
   const uint64_t *mask = nullptr;
   if (plan) {
     if (plan->n_ops <= 0) return fail(OSDP_ERR_INVALID_ARG, "plan->n_ops must be positive");
@@ -143,9 +143,11 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
     if (plan->zdp_mask) mask = plan->zdp_mask + op_index;
     if (plan->split_dim_per_op) {
       const uint8_t d = plan->split_dim_per_op[op_index];
-      if (d != OSDP_SPLIT_OUT_FEATURES && d != OSDP_SPLIT_IN_FEATURES && d != OSDP_SPLIT_LONGER)
+      if (d != OSDP_SPLIT_OUT_FEATURES && d != OSDP_SPLIT_IN_FEATURES && d != OSDP_SPLIT_LONGER && d != OSDP_SPLIT_PER_PASS)
         return fail(OSDP_ERR_INVALID_ARG, "unknown split dimension %d", static_cast<int>(d));
-      rows = d == OSDP_SPLIT_IN_FEATURES || (d == OSDP_SPLIT_LONGER && shape->I > shape->O);
+      // (per pass: columns in the forward pass, rows in the backward pass, so that Y, dX and dW all concatenate)
+      rows = d == OSDP_SPLIT_IN_FEATURES || (d == OSDP_SPLIT_LONGER && shape->I > shape->O) || (d == OSDP_SPLIT_PER_PASS && is_bwd);
+      per_pass = d == OSDP_SPLIT_PER_PASS;
     }
   }
   if (k == 0) k = 1;
@@ -159,6 +161,8 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
       if (k > 64) return fail(OSDP_ERR_UNSUPPORTED, "a zdp_mask with cleared bits covers at most 64 slices (k = %lld)", (long long)k);
       if (!allow_dp)
         return fail(OSDP_ERR_UNSUPPORTED, "slices in DP mode (zdp_mask with cleared bits) need the replicas: use the _mixed entry points");
+      if (per_pass)
+        return fail(OSDP_ERR_UNSUPPORTED, "slices in DP mode need one split dimension for both passes (a replica is laid out slice by slice)");
       zdp = *mask & want;
     }
   }
@@ -366,10 +370,16 @@ osdp_status resolve(const osdp_shape *shape, const osdp_plan *plan, int32_t op_i
     if (r->any_dp) widest = O;
     r->parts_bytes = gemm_forward_parts_bytes(T, widest, D);
   }
+  if (is_bwd && bwd_concat) {  // dX of row slices: the same shape of problem
+    int64_t widest = 0;
+    for (const Slice &l : r->pass) widest = std::max(widest, span(l.c0, l.c1));
+    if (r->any_dp) widest = I;
+    r->parts_bytes = gemm_forward_parts_bytes(T, widest, D);
+  }
   return OSDP_OK;
 }
 
-// Staging slots, the fp32 partial sum, the planes of forward launches split along K.
+// Staging slots, the fp32 partial sum, the planes of concatenating launches split along K.
 size_t workspace_total(const Resolved &r) { return r.slot_bytes * r.slots + r.acc_bytes + r.parts_bytes; }
 
 osdp_status fill_table(const void *const *ptrs, int32_t N, const char *name, ShardTable *t) {
@@ -1018,6 +1028,7 @@ static osdp_status backward(const osdp_shape *shape, const osdp_plan *plan, int3
   }
   char *ws = static_cast<char *>(workspace);
   float *acc = reinterpret_cast<float *>(ws + r.slot_bytes * r.slots);  // column slices: dX's fp32 partial sum
+  void *planes = r.parts_bytes ? ws + r.slot_bytes * r.slots + r.acc_bytes : nullptr;  // row slices: planes of dX launches split along K
   const int n = static_cast<int>(r.sub.size());
   // The gathers of a group run on the copy stream behind dW.  Each group then costs four event operations, which
   // is more than a small gather takes (measured: with 4 MB groups one stream is 5-12 % faster, with 25 MB groups
@@ -1075,6 +1086,7 @@ static osdp_status backward(const osdp_shape *shape, const osdp_plan *plan, int3
                               weights_of(r, rep, j0, ws + static_cast<size_t>(j0 - g0) * r.slot_bytes),
                               weights_of(r, rep, j1 - 1, ws + static_cast<size_t>(j1 - 1 - g0) * r.slot_bytes), dY, lddy, dX,
                               lddx, acc, next_pass, r.pass.size());
+      gx.parts = planes; gx.parts_bytes = r.parts_bytes;
       OSDP_HIP(do_gemm(OSDP_KERNEL_GEMM_DX, gx, sc));
     }
     if (poison) OSDP_HIP(launch_fill16(ws, r.slot_bytes * r.slots, kPoison, sc));

@@ -296,11 +296,11 @@ int best_tile(int M, int N, int n_split, int kind, double *cost, int parts = 1) 
   return best;
 }
 
-// ---- forward launches split along K --------------------------------------------------------------------------
+// ---- concatenating launches split along K ----------------------------------------------------------------------
 // A slice of a wide operator applied to few tokens (4096 x 1024 x 32768) has few output tiles and a long reduction:
 // most CUs get no 256 x 256 tile, and the 128 x 128 tiles that would occupy them run at 70 % of the large tile's
-// rate.  The forward product of such an operator is therefore defined as the sum of kPartK-long parts of the
-// reduction: the parts run side by side as one launch (grid = parts x tiles), each into its own fp32 plane, and a
+// rate.  The forward product of such an operator over column slices (and likewise dX over row slices) is therefore
+// defined as the sum of kPartK-long parts of the reduction: the parts run side by side as one launch (grid = parts x tiles), each into its own fp32 plane, and a
 // second kernel adds the planes, plane 0 first, and rounds to bf16.  The number of parts depends on the token count
 // and the reduction length alone - never on the slice width, the tile shape or the kernel - so Y keeps the same bits
 // for every k, as the unsplit operator (k = 1) runs the same parts.
@@ -447,7 +447,9 @@ double plan_launches(int M, int N, int K, int kind, int *axis, int *cut) {
 
 template <bool kAK, bool kBK, int kEpi, bool kAccIn>
 hipError_t launch_planned(const GemmParams &p, hipStream_t stream, bool *carry, float *planes, size_t planes_bytes) {
-  if constexpr (kAK && !kBK && !kAccIn && kEpi == static_cast<int>(Epilogue::kBf16RowMajor)) {
+  // (forward launches of column slices, and the dX launches of row slices, which have the same shape of problem:
+  // few tokens, a slice's worth of output columns, the whole uncut dimension as the reduction)
+  if constexpr (kAK && !kAccIn && kEpi == static_cast<int>(Epilogue::kBf16RowMajor)) {
     // (a caller that passes no planes asks for the one-part product: the forward of row slices, whose launches
     // continue one accumulator chain instead)
     const int parts = (p.k_split || !planes) ? 1 : forward_k_parts(p.M, p.K);

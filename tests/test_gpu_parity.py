@@ -193,8 +193,9 @@ def _edge_entries(n, cuts):
 def _check_samples(H, oracle, label, d, got, T, I, O, N, k, rows, g, n_samples):
     """Random entries of Y, dX and dW plus every entry whose row / column lies at a slice, shard or tile edge
     paired with every such column / row (whole edge-by-edge blocks), each against the oracle's own dot product."""
-    cuts_o = [] if rows else [j * O // k for j in range(k + 1)]
-    cuts_i = [s * I // N for s in range(N + 1)] + ([j * I // k for j in range(k + 1)] if rows else [])
+    # rows: True = W cut along its rows, False = along its columns, None = columns forward and rows backward
+    cuts_o = [] if rows is True else [j * O // k for j in range(k + 1)]
+    cuts_i = [s * I // N for s in range(N + 1)] + ([j * I // k for j in range(k + 1)] if rows is not False else [])
     edges_o, edges_i, edges_t = _edge_entries(O, cuts_o), _edge_entries(I, cuts_i), _edge_entries(T, [])
 
     def pairs(n0, n1, e0, e1):
@@ -224,6 +225,8 @@ def _sampled_check(H, oracle, cfg, op_index, op, T, N, k, plan=None, n_samples=1
     got = dev.results()
     g = np.random.default_rng(cfg * 1000 + op_index)
     rows = plan is not None and _cuts_rows(plan, 0, I, O)
+    if plan is not None and plan.split_dim_per_op is not None and plan.split_dim_per_op[0] == 3:   # OSDP_SPLIT_PER_PASS
+        rows = None
     _check_samples(H, oracle, f"cfg{cfg} {op.name}", d, got, T, I, O, N, max(k, 1), rows, g, n_samples)
     # properties that hold at any size: nothing left unwritten (outputs were NaN-poisoned)
     for name in ("Y", "dX", "dW"):
@@ -1135,3 +1138,60 @@ def test_forward_parts_of_a_long_reduction_keep_the_bits_for_every_k_and_kernel(
                     assert np.array_equal(H.to_bits(op.Y), base), f"Y differs from k=1 ({setting}, k={k}, mode={mode}, pair={pair})"
         for name in setting:
             debug(name, DEBUG_DEFAULTS[name])
+
+
+# ------------------------------------------------ columns in the forward pass, rows in the backward pass
+@pytest.mark.parametrize("T,I,O,N", [(300, 264, 640, 4),      # ragged: the checked kernel
+                                     (512, 1024, 2048, 8),    # the unchecked kernels
+                                     (256, 16384, 512, 4)])   # long forward reduction: Y is summed in parts
+def test_split_per_pass_matches_the_oracle_and_the_unsplit_bits(H, oracle, T, I, O, N):
+    """OSDP_SPLIT_PER_PASS cuts W along its columns for the forward pass and along its rows for the backward pass, so
+    that Y, dX and dW are all concatenations: every k, staging mode and stream choice must give the unsplit
+    operator's bits (no reduction is reordered anywhere), the oracle's values, and the staging law of each pass."""
+    import paper_2209_13258_amd as osdp
+    d = wl.small_case(161, T, I, O, N)
+    want = oracle.linear(d["X"], d["W_shards"], O, dY=d["dY"])
+    base_op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+    base_op.fwd(1)
+    base_op.bwd(1)
+    base = base_op.results()
+    for name in ("Y", "dX", "dW"):
+        H.assert_close(name, base[name], want[name])
+    sc, sp = H.streams()
+    for k in (2, 4, 8):
+        if I % k or O % k or (I // k) % 8 or (O // k) % 8:
+            continue
+        for mode, slots in ((osdp.OSDP_STAGING_SINGLE, 1), (osdp.OSDP_STAGING_DOUBLE, 2), (osdp.OSDP_STAGING_HALF, 1)):
+            if mode == osdp.OSDP_STAGING_HALF and ((I // k) % 16 or (O // k) % 16):
+                continue
+            plan = osdp.Plan([k], staging=mode, split_dim_per_op=[osdp.OSDP_SPLIT_PER_PASS])
+            for two_streams in (False, True):
+                _announce("per pass", T, I, O, N, "k", k, "mode", mode, "two streams", two_streams)
+                op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+                torch.cuda.synchronize()
+                with torch.cuda.stream(sc):
+                    st = (sc, sp) if two_streams else (sc, None)
+                    op.fwd(k, plan=plan, streams=st)
+                    op.bwd(k, plan=plan, streams=st)
+                sc.synchronize()
+                got = op.results()
+                for name in ("Y", "dX", "dW"):
+                    assert np.array_equal(got[name], base[name]), f"{name} differs from the unsplit result (k {k}, mode {mode})"
+            _, peak_f = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, False, plan)
+            tot_b, peak_b = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, True, plan)
+            assert peak_f == oracle.peak_staging_bytes(I, O, k, slots, 2)
+            assert peak_b == oracle.peak_staging_bytes_rows(I, O, k, slots, 2)
+            assert tot_b == peak_b   # the backward pass keeps no fp32 sum (and these shapes need no planes)
+
+
+def test_split_per_pass_config4(H, oracle):
+    """Config 4 at k = 8 with the per-pass cut, the variant the benchmark reports beside the column slices: sampled
+    entries against the oracle (the forward of `down` and the dX of `up` run in parts of the reduction)."""
+    import paper_2209_13258_amd as osdp
+    w = wl.workload(4, 8)
+    for n, op in enumerate(w.ops):
+        plan = osdp.Plan([8], split_dim_per_op=[osdp.OSDP_SPLIT_PER_PASS])
+        _sampled_check(H, oracle, 4, n, op, w.T, w.N, 8, plan=plan, n_samples=20_000)
+        tot_f, _ = osdp.osdp_split_linear_workspace_bytes(w.T, op.I, op.O, w.N, 8, False, plan)
+        tot_b, _ = osdp.osdp_split_linear_workspace_bytes(w.T, op.I, op.O, w.N, 8, True, plan)
+        assert max(tot_f, tot_b) <= 256 << 20   # two 64 MiB slots and at most 128 MiB of planes: no T x I fp32 sum

@@ -408,3 +408,17 @@ int main(void) {
     r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
     assert r.stdout.strip()
+
+
+@pytest.mark.parametrize("T,I,O,N,k", [(8192, 1024, 4096, 8, 4), (16384, 2560, 10240, 8, 4), (128, 256, 1024, 2, 2)])
+def test_per_pass_split_needs_no_partial_sum(oracle, T, I, O, N, k):
+    """Columns in the forward pass, rows in the backward pass: both passes only concatenate, so the workspace is the
+    staging slots alone (these shapes need no planes), and each pass follows its own dimension's size / k law."""
+    for mode, slots in ((osdp.OSDP_STAGING_SINGLE, 1), (osdp.OSDP_STAGING_DOUBLE, 2)):
+        plan = osdp.Plan([k], staging=mode, split_dim_per_op=[osdp.OSDP_SPLIT_PER_PASS])
+        tot_f, peak_f = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, False, plan)
+        tot_b, peak_b = osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, True, plan)
+        assert tot_f == peak_f == oracle.peak_staging_bytes(I, O, k, slots, 2)
+        assert tot_b == peak_b == oracle.peak_staging_bytes_rows(I, O, k, slots, 2)
+    with pytest.raises(osdp.OsdpError):   # a replica is laid out slice by slice: one split dimension for both passes
+        osdp.osdp_split_linear_workspace_bytes(T, I, O, N, k, True, osdp.Plan([k], zdp_mask=[1], split_dim_per_op=[osdp.OSDP_SPLIT_PER_PASS]))
