@@ -313,7 +313,7 @@ def auto_granularity(st, osdp, torch, steps, warmup):
 
         def show(i):
             c = cands[i]
-            return {"k": c.k, "split_dim": "in" if c.split_dim else "out", "staging": names[c.staging],
+            return {"k": c.k, "split_dim": {0: "out", 1: "in", 3: "per_pass"}[c.split_dim], "staging": names[c.staging],
                     "peak_staging_mb": round(c.peak_weight_staging / 2 ** 20, 3), "workspace_mb": round(c.workspace / 2 ** 20, 3),
                     "ms": round(c.ms, 4), "tflops": round(6 * st.w.T * op.I * op.O / (c.ms * 1e-3) / 1e12, 1)}
         same_budget = osdp.osdp_granularity_select(cands, st.peak_staging, 0, 0.0)

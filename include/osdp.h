@@ -301,8 +301,8 @@ typedef struct {
 
 /* Lists the combinations that osdp_split_linear_fwd / _bwd accept for this
  * shape (shape->k is ignored): for every k of k_list (host, n_k entries >= 1;
- * NULL = 1, 2, 3, 4, 6, 8, 12, 16), in the order given, for the column split
- * then the row split, for SINGLE, DOUBLE, HALF staging.  Combinations that
+ * NULL = 1, 2, 3, 4, 6, 8, 12, 16), in the order given, for the column split,
+ * the row split, then the per-pass split, for SINGLE, DOUBLE, HALF staging.  Combinations that
  * resolve to the same execution are listed once (k = 1: one SINGLE entry).
  * Writes at most `capacity` entries to out (ms = 0) and the full count to
  * *count; out may be NULL when capacity is 0. Host only. */

@@ -1132,7 +1132,7 @@ osdp_status osdp_granularity_candidates(const osdp_shape *shape, const int32_t *
   for (int32_t i = 0; i < n_k; ++i) {
     const int32_t k = k_list[i];
     if (k < 1) return fail(OSDP_ERR_INVALID_ARG, "k_list[%d] = %d is below 1", i, k);
-    for (uint8_t dim : {uint8_t(OSDP_SPLIT_OUT_FEATURES), uint8_t(OSDP_SPLIT_IN_FEATURES)})
+    for (uint8_t dim : {uint8_t(OSDP_SPLIT_OUT_FEATURES), uint8_t(OSDP_SPLIT_IN_FEATURES), uint8_t(OSDP_SPLIT_PER_PASS)})
       for (int32_t mode : {int32_t(OSDP_STAGING_SINGLE), int32_t(OSDP_STAGING_DOUBLE), int32_t(OSDP_STAGING_HALF)}) {
         // the unsplit operator is the same execution whichever dimension is named, and has nothing to double-buffer
         if (k == 1 && (mode == OSDP_STAGING_DOUBLE || (mode == OSDP_STAGING_SINGLE && dim != OSDP_SPLIT_OUT_FEATURES))) continue;
@@ -1143,7 +1143,7 @@ osdp_status osdp_granularity_candidates(const osdp_shape *shape, const int32_t *
         if (n < capacity) {
           osdp_granularity_candidate &c = out[n];
           c.k = k; c.staging = mode; c.split_dim = dim; c.reserved = 0;
-          c.peak_weight_staging = f.peak_staging;
+          c.peak_weight_staging = std::max(f.peak_staging, b.peak_staging);  // (the two passes may cut different dimensions)
           c.workspace = std::max(workspace_total(f), workspace_total(b));
           c.ms = 0.0;
         }
@@ -1199,7 +1199,8 @@ osdp_status osdp_granularity_measure(const osdp_shape *shape, const void *X, int
     const osdp_granularity_candidate &c = cands[i];
     const uint8_t dim = static_cast<uint8_t>(c.split_dim);
     osdp_plan plan = {1, &c.k, nullptr, c.staging, &dim};
-    if (c.k < 1 || c.split_dim < 0 || c.split_dim > 1) return fail(OSDP_ERR_INVALID_ARG, "candidate %d is malformed", i);
+    if (c.k < 1 || (c.split_dim != OSDP_SPLIT_OUT_FEATURES && c.split_dim != OSDP_SPLIT_IN_FEATURES && c.split_dim != OSDP_SPLIT_PER_PASS))
+      return fail(OSDP_ERR_INVALID_ARG, "candidate %d is malformed", i);
     for (int is_bwd = 0; is_bwd < 2; ++is_bwd) {
       Resolved r;
       if ((st = resolve(shape, &plan, 0, two_streams, is_bwd != 0, &r)) != OSDP_OK) return st;

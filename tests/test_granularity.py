@@ -109,24 +109,28 @@ def test_candidates_are_exactly_what_the_kernels_take(oracle, T, I, O, N):
            for c in osdp.osdp_granularity_candidates(T, I, O, N)]
     want = []
     for k in ks:
-        for dim, length, rng in ((0, O, oracle.slice_range), (1, I, oracle.row_slice_range)):
-            if k > length:
+        for dim in (0, 1, 3):   # columns, rows, columns forward + rows backward (both sets of bounds must be taken)
+            sets = [(O, oracle.slice_range)] * (dim != 1) + [(I, oracle.row_slice_range)] * (dim != 0)
+            if any(k > length for length, _ in sets):
                 continue
-            bounds = [rng(length, k, j) for j in range(k)]
+            bounds = [rng(length, k, j) for length, rng in sets for j in range(k)]
             if any(a % 8 or b % 8 for a, b in bounds):
                 continue
             for mode in (osdp.OSDP_STAGING_SINGLE, osdp.OSDP_STAGING_DOUBLE, osdp.OSDP_STAGING_HALF):
-                if k == 1 and (mode == osdp.OSDP_STAGING_DOUBLE or (mode == osdp.OSDP_STAGING_SINGLE and dim == 1)):
+                if k == 1 and (mode == osdp.OSDP_STAGING_DOUBLE or (mode == osdp.OSDP_STAGING_SINGLE and dim != 0)):
                     continue
                 if mode == osdp.OSDP_STAGING_HALF and any((b - a) % 16 for a, b in bounds):
                     continue
-                law = oracle.peak_staging_bytes_rows if dim else oracle.peak_staging_bytes
-                widest = max(b - a for a, b in bounds)
-                other = O if dim else I
-                if mode == osdp.OSDP_STAGING_HALF:
-                    peak = 2 * (widest // 2) * other * 2
-                else:
-                    peak = law(I, O, k, 2 if mode == osdp.OSDP_STAGING_DOUBLE else 1, 2)
+                peak = 0
+                for length, rng in sets:   # the larger of the passes' peaks
+                    rows = rng is oracle.row_slice_range
+                    law = oracle.peak_staging_bytes_rows if rows else oracle.peak_staging_bytes
+                    widest = max(b - a for a, b in (rng(length, k, j) for j in range(k)))
+                    other = O if rows else I
+                    if mode == osdp.OSDP_STAGING_HALF:
+                        peak = max(peak, 2 * (widest // 2) * other * 2)
+                    else:
+                        peak = max(peak, law(I, O, k, 2 if mode == osdp.OSDP_STAGING_DOUBLE else 1, 2))
                 want.append((k, dim, mode, peak))
     assert [g[:4] for g in got] == want
     for k, dim, mode, peak, ws, ms in got:
