@@ -1195,3 +1195,48 @@ def test_split_per_pass_config4(H, oracle):
         tot_f, _ = osdp.osdp_split_linear_workspace_bytes(w.T, op.I, op.O, w.N, 8, False, plan)
         tot_b, _ = osdp.osdp_split_linear_workspace_bytes(w.T, op.I, op.O, w.N, 8, True, plan)
         assert max(tot_f, tot_b) <= 256 << 20   # two 64 MiB slots and at most 128 MiB of planes: no T x I fp32 sum
+
+
+@pytest.mark.parametrize("T,I,O,N", [(512, 1024, 32768, 8),    # four parts of 8192 output features
+                                     (300, 520, 49152, 4)])    # six parts; ragged: the checked kernel
+def test_dx_parts_of_a_long_reduction_keep_the_bits_for_every_k_and_kernel(H, oracle, T, I, O, N, debug):
+    """The mirror image for row slices: dX[:, rows_j] = dY . W[rows_j, :]^T reduces over all O output features, in
+    parts of 8192 when few tokens meet a long reduction; the number of parts depends on T and O alone, so dX keeps
+    the bits of the unsplit operator under a row plan for every k, staging mode, tile shape and kernel."""
+    import paper_2209_13258_amd as osdp
+    d = wl.small_case(171, T, I, O, N)
+    want = oracle.linear(d["X"], d["W_shards"], O, dY=d["dY"], want=("dX",))
+    rows = [osdp.OSDP_SPLIT_IN_FEATURES]
+
+    def run(k, mode):
+        plan = osdp.Plan([k], staging=mode, split_dim_per_op=rows)
+        op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+        sc, sp = H.streams()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(sc):
+            op.bwd(k, plan=plan, streams=(sc, sp))
+        sc.synchronize()
+        return H.to_bits(op.dX)
+
+    base = run(1, osdp.OSDP_STAGING_SINGLE)
+    H.assert_close("dX", base, want["dX"])
+    debug("split_k", 0)
+    one_part = run(1, osdp.OSDP_STAGING_SINGLE)
+    debug("split_k", -1)
+    H.assert_close("dX (one part)", one_part, want["dX"])
+    assert not np.array_equal(base, one_part)
+    fast = T % 128 == 0 and I % 128 == 0
+    settings = [dict()] + ([dict(tile=t, four_wave=f) for t, f in ((0, 0), (0, 1), (3, -1))] if fast else []) + [dict(gemm_generic=1)]
+    for setting in settings:
+        for name, value in setting.items():
+            debug(name, value)
+        for k in (1, 2, 4):
+            if I % k or (I // k) % 8:
+                continue
+            for mode in (osdp.OSDP_STAGING_SINGLE, osdp.OSDP_STAGING_DOUBLE, osdp.OSDP_STAGING_HALF):
+                if mode == osdp.OSDP_STAGING_HALF and (I // k) % 16:
+                    continue
+                _announce("dX parts", T, I, O, N, setting, "k", k, "mode", mode)
+                assert np.array_equal(run(k, mode), base), f"dX differs from k=1 ({setting}, k={k}, mode={mode})"
+        for name in setting:
+            debug(name, DEBUG_DEFAULTS[name])
