@@ -51,11 +51,21 @@ __device__ __forceinline__ void mma_16x16x32_agpr(f32x4 &c, bf16x8 a_rows, bf16x
 // A wave-level direct-to-LDS load that is issued with all lanes off when `on` is 0 (it then moves nothing): the loads
 // of K blocks beyond the last, which the uniform K loop below would otherwise fetch for nobody.  All 64 lanes are
 // active wherever the kernel calls this, so EXEC is put back to all ones.
-__device__ __forceinline__ void dma16_if(uint32_t on, const uint16_t *src, uint32_t dst) {  // on: 0 or 0xffffffff
+// The source is a byte address common to the wave (in scalar registers) plus a 32-bit byte offset per lane: the 16
+// loads of a K block then share two lane offsets that never change, and moving on to the next block is scalar
+// arithmetic, where per-lane 64-bit pointers cost 32 registers and a vector add each per block.
+__device__ __forceinline__ void dma16_if(uint32_t on, uint64_t base, uint32_t lane_off, uint32_t dst) {  // on: 0 or 0xffffffff
   const uint32_t m0 = __builtin_amdgcn_readfirstlane(dst), half = __builtin_amdgcn_readfirstlane(on);
   asm volatile("s_mov_b32 exec_lo, %0\n\ts_mov_b32 exec_hi, %0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\t"
-               "global_load_lds_dwordx4 %2, off\n\ts_mov_b64 exec, -1"
-               ::"s"(half), "s"(m0), "v"(src) : "memory");
+               "global_load_lds_dwordx4 %2, %3\n\ts_mov_b64 exec, -1"
+               ::"s"(half), "s"(m0), "v"(lane_off), "s"(base) : "memory");
+}
+
+// A 64-bit value that is the same in every lane, as the compiler can see.
+__device__ __forceinline__ uint64_t uniform64(uint64_t v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+  return (static_cast<uint64_t>(hi) << 32) | lo;
 }
 
 // One operand's share of a ring slot: 256 rows (or columns) x 64 k, 32 KB, filled by 32 wave-level
@@ -114,8 +124,9 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
   }
   const int tid = threadIdx.x;
   // ---- the carried gather: this workgroup's range of vectors, piece i = vectors first + 256 i + tid ----------
-  // Pieces beyond the range copy the range's last vector again (the same bytes to the same place), so that every
-  // K block runs the same instructions; a workgroup whose range is empty does that with the job's vector 0.
+  // Lanes beyond the range's end inside its last piece copy the range's last vector again (the same bytes to the
+  // same place); K blocks beyond the last piece issue nothing for the copy (one uniform test per hook), which is what
+  // keeps a small slice cheap to carry through a long reduction.
   uint64_t copy_first = 0, copy_last = 0;
   uint32_t copy_pieces = 0;
   const uint16_t *const *g_tab = nullptr;
@@ -182,15 +193,15 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
   const uint16_t *baseB = second ? p.B2 : p.B;
   const int64_t ldb = second ? p.ldb2 : p.ldb;
   const int nB = second ? n0 - p.n_split : n0;
-  const uint16_t *srcA[OpA::kLoads], *srcB[OpB::kLoads];
-  {
-    const uint16_t *a0 = (kAK ? p.A + static_cast<int64_t>(m0) * p.lda + k0 : p.A + m0 + k0 * p.lda) + OpA::lane_src(wave, lane, p.lda);
-    const uint16_t *b0 = (kBKc ? baseB + static_cast<int64_t>(nB) * ldb + k0 : baseB + nB + k0 * ldb) + OpB::lane_src(wave, lane, ldb);
-#pragma unroll
-    for (int i = 0; i < OpA::kLoads; ++i) srcA[i] = a0 + OpA::load_rows(i) * p.lda;
-#pragma unroll
-    for (int i = 0; i < OpB::kLoads; ++i) srcB[i] = b0 + OpB::load_rows(i) * ldb;
-  }
+  // Source of load i of an operand's current K block: byte address blockX + rowX(i), the same for the whole wave,
+  // plus this lane's byte offset laneX (all offsets inside a 256-row block are far below 2^32 bytes).
+  uint64_t blockA = uniform64(reinterpret_cast<uint64_t>(kAK ? p.A + static_cast<int64_t>(m0) * p.lda + k0 : p.A + m0 + k0 * p.lda));
+  uint64_t blockB = uniform64(reinterpret_cast<uint64_t>(kBKc ? baseB + static_cast<int64_t>(nB) * ldb + k0 : baseB + nB + k0 * ldb));
+  const uint32_t laneA = static_cast<uint32_t>(OpA::lane_src(wave, lane, p.lda) * 2);
+  uint32_t laneB = static_cast<uint32_t>(OpB::lane_src(wave, lane, ldb) * 2);
+  auto rowA = [&](int i) { return static_cast<uint64_t>(OpA::load_rows(i)) * static_cast<uint64_t>(p.lda) * 2; };
+  int64_t ldb_cur = ldb;
+  auto rowB = [&](int i) { return static_cast<uint64_t>(OpB::load_rows(i)) * static_cast<uint64_t>(ldb_cur) * 2; };
   const int64_t stepA = OpA::block_stride(p.lda);
   int64_t stepB = OpB::block_stride(ldb);
   const int nb = K / 64;
@@ -220,19 +231,19 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
     constexpr int i = decltype(idx)::value;
     const uint32_t sb = lds_base + slot * (kSlotElems * 2);
     if constexpr (i < OpA::kLoads) {
-      dma16_if(load_mask, srcA[i], sb + dstA[i]);
-      srcA[i] += advA;
+      dma16_if(load_mask, blockA + rowA(i), laneA, sb + dstA[i]);
+      if constexpr (i == OpA::kLoads - 1) blockA += static_cast<uint64_t>(advA) * 2;  // on to the next K block
     } else {
       constexpr int j = i - OpA::kLoads;
-      dma16_if(load_mask, srcB[j], sb + dstB[j]);
-      srcB[j] += advB;
+      dma16_if(load_mask, blockB + rowB(j), laneB, sb + dstB[j]);
+      if constexpr (j == OpB::kLoads - 1) blockB += static_cast<uint64_t>(advB) * 2;
     }
   };
   auto block_issued = [&]() {
-    if (p.k_split && --first_seg == 0) {
-      const uint16_t *b0 = (kBKc ? p.B2 + static_cast<int64_t>(n0) * p.ldb2 : p.B2 + n0) + OpB::lane_src(wave, lane, p.ldb2);
-#pragma unroll
-      for (int i = 0; i < OpB::kLoads; ++i) srcB[i] = b0 + OpB::load_rows(i) * p.ldb2;
+    if (p.k_split && --first_seg == 0) {  // B continues in its second K segment
+      blockB = uniform64(reinterpret_cast<uint64_t>(kBKc ? p.B2 + static_cast<int64_t>(n0) * p.ldb2 : p.B2 + n0));
+      laneB = static_cast<uint32_t>(OpB::lane_src(wave, lane, p.ldb2) * 2);
+      ldb_cur = p.ldb2;
       stepB = OpB::block_stride(p.ldb2);
     }
   };
@@ -278,11 +289,18 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
       }
       // carried gather: in the block's first K step the address of the next piece is worked out; in the second,
       // just behind the barrier where every load has landed, the piece in registers goes out and the next comes in
-      if constexpr (kCopy && !kLoad && i == 40) copy_ptr = copy_src(copy_i + 1, &copy_next_v);
-      if constexpr (kCopy && kLoad && i == 0) store_global16(p.job.dst + copy_v, copy_data);
+      // (all three behind one uniform test: once the range is copied the remaining K blocks issue nothing for it)
+      if constexpr (kCopy && !kLoad && i == 40) {
+        if (copy_i + 1 < copy_pieces) copy_ptr = copy_src(copy_i + 1, &copy_next_v);
+      }
+      if constexpr (kCopy && kLoad && i == 0) {
+        if (copy_i < copy_pieces) store_global16(p.job.dst + copy_v, copy_data);
+      }
       if constexpr (kCopy && kLoad && i == 1) {
-        copy_data = load_global16(copy_ptr);
-        copy_v = copy_next_v;
+        if (copy_i + 1 < copy_pieces) {
+          copy_data = load_global16(copy_ptr);
+          copy_v = copy_next_v;
+        }
         ++copy_i;
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -311,7 +329,7 @@ void gemm_w4_kernel(GemmParams p, int tiles_m, int tiles_n) {
   wait_vmcnt<0>();  // surplus loads must have landed before the workgroup gives its LDS back
   if constexpr (kCopy) {
     // the piece still in registers, and whatever the K loop was too short for
-    store_global16(p.job.dst + copy_v, copy_data);
+    if (copy_i < copy_pieces) store_global16(p.job.dst + copy_v, copy_data);
     for (uint32_t i = copy_i + 1; i < copy_pieces; ++i) {
       uint32_t v;
       const uint4 *src = copy_src(i, &v);
