@@ -503,6 +503,7 @@ def main():
         # the same step captured into a HIP graph and replayed: what the eager step's launch gaps cost
         mg = graph_replay_ms(st, max(a.steps, 20), a.warmup)
         out["graph_replay"] = {"tflops": round(flops / (mg * 1e-3) / 1e12, 2), "median_ms_per_step": round(mg, 4)}
+        out["headline_steps_executed"] += a.warmup + max(a.steps, 20)   # the replays run the step's kernels too
 
     if not a.no_sweep and a.zdp_slices is None:
         # the gather kernel on its own: one slice of the first operator, back to back (achieved HBM rate of the copy)
