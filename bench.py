@@ -251,6 +251,9 @@ def kernel_table(stats):
         if name == "gather_carried":   # gathers that ran inside GEMM launches: no time of their own
             out[name] = dict(launches=s["launches"], mb=round(s["bytes"] / 2 / 2 ** 20, 2))
             continue
+        if name == "gemm_persistent":  # GEMM launches (counted under their kinds) that ran as the persistent kernel
+            out[name] = dict(launches=s["launches"])
+            continue
         avg_ms = s["ms"] / s["launches"]
         e = dict(launches=s["launches"], avg_us=round(avg_ms * 1e3, 2), total_ms=round(s["ms"], 3))
         if s["flops"]:
@@ -270,7 +273,7 @@ def measure(st, flops, steps, warmup, serial, config=None):
     ms_prof, stats = st.run(n_prof, 2, serial=serial, profile=True)
     ov = stats["_overlap"]
     kernels = kernel_table(stats)
-    gemms = {k: v for k, v in kernels.items() if k.startswith("gemm")}
+    gemms = {k: v for k, v in kernels.items() if k.startswith("gemm") and "total_ms" in v}
     dom = max(gemms, key=lambda k: gemms[k]["total_ms"])
     roofline = {"bound": "mfma", "kernel": dom, "achieved": gemms[dom]["tflops"], "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(gemms[dom]["tflops"] / PEAK_BF16_TFLOPS, 4),
@@ -361,8 +364,8 @@ def plan_search(w, kernels, staging, rows, torch, osdp, steps, warmup):
     from the measured fixed cost of the smallest gather; the memory limit leaves room for half of the weights to be replicated.
     The chosen per-slice modes are then run through the mixed entry points and timed."""
     import workloads as wl
-    gemm_ms = sum(v["total_ms"] for k, v in kernels.items() if k.startswith("gemm"))
-    gemm_flops = sum(v["tflops"] * v["total_ms"] for k, v in kernels.items() if k.startswith("gemm")) * 1e9
+    gemm_ms = sum(v["total_ms"] for k, v in kernels.items() if k.startswith("gemm") and "total_ms" in v)
+    gemm_flops = sum(v["tflops"] * v["total_ms"] for k, v in kernels.items() if k.startswith("gemm") and "total_ms" in v) * 1e9
     flops_per_s = gemm_flops / (gemm_ms * 1e-3)
     gather = kernels.get("gather")
     beta = 1.0 / (gather["gbs_algorithmic"] * 1e9 / 2) if gather else 1.0 / 2e12   # seconds per byte gathered
@@ -549,7 +552,7 @@ def main():
                 mk = measure(st, fk, sub_steps, sub_warm, a.serial)
                 row[mname] = {key: mk[key] for key in ("tflops", "frac_bf16_mfma_peak", "median_ms_per_step", "peak_staging_mb",
                                                        "workspace_mb", "gathers", "idle_us_per_step")}
-                row[mname]["roofline_frac"] = {kk: vv.get("frac_mfma_peak") for kk, vv in mk["kernels"].items() if kk.startswith("gemm")}
+                row[mname]["roofline_frac"] = {kk: vv.get("frac_mfma_peak") for kk, vv in mk["kernels"].items() if kk.startswith("gemm") and "frac_mfma_peak" in vv}
             if k > 1:
                 del st
                 torch.cuda.empty_cache()

@@ -36,8 +36,9 @@ OSDP_KERNEL_GEMM_FWD = 1
 OSDP_KERNEL_GEMM_DW = 2
 OSDP_KERNEL_GEMM_DX = 3
 OSDP_KERNEL_GATHER_CARRIED = 4
-OSDP_KERNEL_KINDS = 5
-KERNEL_NAMES = ("gather", "gemm_fwd", "gemm_dw", "gemm_dx", "gather_carried")
+OSDP_KERNEL_GEMM_PERSISTENT = 5
+OSDP_KERNEL_KINDS = 6
+KERNEL_NAMES = ("gather", "gemm_fwd", "gemm_dw", "gemm_dx", "gather_carried", "gemm_persistent")
 
 EXPORTS = (
     "osdp_slice_range", "osdp_row_slice_range", "osdp_split_linear_gather_slice",

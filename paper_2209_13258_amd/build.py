@@ -11,7 +11,7 @@ ROOT = PKG.parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libosdp.so"
 SOURCES = ["osdp_api.hip", "osdp_gather.hip", "osdp_gemm.hip", "osdp_search.hip"]
-HEADERS = [CSRC / "osdp_internal.h", CSRC / "gemm_common.h", CSRC / "gemm_dma.h", CSRC / "gemm_w4.h", ROOT / "include" / "osdp.h"]
+HEADERS = [CSRC / "osdp_internal.h", CSRC / "gemm_common.h", CSRC / "gemm_dma.h", CSRC / "gemm_w4.h", CSRC / "gemm_w4p.h", ROOT / "include" / "osdp.h"]
 
 HIPCC_FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950", "-fvisibility=hidden",

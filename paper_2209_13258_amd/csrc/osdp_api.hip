@@ -506,6 +506,7 @@ struct Profile {
   std::vector<TimedLaunch> launches;
   std::vector<hipEvent_t> spare;  // timed events kept for reuse
   int64_t carried_launches = 0;   // gathers that ran inside a GEMM launch
+  int64_t persistent_launches = 0;  // GEMM launches that ran as the persistent kernel
   double carried_bytes = 0.0;
   // filled by osdp_profile_end for osdp_profile_overlap: [start, stop) of every timed launch in ms from the first event
   std::vector<std::pair<double, double>> gemm_iv, gather_iv;
@@ -589,10 +590,12 @@ hipError_t do_gemm(int kind, const GemmProblem &g, hipStream_t stream) {
   bool carried = false;
   GemmProblem q = g;
   q.carried = &carried;
+  const int64_t persistent_before = gemm_persistent_launches();
   hipError_t e = timed(kind, 2.0 * M * N * K, bytes, stream, [&] { return launch_gemm(q, stream); });
+  Profile &pf = t_profile;
+  if (pf.active) pf.persistent_launches += gemm_persistent_launches() - persistent_before;
   if (e != hipSuccess || !g.carry) return e;
   if (!carried) return gather_now(*g.carry, stream);
-  Profile &pf = t_profile;
   if (pf.active) {
     pf.carried_launches += 1;
     pf.carried_bytes += 4.0 * static_cast<double>(g.carry->rows) * static_cast<double>(g.carry->w);
@@ -739,7 +742,7 @@ const DebugSwitch kSwitches[] = {
     {"gemm_generic", &DebugOptions::gemm_generic, 0, 1}, {"tile", &DebugOptions::tile, -1, 3},
     {"deep", &DebugOptions::deep, -1, 1},                {"split_launch", &DebugOptions::split_launch, -1, 1},
     {"fwd_pair", &DebugOptions::fwd_pair, -1, 1},        {"poison_staging", &DebugOptions::poison_staging, 0, 1},
-    {"split_k", &DebugOptions::split_k, -1, 1},          {"four_wave", &DebugOptions::four_wave, -1, 1},      {"fused_gather", &DebugOptions::fused_gather, -1, 1},
+    {"persistent", &DebugOptions::persistent, -1, 1},    {"split_k", &DebugOptions::split_k, -1, 1},          {"four_wave", &DebugOptions::four_wave, -1, 1},      {"fused_gather", &DebugOptions::fused_gather, -1, 1},
 };
 }  // namespace
 
@@ -1262,6 +1265,7 @@ osdp_status osdp_profile_begin(int32_t max_launches) {
   }
   pf.launches.clear();
   pf.carried_launches = 0;
+  pf.persistent_launches = 0;
   pf.carried_bytes = 0.0;
   pf.max_launches = static_cast<size_t>(max_launches);
   pf.active = true;
@@ -1293,6 +1297,7 @@ osdp_status osdp_profile_end(osdp_kernel_stats *stats) {
   pf.launches.clear();
   stats[OSDP_KERNEL_GATHER_CARRIED].launches = pf.carried_launches;
   stats[OSDP_KERNEL_GATHER_CARRIED].bytes = pf.carried_bytes;
+  stats[OSDP_KERNEL_GEMM_PERSISTENT].launches = pf.persistent_launches;
   return OSDP_OK;
 }
 

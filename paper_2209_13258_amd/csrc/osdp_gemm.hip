@@ -13,6 +13,7 @@
 #include "gemm_common.h"
 #include "gemm_dma.h"
 #include "gemm_w4.h"
+#include "gemm_w4p.h"
 
 namespace osdp {
 
@@ -229,6 +230,24 @@ void combine_parts_kernel(GemmParams p, const float *parts, int n_parts) {
 }
 
 constexpr int kCUs = 256;
+
+thread_local int64_t t_persistent_launches = 0;
+
+// The persistent form of the four-wave kernel: one workgroup per CU walks through the tiles.
+template <bool kAK, bool kBK, int kEpi, bool kAccIn>
+hipError_t launch_w4p(const GemmParams &p, hipStream_t stream) {
+  constexpr size_t lds = 2 * (256 + 256) * 64 * sizeof(uint16_t);
+  auto kernel = gemm_w4p_kernel<kAK, kBK, kEpi, kAccIn>;
+  static bool configured[kMaxDevices] = {};
+  hipError_t e = allow_lds(kernel, lds, configured);
+  if (e != hipSuccess) return e;
+  const int tiles_m = p.M / 256, tiles_n = p.N / 256;
+  const int tiles = tiles_m * tiles_n;
+  hipLaunchKernelGGL(kernel, dim3(tiles < kCUs ? tiles : kCUs), dim3(256), lds, stream, p, tiles_m, tiles_n);
+  t_persistent_launches += 1;
+  return hipGetLastError();
+}
+
 constexpr int kShortK = 1024;
 constexpr int kW4MinK = 192;  // the four-wave kernel's K loop assumes at least three K blocks of 64
 constexpr int kW4MinKdW = 8192;
@@ -355,6 +374,12 @@ hipError_t launch_best(const GemmParams &p, hipStream_t stream, bool *carry) {
         // (dW, both operands MN-contiguous: twice the fragment-read instructions and a serial epilogue per wave;
         // measured through the library, the four-wave kernel is 4-9 % ahead from K = 8192 and 3 % behind at K = 4096)
         if (p.K / parts >= kW4MinK && fw != 0 && (fw == 1 || p.K >= (kind == 1 ? kW4MinKdW : kW4MinK))) {
+          // More tiles than CUs: the persistent form overlaps each tile's start-up with its predecessor's end
+          // (3-12 % per launch).  It takes no gather along: *carry stays as it is and the caller launches the
+          // gather by itself, which measured better on every workload than keeping the plain kernel for its sake.
+          if (debug_options().persistent.load(std::memory_order_relaxed) != 0 &&  // testing: 0 never
+              parts == 1 && static_cast<long>(p.M / 256) * (p.N / 256) > kCUs)
+            return launch_w4p<kAK, kBK, kEpi, kAccIn>(p, stream);
           if constexpr (!(kAK && kBK)) {  // dX launches read every staged slice there is: they never carry a gather
             if (*carry) {
               *carry = false;
@@ -516,6 +541,8 @@ double gemm_estimate_us(int64_t M, int64_t N, int64_t K, bool forward_parts) {
   const double rounds = static_cast<double>(static_cast<long>((tiles + kCUs - 1) / kCUs));
   return rounds * GBM * GBN * 5.0 * 2.0 * static_cast<double>(K) / 5.0e6 + 6.0;  // the checked kernel is about 5x slower per tile
 }
+
+int64_t gemm_persistent_launches() { return t_persistent_launches; }
 
 size_t gemm_forward_parts_bytes(int64_t M, int64_t N, int64_t K) {
   const int parts = forward_k_parts(M, K);

@@ -106,6 +106,9 @@ bool gemm_takes_two_column_segments(int64_t M, int64_t n_first, int64_t n_second
 // tokens meet a long reduction.
 double gemm_estimate_us(int64_t M, int64_t N, int64_t K, bool forward_parts = false);
 
+// Launches of the calling thread that ran as the persistent four-wave kernel so far (for the profile).
+int64_t gemm_persistent_launches();
+
 // Bytes of fp32 planes that launch_gemm needs in GemmProblem::parts for a forward product (A K-contiguous, B
 // N-contiguous, bf16 row-major result, no accumulator) of M x N x K; 0: that product is not split along K.  The
 // number of parts is a function of M and K alone.
@@ -129,6 +132,7 @@ struct DebugOptions {
   std::atomic<int32_t> fwd_pair{-1};       // 0: the forward never pairs staged slices; 1: whenever the kernel can
   std::atomic<int32_t> fused_gather{-1};   // 0: gathers always run as launches of their own (second stream where given)
   std::atomic<int32_t> four_wave{-1};      // 0: 256 x 256 tiles run on the eight-wave kernel; 1: on the four-wave kernel wherever it can
+  std::atomic<int32_t> persistent{-1};     // 0: launches of more 256 x 256 tiles than CUs keep the plain four-wave kernel instead of its persistent form
   std::atomic<int32_t> split_k{-1};        // 0: forward products are never split along K (changes the bits of those that are)
   std::atomic<int32_t> poison_staging{0};  // 1: staging slots hold NaN patterns whenever no gathered slice is live in them
 };

@@ -16,7 +16,7 @@ def H():
     return gpu_harness
 
 
-DEBUG_DEFAULTS = {"split_k": -1, "four_wave": -1, "fused_gather": -1, "gemm_generic": 0, "tile": -1, "deep": -1, "split_launch": -1, "fwd_pair": -1, "poison_staging": 0}
+DEBUG_DEFAULTS = {"persistent": -1, "split_k": -1, "four_wave": -1, "fused_gather": -1, "gemm_generic": 0, "tile": -1, "deep": -1, "split_launch": -1, "fwd_pair": -1, "poison_staging": 0}
 
 
 @pytest.fixture
@@ -753,6 +753,56 @@ def test_every_tile_shape_gives_the_bits_of_the_checked_kernel(H, oracle, T, I, 
             got = op.results()
             for name in ("Y", "dX", "dW"):
                 assert np.array_equal(got[name], ref[name]), f"{name} differs (tile {tile}, k {k}, dim {dim})"
+
+
+# ------------------------------------------------ the persistent form of the four-wave kernel
+@pytest.mark.parametrize("dim", [0, 1])
+def test_persistent_kernel_keeps_the_bits_of_one_tile_per_workgroup(H, oracle, debug, dim):
+    """A launch of more 256 x 256 tiles than CUs runs as one workgroup per CU that walks through the tiles, the loads
+    of a tile's first K blocks under way before the previous tile is stored.  272 and 289 tiles here: some
+    workgroups run two tiles and most one.  With three slices every variant runs: the plain product, the three stages
+    of a sum over slices (fp32 out, fp32 in and out, fp32 in), and dW into the shard-major layout.  Every bit must
+    be the one that the kernel of one tile per workgroup gives, and the values the oracle's."""
+    import paper_2209_13258_amd as osdp
+    T, N, k = 4352, 8, 3
+    I, O = (4352, 12288) if dim == 0 else (13056, 4096)
+    d = wl.small_case(191 + dim, T, I, O, N)
+    sc, sp = H.streams()
+
+    def run(mode):
+        plan = osdp.Plan([k], staging=mode, split_dim_per_op=[dim])
+        op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+        torch.cuda.synchronize()
+        osdp.osdp_profile_begin(1000)
+        with torch.cuda.stream(sc):
+            op.fwd(k, plan=plan, streams=(sc, sp))
+            op.bwd(k, plan=plan, streams=(sc, sp))
+        sc.synchronize()
+        return op.results(), osdp.osdp_profile_end()["gemm_persistent"]["launches"]
+
+    debug("tile", 0)           # (for 272 tiles the library would pick smaller tiles, or 256 large ones plus a remainder)
+    debug("four_wave", 1)      # (dW reduces over T = 4352, where the library would still pick the eight-wave kernel)
+    debug("persistent", 0)
+    _announce("persistent off", T, I, O, N, k, dim)
+    ref, n = run(osdp.OSDP_STAGING_SINGLE)
+    assert n == 0
+    g = np.random.default_rng(190 + dim)
+    _check_samples(H, oracle, "one tile per workgroup", d, ref, T, I, O, N, k, bool(dim), g, 20_000)
+    debug("persistent", -1)
+    for mode in (osdp.OSDP_STAGING_SINGLE, osdp.OSDP_STAGING_DOUBLE):
+        _announce("persistent on", T, I, O, N, k, dim, "staging", mode)
+        got, n = run(mode)
+        # SINGLE: a launch per slice for Y and for dX, and one for all of dW (which needs no weights); DOUBLE may
+        # pair slices into launches of two K segments, which keep the plain kernel
+        assert n == 7 if mode == osdp.OSDP_STAGING_SINGLE else n >= 3, f"{n} persistent launches"
+        for name in ("Y", "dX", "dW"):
+            assert np.array_equal(got[name], ref[name]), f"{name} differs (staging {mode})"
+    debug("tile", -1)
+    debug("four_wave", -1)
+    _announce("persistent on, library's own launch plan", T, I, O, N, k, dim)
+    got, n = run(osdp.OSDP_STAGING_DOUBLE)
+    for name in ("Y", "dX", "dW"):
+        assert np.array_equal(got[name], ref[name]), f"{name} differs (library's own launch plan)"
 
 
 # ------------------------------------------------ leading dimensions and many shards

@@ -29,11 +29,11 @@ def gemm_asm(tmp_path_factory):
     return out.read_text().split("\n")
 
 
-def _kernels(lines):
-    """{mangled name: list of instruction lines} for the four-wave kernels."""
+def _kernels(lines, kernel="gemm_w4_kernel"):
+    """{mangled name: list of instruction lines} for the instantiations of one kernel template."""
     kernels, cur = {}, None
     for line in lines:
-        m = re.match(r"^(_ZN4osdp\S*gemm_w4_kernel\S*):", line)
+        m = re.match(r"^(_ZN4osdp\S*" + kernel + r"I\S*):", line)
         if m:
             cur = m.group(1)
             kernels[cur] = []
@@ -58,3 +58,37 @@ def test_four_wave_kernels_keep_their_k_loop_free_of_scratch_and_accumulator_mov
             near = ins[max(0, i - 3):i]
             assert not [t for t in near if t.startswith(("v_accvgpr_write", "v_accvgpr_mov"))], \
                 f"{name}: an accumulator register is written right in front of an inline MFMA"
+
+
+def _vgprs(operand):
+    """The VGPR numbers an operand like v7 or v[8:11] names (empty for anything else)."""
+    m = re.fullmatch(r"v(\d+)", operand)
+    if m:
+        return {int(m.group(1))}
+    m = re.fullmatch(r"v\[(\d+):(\d+)\]", operand)
+    return set(range(int(m.group(1)), int(m.group(2)) + 1)) if m else set()
+
+
+def test_persistent_four_wave_kernels_use_no_scratch_and_respect_the_mfma_hazards(gemm_asm):
+    """The persistent form runs its epilogue and the start of the next tile inside the loop over K blocks, where the
+    compiler has no register to spare: any spill there, any accumulator moved by the compiler, or a source
+    register of an inline MFMA written by a VALU instruction just before it (two wait states are needed, and the
+    compiler pads none for an instruction it cannot see) is a defect."""
+    kernels = _kernels(gemm_asm, "gemm_w4p_kernel")
+    assert len(kernels) >= 10, "the persistent kernel's instantiations were not found in the assembly"
+    for name, ins in kernels.items():
+        assert not [t for t in ins if t.startswith("scratch_")], f"{name}: scratch traffic"
+        mfma = [i for i, t in enumerate(ins) if t.startswith("v_mfma")]
+        # one K block of 128, plus 64 that clear the accumulators before the first tile and 64 between tiles
+        # (instantiations that start from a stored partial sum load it instead)
+        assert len(mfma) in (128, 256), f"{name}: {len(mfma)} MFMAs"
+        for i in mfma:
+            near = ins[max(0, i - 3):i]
+            assert not [t for t in near if t.startswith(("v_accvgpr_write", "v_accvgpr_mov"))], \
+                f"{name}: an accumulator register is written right in front of an inline MFMA"
+            ops = [o.strip() for o in ins[i].split(None, 1)[1].split(",")]
+            srcs = _vgprs(ops[1]) | _vgprs(ops[2])
+            for t in ins[max(0, i - 2):i]:
+                if t.startswith("v_") and not t.startswith("v_mfma"):
+                    dst = t.split(None, 1)[1].split(",")[0].strip()
+                    assert not (_vgprs(dst) & srcs), f"{name}: '{t}' writes a source of the MFMA that follows it"
