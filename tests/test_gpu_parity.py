@@ -805,6 +805,54 @@ def test_persistent_kernel_keeps_the_bits_of_one_tile_per_workgroup(H, oracle, d
         assert np.array_equal(got[name], ref[name]), f"{name} differs (library's own launch plan)"
 
 
+@pytest.mark.parametrize("rows", [False, True])
+def test_persistent_kernel_reads_a_dp_and_a_gathered_slice_in_one_launch(H, oracle, debug, rows):
+    """Launches over a DP slice (read in its replica, row length of the whole weight) and a gathered neighbour (in a
+    staging slot, row length of the slice) hand the kernel two segments of B with different leading dimensions: by
+    tile column where the launch concatenates, switched in the middle of every tile's K loop where it sums.  In the
+    persistent form the switch happens on the load side, two K blocks ahead of the MFMAs and across tile
+    boundaries.  Same bits as the all-gathered plan on one tile per workgroup."""
+    import paper_2209_13258_amd as osdp
+    T, I, O, N, k = 4352, 4096, 8192, 8, 4
+    if rows:
+        I, O = O, I
+    dim = osdp.OSDP_SPLIT_IN_FEATURES if rows else osdp.OSDP_SPLIT_OUT_FEATURES
+    d = wl.small_case(193, T, I, O, N)
+    debug("tile", 0)
+    debug("four_wave", 1)
+    debug("persistent", 0)
+    base = H.Operator(d["X"], d["dY"], d["W_shards"], O)
+    plan0 = osdp.Plan([k], split_dim_per_op=[dim])
+    base.fwd(k, plan=plan0)
+    base.bwd(k, plan=plan0)
+    ref = base.results()
+    g = np.random.default_rng(193)
+    _check_samples(H, oracle, "all gathered, one tile per workgroup", d, ref, T, I, O, N, k, rows, g, 10_000)
+    debug("persistent", -1)
+    debug("fwd_pair", 1)
+    W = np.concatenate(d["W_shards"])[: I * O].reshape(I, O)
+    rng = [(oracle.row_slice_range(I, k, j) if rows else oracle.slice_range(O, k, j)) for j in range(k)]
+    for mask in (0b1010, 0b0110):
+        _announce("persistent, DP and gathered slices", bin(mask), "rows" if rows else "cols")
+        w_dp = [None if (mask >> j) & 1 else (W, a * O if rows else a) for j, (a, b) in enumerate(rng)]
+        dev = _MixedDevice(H, d, d["W_shards"], w_dp, O, rng, I, O, rows, W)
+        sc, sp = H.streams()
+        torch.cuda.synchronize()
+        osdp.osdp_profile_begin(1000)
+        with torch.cuda.stream(sc):
+            dev.run(k, osdp.Plan([k], staging=osdp.OSDP_STAGING_DOUBLE, zdp_mask=[mask], split_dim_per_op=[dim]), streams=(sc, sp))
+        sc.synchronize()
+        st = osdp.osdp_profile_end()
+        n = st["gemm_persistent"]["launches"]
+        # two launches over two slices each for Y and for dX, all of them persistent (dW: as the estimate cuts it)
+        assert st["gemm_fwd"]["launches"] == 2 and st["gemm_dx"]["launches"] == 2 and n >= 4, \
+            f"{st['gemm_fwd']['launches']} forward, {st['gemm_dx']['launches']} dX, {n} persistent launches"
+        got, dW, _, _ = dev.gradient(H, I, O, mask)
+        assert np.array_equal(got["Y"], ref["Y"]), f"Y differs (mask {mask:04b})"
+        assert np.array_equal(got["dX"], ref["dX"]), f"dX differs (mask {mask:04b})"
+        assert np.array_equal(dW, ref["dW"]), f"dW differs (mask {mask:04b})"
+
+
 # ------------------------------------------------ leading dimensions and many shards
 @pytest.mark.parametrize("T,I,O,N,k,dim", [(256, 256, 512, 4, 2, 0),     # unchecked kernels
                                             (77, 136, 200, 1, 1, 0),     # checked kernel
