@@ -406,8 +406,9 @@ OSDP_API osdp_status osdp_plan_search(const osdp_operator_cost *ops, int32_t n, 
  *                            changes result bits: those of the products that are otherwise summed in parts)
  *   "four_wave"     -1 .. 1  0: 256x256 tiles always run on the eight-wave kernel; 1: on the four-wave kernel
  *                            whenever it takes the launch (K >= 192), also where the eight-wave one measured faster
- *   "persistent"    -1 | 0   0: a launch of more 256x256 tiles than CUs keeps the four-wave kernel of one tile per
- *                            workgroup; otherwise one workgroup per CU walks through the tiles
+ *   "persistent"    -1 .. 1  0: a launch of more 256x256 tiles than CUs keeps the four-wave kernel of one tile per
+ *                            workgroup; otherwise one workgroup per CU walks through the tiles; 1: the walking
+ *                            form also for launches of fewer tiles
  *   "fused_gather"  -1 | 0   0: every gather is a launch of its own (on stream_copy where the pipeline overlaps);
  *                            otherwise a GEMM launch takes the next slice's gather along wherever it can
  *   "fwd_pair"      -1 .. 1  0: the forward never runs two staged slices in one launch; 1: whenever it can

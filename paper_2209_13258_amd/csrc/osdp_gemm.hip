@@ -377,8 +377,8 @@ hipError_t launch_best(const GemmParams &p, hipStream_t stream, bool *carry) {
           // More tiles than CUs: the persistent form overlaps each tile's start-up with its predecessor's end
           // (3-12 % per launch).  It takes no gather along: *carry stays as it is and the caller launches the
           // gather by itself, which measured better on every workload than keeping the plain kernel for its sake.
-          if (debug_options().persistent.load(std::memory_order_relaxed) != 0 &&  // testing: 0 never
-              parts == 1 && static_cast<long>(p.M / 256) * (p.N / 256) > kCUs)
+          const int pst = debug_options().persistent.load(std::memory_order_relaxed);  // testing: 0 never, 1 for any number of tiles
+          if (pst != 0 && parts == 1 && (pst == 1 || static_cast<long>(p.M / 256) * (p.N / 256) > kCUs))
             return launch_w4p<kAK, kBK, kEpi, kAccIn>(p, stream);
           if constexpr (!(kAK && kBK)) {  // dX launches read every staged slice there is: they never carry a gather
             if (*carry) {

@@ -132,7 +132,7 @@ struct DebugOptions {
   std::atomic<int32_t> fwd_pair{-1};       // 0: the forward never pairs staged slices; 1: whenever the kernel can
   std::atomic<int32_t> fused_gather{-1};   // 0: gathers always run as launches of their own (second stream where given)
   std::atomic<int32_t> four_wave{-1};      // 0: 256 x 256 tiles run on the eight-wave kernel; 1: on the four-wave kernel wherever it can
-  std::atomic<int32_t> persistent{-1};     // 0: launches of more 256 x 256 tiles than CUs keep the plain four-wave kernel instead of its persistent form
+  std::atomic<int32_t> persistent{-1};     // 0: launches of more 256 x 256 tiles than CUs keep the plain four-wave kernel instead of its persistent form; 1: the persistent form for any number of tiles
   std::atomic<int32_t> split_k{-1};        // 0: forward products are never split along K (changes the bits of those that are)
   std::atomic<int32_t> poison_staging{0};  // 1: staging slots hold NaN patterns whenever no gathered slice is live in them
 };

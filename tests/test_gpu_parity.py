@@ -715,7 +715,8 @@ def test_config2_one_of_four_slices_zdp(H, oracle, rows):
 
 
 # ------------------------------------------------ every tile shape of the unchecked kernel
-@pytest.mark.parametrize("T,I,O,N", [(512, 512, 768, 4), (256, 1024, 256, 8)])
+@pytest.mark.parametrize("T,I,O,N", [(512, 512, 768, 4), (256, 1024, 256, 8),
+                                     (256, 192, 512, 4)])   # forward K = 192: the four-wave kernels' shortest K loop (3 blocks)
 def test_every_tile_shape_gives_the_bits_of_the_checked_kernel(H, oracle, T, I, O, N, debug):
     """The host picks tile shapes by cost, so a test shape may never meet some of them: each of the four
     (with its own K block, LDS stage count and launch bounds per operand layout and pipeline depth) is forced in turn, for
@@ -735,12 +736,15 @@ def test_every_tile_shape_gives_the_bits_of_the_checked_kernel(H, oracle, T, I, 
     sc, sp = H.streams()
     # these shapes give every launch at most one tile per CU, where the library would use its deep-pipeline
     # variants of tiles 1..3 only: both pipelines of each tile are forced in turn
-    # (tile 0 twice: on the eight-wave kernel, and on the four-wave kernel also where the library would not pick it)
-    for tile, deep, four_wave in (("0", "1", 0), ("0", "1", 1), ("1", "0", -1), ("1", "1", -1), ("2", "0", -1), ("2", "1", -1),
-                                  ("3", "0", -1), ("3", "1", -1)):
+    # (tile 0 three times: on the eight-wave kernel, on the four-wave kernel also where the library would not pick it,
+    # and on the four-wave kernel's persistent form, here with fewer workgroups than CUs and one tile each)
+    for tile, deep, four_wave, persistent in (("0", "1", 0, -1), ("0", "1", 1, -1), ("0", "1", 1, 1), ("1", "0", -1, -1),
+                                              ("1", "1", -1, -1), ("2", "0", -1, -1), ("2", "1", -1, -1),
+                                              ("3", "0", -1, -1), ("3", "1", -1, -1)):
         debug("tile", tile)
         debug("deep", deep)
         debug("four_wave", four_wave)
+        debug("persistent", persistent)
         for k, dim in ((1, 0), (2, 0), (2, 1)):
             _announce("tile", tile, "deep", deep, T, I, O, N, "k", k, "dim", dim)
             plan = osdp.Plan([k], staging=osdp.OSDP_STAGING_DOUBLE, split_dim_per_op=[dim])
