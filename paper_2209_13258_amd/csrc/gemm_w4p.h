@@ -11,8 +11,8 @@
 // acknowledgement, about half a microsecond per tile.)
 //
 // Same tiles in the same order per XCD, same MFMA sequence per output element as every other GEMM kernel of the
-// library: same bits.  Takes what the plain kernel takes except parts of the reduction and a carried gather:
-// M % 256 == 0, N % 256 == 0 (n_split % 256 == 0), K % 64 == 0 (k_split % 64 == 0), K >= 192.
+// library: same bits.  Takes what the plain kernel takes except a carried gather: M % 256 == 0, N % 256 == 0
+// (n_split % 256 == 0), K % 64 == 0 (k_split % 64 == 0), K >= 192 (per part, when the launch runs parts of the reduction).
 #pragma once
 #include "gemm_w4.h"
 
@@ -61,9 +61,13 @@ void gemm_w4p_kernel(GemmParams p, int tiles_m, int tiles_n) {
   const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
   const int l16 = lane & 15, q4 = lane >> 4;
-  const int tiles = tiles_m * tiles_n, G = gridDim.x;
+  // A launch split along K: the tiles of part 0 come first, then those of part 1, ...; each part runs its own range
+  // of k and stores its own fp32 plane (the planes lie one below the other in C).
+  const int parts = p.k_parts > 1 ? p.k_parts : 1;
+  const int part_tiles = tiles_m * tiles_n, tiles = part_tiles * parts, G = gridDim.x;
   const int first = logical_block();  // < tiles: the host launches at most one workgroup per tile
-  const int nb = p.K / 64;
+  const int part_k = p.K / parts;
+  const int nb = part_k / 64;
   const int my_tiles = (tiles - first + G - 1) / G;
 
   // ---- the load side: tile `lt`, its next block `lb`, the sources of that block ---------------------------
@@ -80,15 +84,17 @@ void gemm_w4p_kernel(GemmParams p, int tiles_m, int tiles_n) {
   const int seg_blocks = p.k_split / 64;  // K blocks of B's first segment when B has two (0: one segment)
   auto load_tile = [&](int t) {  // point the sources at block 0 of tile t
     int tm, tn;
-    tile_of_pid(t, tiles_m, tiles_n, &tm, &tn);
+    const int part = t / part_tiles;
+    tile_of_pid(t - part * part_tiles, tiles_m, tiles_n, &tm, &tn);
     const int m0 = tm * BM, n0 = tn * BN;
+    const int64_t k0 = static_cast<int64_t>(part) * part_k;
     n0l = n0;
     const bool second = p.n_split && n0 >= p.n_split;
     const uint16_t *baseB = second ? p.B2 : p.B;
     const int nB = second ? n0 - p.n_split : n0;
     ldb_cur = second ? p.ldb2 : p.ldb;
-    blockA = uniform64(reinterpret_cast<uint64_t>(kAK ? p.A + static_cast<int64_t>(m0) * p.lda : p.A + m0));
-    blockB = uniform64(reinterpret_cast<uint64_t>(kBKc ? baseB + static_cast<int64_t>(nB) * ldb_cur : baseB + nB));
+    blockA = uniform64(reinterpret_cast<uint64_t>(kAK ? p.A + static_cast<int64_t>(m0) * p.lda + k0 : p.A + m0 + k0 * p.lda));
+    blockB = uniform64(reinterpret_cast<uint64_t>(kBKc ? baseB + static_cast<int64_t>(nB) * ldb_cur + k0 : baseB + nB + k0 * ldb_cur));
     laneB = static_cast<uint32_t>(OpB::lane_src(wave, lane, ldb_cur) * 2);
     stepB = OpB::block_stride(ldb_cur);
   };
@@ -142,8 +148,9 @@ void gemm_w4p_kernel(GemmParams p, int tiles_m, int tiles_n) {
   asm volatile("s_nop 1" : "+v"(zero));
   auto begin_tile = [&](int t, int l16e, int q4e) {
     int tm, tn;
-    tile_of_pid(t, tiles_m, tiles_n, &tm, &tn);
-    m0c = tm * BM;
+    const int part = t / part_tiles;
+    tile_of_pid(t - part * part_tiles, tiles_m, tiles_n, &tm, &tn);
+    m0c = tm * BM + part * p.M;  // (row of C: the part's plane starts at row part * M)
     n0c = tn * BN;
     static_for<MB * NB>([&](auto idx) {
       constexpr int i = decltype(idx)::value, bn = i / MB, bm = i % MB;  // the order of the K loop's steps

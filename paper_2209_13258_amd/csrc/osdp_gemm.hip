@@ -242,7 +242,7 @@ hipError_t launch_w4p(const GemmParams &p, hipStream_t stream) {
   hipError_t e = allow_lds(kernel, lds, configured);
   if (e != hipSuccess) return e;
   const int tiles_m = p.M / 256, tiles_n = p.N / 256;
-  const int tiles = tiles_m * tiles_n;
+  const int tiles = tiles_m * tiles_n * (p.k_parts > 1 ? p.k_parts : 1);
   hipLaunchKernelGGL(kernel, dim3(tiles < kCUs ? tiles : kCUs), dim3(256), lds, stream, p, tiles_m, tiles_n);
   t_persistent_launches += 1;
   return hipGetLastError();
@@ -378,7 +378,8 @@ hipError_t launch_best(const GemmParams &p, hipStream_t stream, bool *carry) {
           // (3-12 % per launch).  It takes no gather along: *carry stays as it is and the caller launches the
           // gather by itself, which measured better on every workload than keeping the plain kernel for its sake.
           const int pst = debug_options().persistent.load(std::memory_order_relaxed);  // testing: 0 never, 1 for any number of tiles
-          if (pst != 0 && parts == 1 && (pst == 1 || static_cast<long>(p.M / 256) * (p.N / 256) > kCUs))
+          if (pst != 0 && !(parts > 1 && (p.k_split || kAccIn)) &&
+              (pst == 1 || static_cast<long>(p.M / 256) * (p.N / 256) * parts > kCUs))
             return launch_w4p<kAK, kBK, kEpi, kAccIn>(p, stream);
           if constexpr (!(kAK && kBK)) {  // dX launches read every staged slice there is: they never carry a gather
             if (*carry) {

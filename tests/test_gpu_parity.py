@@ -1215,7 +1215,8 @@ def test_forward_parts_of_a_long_reduction_keep_the_bits_for_every_k_and_kernel(
     assert not np.array_equal(base, one_part)   # the parts are really summed separately
     sc, sp = H.streams()
     fast = T % 128 == 0 and O % 128 == 0
-    settings = [dict()] + ([dict(tile=t, four_wave=f) for t, f in ((0, 0), (0, 1), (1, -1), (2, -1), (3, -1))] if fast else []) \
+    settings = [dict()] + ([dict(tile=t, four_wave=f) for t, f in ((0, 0), (0, 1), (1, -1), (2, -1), (3, -1))] +
+                           [dict(tile=0, four_wave=1, persistent=1)] if fast else []) \
         + [dict(gemm_generic=1)]
     for setting in settings:
         for name, value in setting.items():
@@ -1328,7 +1329,8 @@ def test_dx_parts_of_a_long_reduction_keep_the_bits_for_every_k_and_kernel(H, or
     H.assert_close("dX (one part)", one_part, want["dX"])
     assert not np.array_equal(base, one_part)
     fast = T % 128 == 0 and I % 128 == 0
-    settings = [dict()] + ([dict(tile=t, four_wave=f) for t, f in ((0, 0), (0, 1), (3, -1))] if fast else []) + [dict(gemm_generic=1)]
+    settings = [dict()] + ([dict(tile=t, four_wave=f) for t, f in ((0, 0), (0, 1), (3, -1))] +
+                           [dict(tile=0, four_wave=1, persistent=1)] if fast else []) + [dict(gemm_generic=1)]
     for setting in settings:
         for name, value in setting.items():
             debug(name, value)
