@@ -8,7 +8,7 @@
 // MFMA of the current one; between the two tiles stand only the stores of the finished tile and the reset of the
 // accumulators.  (The stores of tile t are older than the loads of block 2 of tile t+1 in the wave's memory
 // counter, which counts loads and stores together and in order: the wait for that block also waits for their
-// acknowledgement, about half a microsecond per tile.)
+// acknowledgement.)
 //
 // Same tiles in the same order per XCD, same MFMA sequence per output element as every other GEMM kernel of the
 // library: same bits.  Takes what the plain kernel takes except a carried gather: M % 256 == 0, N % 256 == 0
