@@ -575,6 +575,13 @@ def main():
                 m2 = measure(st, fk, sub_steps, sub_warm, False)
                 osdp.osdp_debug_option("fused_gather", -1 if a.gathers == "carried" else 0)
                 row["double_gathers_launched_two_streams"] = {key: m2[key] for key in ("tflops", "median_ms_per_step", "gathers", "idle_us_per_step")}
+                # the same stack with the persistent form of the four-wave kernel switched off (one tile per workgroup)
+                osdp.osdp_debug_option("persistent", 0)
+                m3 = per_step_times(st, sub_steps, sub_warm, a.serial)[0]
+                osdp.osdp_debug_option("persistent", -1)
+                m4 = per_step_times(st, sub_steps, sub_warm, a.serial)[0]
+                row["double_one_tile_per_workgroup"] = {"tflops": round(fk / (m3 * 1e-3) / 1e12, 2), "median_ms_per_step": round(m3, 4),
+                                                        "persistent_again_tflops": round(fk / (m4 * 1e-3) / 1e12, 2)}
             sweep[str(k)] = row
         if "1" in sweep:   # time(k) / time(unsplit): what splitting costs, overlap and all
             t1 = sweep["1"]["single"]["median_ms_per_step"]
