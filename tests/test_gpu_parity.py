@@ -901,13 +901,14 @@ def test_padded_leading_dimensions_and_many_shards(H, oracle, T, I, O, N, k, dim
 
 
 # ------------------------------------------------ capture into a HIP graph
-@pytest.mark.parametrize("pair", ["0", "1"])
-def test_calls_can_be_captured_into_a_graph_and_replayed(H, pair, debug):
+@pytest.mark.parametrize("pair,persistent", [("0", -1), ("1", -1), ("1", 1)])
+def test_calls_can_be_captured_into_a_graph_and_replayed(H, pair, persistent, debug):
     """A forward + backward captured on the compute stream (one-stream and two-stream pipelines, the latter with
     its cross-stream events inside the capture) replays to the bits of the eager calls, every time, with eager work
     and new inputs between the replays."""
     import paper_2209_13258_amd as osdp
     debug("fwd_pair", pair)   # "0": the forward overlaps gathers on the copy stream; "1": one stream
+    debug("persistent", persistent)   # 1: the four-wave launches of this small shape run in their persistent form too
     T, I, O, N, k = 512, 2048, 4096, 8, 2       # 8 MB slices: the backward uses the copy stream too
     d = wl.small_case(91, T, I, O, N)
     op = H.Operator(d["X"], d["dY"], d["W_shards"], O)
@@ -935,7 +936,7 @@ def test_calls_can_be_captured_into_a_graph_and_replayed(H, pair, debug):
     g = torch.Generator(device="cuda")
     g.manual_seed(92)
     for rep in range(3):
-        _announce("graph replay", pair, rep)
+        _announce("graph replay", pair, persistent, rep)
         poison()
         graph.replay()
         torch.cuda.synchronize()
