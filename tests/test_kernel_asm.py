@@ -46,6 +46,27 @@ def _kernels(lines, kernel="gemm_w4_kernel"):
     return kernels
 
 
+def _vgprs(operand):
+    """The VGPR numbers an operand like v7 or v[8:11] names (empty for anything else)."""
+    m = re.fullmatch(r"v(\d+)", operand)
+    if m:
+        return {int(m.group(1))}
+    m = re.fullmatch(r"v\[(\d+):(\d+)\]", operand)
+    return set(range(int(m.group(1)), int(m.group(2)) + 1)) if m else set()
+
+
+def _assert_no_valu_write_in_front_of_its_mfma(name, ins, mfma):
+    """An MFMA may not read a register in the two cycles after a VALU instruction wrote it; the compiler pads none
+    for an MFMA it cannot see."""
+    for i in mfma:
+        ops = [o.strip() for o in ins[i].split(None, 1)[1].split(",")]
+        srcs = _vgprs(ops[1]) | _vgprs(ops[2])
+        for t in ins[max(0, i - 2):i]:
+            if t.startswith("v_") and not t.startswith("v_mfma"):
+                dst = t.split(None, 1)[1].split(",")[0].strip()
+                assert not (_vgprs(dst) & srcs), f"{name}: '{t}' writes a source of the MFMA that follows it"
+
+
 def test_four_wave_kernels_keep_their_k_loop_free_of_scratch_and_accumulator_moves(gemm_asm):
     kernels = _kernels(gemm_asm)
     assert len(kernels) >= 12, "the four-wave kernel's instantiations were not found in the assembly"
@@ -58,15 +79,7 @@ def test_four_wave_kernels_keep_their_k_loop_free_of_scratch_and_accumulator_mov
             near = ins[max(0, i - 3):i]
             assert not [t for t in near if t.startswith(("v_accvgpr_write", "v_accvgpr_mov"))], \
                 f"{name}: an accumulator register is written right in front of an inline MFMA"
-
-
-def _vgprs(operand):
-    """The VGPR numbers an operand like v7 or v[8:11] names (empty for anything else)."""
-    m = re.fullmatch(r"v(\d+)", operand)
-    if m:
-        return {int(m.group(1))}
-    m = re.fullmatch(r"v\[(\d+):(\d+)\]", operand)
-    return set(range(int(m.group(1)), int(m.group(2)) + 1)) if m else set()
+        _assert_no_valu_write_in_front_of_its_mfma(name, ins, mfma)
 
 
 def test_persistent_four_wave_kernels_use_no_scratch_and_respect_the_mfma_hazards(gemm_asm):
@@ -86,9 +99,4 @@ def test_persistent_four_wave_kernels_use_no_scratch_and_respect_the_mfma_hazard
             near = ins[max(0, i - 3):i]
             assert not [t for t in near if t.startswith(("v_accvgpr_write", "v_accvgpr_mov"))], \
                 f"{name}: an accumulator register is written right in front of an inline MFMA"
-            ops = [o.strip() for o in ins[i].split(None, 1)[1].split(",")]
-            srcs = _vgprs(ops[1]) | _vgprs(ops[2])
-            for t in ins[max(0, i - 2):i]:
-                if t.startswith("v_") and not t.startswith("v_mfma"):
-                    dst = t.split(None, 1)[1].split(",")[0].strip()
-                    assert not (_vgprs(dst) & srcs), f"{name}: '{t}' writes a source of the MFMA that follows it"
+        _assert_no_valu_write_in_front_of_its_mfma(name, ins, mfma)
