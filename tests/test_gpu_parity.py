@@ -809,6 +809,35 @@ def test_persistent_kernel_keeps_the_bits_of_one_tile_per_workgroup(H, oracle, d
         assert np.array_equal(got[name], ref[name]), f"{name} differs (library's own launch plan)"
 
 
+@pytest.mark.parametrize("I", [192, 256, 320])
+def test_persistent_kernel_with_tiles_of_three_to_five_k_blocks(H, oracle, debug, I):
+    """The loads run two K blocks ahead of the MFMAs: with three to five blocks per tile they are in the next tile
+    most of the time, and the 16 workgroups that run two tiles cross a tile boundary in the prologue's shadow.
+    Forward only (272 tiles of 256 x 256 with K = I), against the oracle element by element and bit for bit against
+    one tile per workgroup."""
+    import paper_2209_13258_amd as osdp
+    T, O, N = 4352, 4096, 8
+    d = wl.small_case(195, T, I, O, N)
+    want = oracle.linear(d["X"], d["W_shards"], O, want=("Y",))
+    debug("tile", 0)
+    got = {}
+    for persistent in (0, -1):
+        debug("persistent", persistent)
+        _announce("short K", T, I, O, "persistent", persistent)
+        op = H.Operator(d["X"], None, d["W_shards"], O)
+        sc, sp = H.streams()
+        torch.cuda.synchronize()
+        osdp.osdp_profile_begin(100)
+        with torch.cuda.stream(sc):
+            op.fwd(1, streams=(sc, sp))
+        sc.synchronize()
+        n = osdp.osdp_profile_end()["gemm_persistent"]["launches"]
+        assert n == (1 if persistent else 0)
+        got[persistent] = H.to_bits(op.Y)
+        H.assert_close(f"Y (persistent {persistent})", got[persistent], want["Y"])
+    assert np.array_equal(got[0], got[-1])
+
+
 @pytest.mark.parametrize("rows", [False, True])
 def test_persistent_kernel_reads_a_dp_and_a_gathered_slice_in_one_launch(H, oracle, debug, rows):
     """Launches over a DP slice (read in its replica, row length of the whole weight) and a gathered neighbour (in a
