@@ -299,7 +299,8 @@ def test_argument_errors_are_raised_before_anything_is_enqueued():
 def test_debug_options_take_known_names_and_values_only():
     for name, good, bad in (("gemm_generic", (0, 1, 0), (-1, 2)), ("tile", (0, 3, -1), (-2, 4)), ("deep", (0, -1), (2,)),
                             ("split_launch", (0, -1), (-2,)), ("fwd_pair", (0, 1, -1), (2,)),
-                            ("poison_staging", (1, 0), (-1, 2))):
+                            ("poison_staging", (1, 0), (-1, 2)), ("persistent", (0, 1, -1), (-2, 2)),
+                            ("four_wave", (0, 1, -1), (2,)), ("fused_gather", (0, -1), (-2,)), ("split_k", (0, -1), (-2,))):
         for v in good:   # the last good value is the default: the switches are process-wide
             osdp.osdp_debug_option(name, v)
         for v in bad:
